@@ -1,0 +1,141 @@
+/*
+ * dropit.h -- C ABI of the MI355X (gfx950) DropIT hot path.
+ *
+ * Two operations of "DropIT: Dropping Intermediate Tensors for Memory-Efficient
+ * DNN Training" (arXiv 2202.13808):
+ *
+ *   forward  : a^ = D(a) = {a_Xr, Xr}   min-k dropping of a layer's cached
+ *              input (Sec. 3.2; Sec. 3.3 "Min-K Elements"; Sec. 4.1
+ *              "Implementation Details")                    -> dropit_compress
+ *   backward : grad(theta) ~= grad(z) * dl(R(a^), theta)/dtheta, the weight
+ *              gradient taken on the zero-filled recovered tensor R(a^)
+ *              (Sec. 3.2, Eq. conv_backward_elem / Eq. fc_backward_elem_save)
+ *                                                           -> dropit_weight_grad
+ *
+ * General conventions
+ *   - Every pointer named x, vals, idx, dY, dW, workspace is a DEVICE pointer
+ *     owned by the caller.  The library allocates nothing, frees nothing and
+ *     keeps no state between calls.  `shape` / `x_shape` / `conv` are HOST
+ *     pointers read during the call only.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).  No call synchronises the host or copies
+ *     device memory to the host: the output length k is a host-side function
+ *     of (numel, gamma), see dropit_keep_count.
+ *   - Tensors are contiguous row-major; a "flat index" is the 0-based
+ *     row-major element offset, stored as int32 (App. A.7 assumes int32
+ *     indices), hence numel <= 2^31 - 1.
+ *   - bf16 data are raw 16-bit patterns (top half of an IEEE fp32).
+ *   - Arguments are validated before any HIP call; errors are returned as
+ *     status codes, nothing aborts.  Results are bit-reproducible run to run.
+ *   - Concurrent calls must use distinct workspaces.
+ */
+#ifndef DROPIT_H
+#define DROPIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DROPIT_F32 = 0, DROPIT_BF16 = 1 } dropit_dtype;
+
+typedef enum {
+    DROPIT_OK = 0,
+    DROPIT_EINVAL = 1,        /* null / misaligned pointer, bad shape, gamma outside [0,1], numel > 2^31-1 */
+    DROPIT_EWORKSPACE = 2,    /* workspace smaller than the matching *_workspace_bytes query */
+    DROPIT_EUNSUPPORTED = 3,  /* a convolution geometry that is not implemented */
+    DROPIT_EHIP = 4           /* a HIP launch failed */
+} dropit_status;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *dropit_status_string(dropit_status s);
+
+/*
+ * Number of retained elements for dropping rate gamma (Sec. 3.3: "drop the
+ * smallest gamma fraction"; Sec. 4.1: top-k "based on a proportion of
+ * 1 - gamma"):  k = floor((1 - gamma) * numel), evaluated in IEEE double as
+ * numel - ceil(gamma * numel).  gamma = 0 keeps everything (the baseline row of
+ * Table 2), gamma = 1 keeps nothing.
+ * Returns -1 if numel < 0, numel > 2^31-1, or gamma is NaN / outside [0,1].
+ */
+int64_t dropit_keep_count(int64_t numel, double gamma);
+
+/* Bytes of device workspace dropit_compress needs for a tensor of `numel`
+ * elements of type `dt` (0 on invalid arguments). */
+size_t dropit_compress_workspace_bytes(int64_t numel, dropit_dtype dt);
+
+/*
+ * Min-k dropping D(a) (Sec. 3.2, Sec. 3.3 "Min-K Elements", Sec. 4.1).
+ *
+ * Keeps the k = dropit_keep_count(numel, gamma) elements of x with the largest
+ * absolute magnitude, ranked over the whole tensor (one ranking per call, i.e.
+ * per mini-batch tensor).  Magnitude order is the unsigned order of the bit
+ * pattern with the sign bit cleared: -0 ties with +0, denormals are ordered
+ * exactly, inf ranks above all finite values and NaN above inf.  Elements that
+ * tie at the threshold magnitude are kept in order of lowest flat index.
+ *
+ *   x      [in]  device, contiguous row-major tensor of `shape` (ndim >= 1,
+ *                all dims >= 1), 16-byte aligned
+ *   shape  [in]  host, ndim extents
+ *   vals   [out] device, k elements of type dt: exact bit copies x[idx[j]]
+ *   idx    [out] device, k int32 flat indices, strictly ascending
+ *   workspace    device, 256-byte aligned, >= dropit_compress_workspace_bytes;
+ *                contents on entry are irrelevant, undefined on exit
+ *
+ * k == 0 writes nothing.  vals/idx may be NULL only if k == 0.
+ */
+dropit_status dropit_compress(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                              double gamma, void *vals, int32_t *idx,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Convolution geometry for dropit_weight_grad (cross-correlation, zero padding,
+ * 0-based: input row = out_row*stride_h - pad_h + u*dil_h). */
+typedef struct {
+    int64_t kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} dropit_conv2d;
+
+/* Bytes of device workspace dropit_weight_grad needs (0 on invalid or
+ * unsupported arguments).  Arguments as for dropit_weight_grad. */
+size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                          int64_t c_out, const dropit_conv2d *conv);
+
+/*
+ * Weight gradient from the sparsified cache (Sec. 3.2): the recover step R(a^)
+ * (zeros at dropped positions) followed by the ordinary dense weight gradient;
+ * the dense product is kept on purpose (Sec. 3.2: sparsity is used for
+ * storage only).
+ *
+ * conv == NULL, fully-connected layer (Eq. fc_backward_elem_save):
+ *     x_shape = [..., C_in]; all leading dims are tokens (N_tok = numel/C_in)
+ *     dY  [N_tok, c_out] row-major, type dt
+ *     dW  [c_out, C_in] row-major fp32:  dW[j][c] = sum_n dY[n][j] * R(a^)[n][c]
+ * conv != NULL, 2-d convolution (Eq. conv_backward_elem):
+ *     x_shape = [N, C, H, W] (NCHW);  dY [N, c_out, OH, OW] with
+ *     OH = (H + 2*pad_h - dil_h*(kh-1) - 1)/stride_h + 1 (OW alike), type dt
+ *     dW  [c_out, C, kh, kw] fp32:
+ *     dW[j][c][u][v] = sum_{n,oy,ox} dY[n][j][oy][ox] * R(a^)[n][c][oy*sh-ph+u*dh][ox*sw-pw+v*dw]
+ *     Only kh = kw = 3, stride 1, pad 1, dilation 1 is implemented; any other
+ *     geometry returns DROPIT_EUNSUPPORTED.
+ *
+ *   vals, idx [in]  device, the k pairs written by dropit_compress for a tensor
+ *                   of x_shape (idx strictly ascending, in range; not checked)
+ *   dY        [in]  device, 16-byte aligned
+ *   dW        [out] device fp32, 16-byte aligned, fully overwritten
+ *   workspace       device, 256-byte aligned, >= dropit_weight_grad_workspace_bytes
+ *
+ * bf16 inputs are multiplied exactly and accumulated in fp32; fp32 inputs use
+ * true fp32 multiply-adds.  k == 0 gives dW = 0.  The bias gradient does not
+ * depend on the cached input and is not computed here.
+ */
+dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k,
+                                 const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                 const void *dY, int64_t c_out, const dropit_conv2d *conv,
+                                 float *dW, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DROPIT_H */

@@ -1,0 +1,18 @@
+"""MI355X-native DropIT hot path: min-k compress + weight gradient from the sparse cache.
+
+The compute lives in ``libdropit.so`` (hand-written gfx950 HIP behind a C ABI,
+declared in ``include/dropit.h``).  This package is only the ctypes binding:
+argument marshalling from torch tensors (device memory + streams) to raw
+pointers.  There is no CPU fallback: without the built library, or without a
+GPU, the calls raise.
+"""
+from .binding import (  # noqa: F401
+    DropitError,
+    compress,
+    compress_workspace_bytes,
+    keep_count,
+    lib,
+    lib_path,
+    weight_grad,
+    weight_grad_workspace_bytes,
+)

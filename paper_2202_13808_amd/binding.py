@@ -1,0 +1,177 @@
+"""ctypes binding of the C ABI in ``include/dropit.h`` -- marshalling only.
+
+Every function here has the name of the C entry point without the ``dropit_``
+prefix and does nothing but turn torch tensors into pointers and sizes.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libdropit.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = range(5)
+
+
+class DropitError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(message)
+        self.status = status
+
+
+class Conv2d(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in
+                ("kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w")]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2202_13808_amd.build` "
+                "(there is no CPU fallback)" % _LIB_PATH)
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32, dbl, sz = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double,
+                                 ctypes.c_size_t)
+        p64 = ctypes.POINTER(ctypes.c_int64)
+        pconv = ctypes.POINTER(Conv2d)
+        L.dropit_status_string.restype = ctypes.c_char_p
+        L.dropit_status_string.argtypes = [i32]
+        L.dropit_keep_count.restype = i64
+        L.dropit_keep_count.argtypes = [i64, dbl]
+        L.dropit_compress_workspace_bytes.restype = sz
+        L.dropit_compress_workspace_bytes.argtypes = [i64, i32]
+        L.dropit_compress.restype = i32
+        L.dropit_compress.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp, sz, vp]
+        L.dropit_weight_grad_workspace_bytes.restype = sz
+        L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, pconv]
+        L.dropit_weight_grad.restype = i32
+        L.dropit_weight_grad.argtypes = [vp, vp, i64, p64, i32, i32, vp, i64, pconv, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise DropitError(status, lib().dropit_status_string(status).decode())
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise TypeError("dropit supports float32 and bfloat16 tensors, got %s" % t)
+
+
+def _shape_array(shape: Sequence[int]):
+    return (ctypes.c_int64 * len(shape))(*[int(s) for s in shape])
+
+
+def _conv_struct(conv) -> Optional[Conv2d]:
+    if conv is None:
+        return None
+    if isinstance(conv, Conv2d):
+        return conv
+    return Conv2d(*[int(v) for v in conv])
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _require_device(*tensors) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("dropit operates on device tensors only (no CPU path)")
+        if t is not None and not t.is_contiguous():
+            raise ValueError("dropit tensors must be contiguous")
+
+
+def keep_count(numel: int, gamma: float) -> int:
+    """dropit_keep_count: k = floor((1-gamma)*numel); -1 if the arguments are invalid."""
+    return int(lib().dropit_keep_count(int(numel), float(gamma)))
+
+
+def compress_workspace_bytes(numel: int, dtype: torch.dtype) -> int:
+    return int(lib().dropit_compress_workspace_bytes(int(numel), _dtype_code(dtype)))
+
+
+def compress(x: torch.Tensor, gamma: float, vals: Optional[torch.Tensor] = None,
+             idx: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+             stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """dropit_compress: returns (vals[k] of x.dtype, idx[k] int32).  Output and workspace
+    tensors are allocated with torch when not passed in."""
+    _require_device(x, vals, idx, workspace)
+    code = _dtype_code(x.dtype)
+    k = keep_count(x.numel(), gamma)
+    if k < 0:
+        _check(EINVAL)
+    if vals is None:
+        vals = torch.empty(k, dtype=x.dtype, device=x.device)
+    if idx is None:
+        idx = torch.empty(k, dtype=torch.int32, device=x.device)
+    if vals.numel() < k or idx.numel() < k or vals.dtype != x.dtype or idx.dtype != torch.int32:
+        raise ValueError("vals/idx must hold k=%d elements of %s / int32" % (k, x.dtype))
+    if workspace is None:
+        workspace = torch.empty(max(compress_workspace_bytes(x.numel(), x.dtype), 1),
+                                dtype=torch.uint8, device=x.device)
+    shape = _shape_array(x.shape)
+    with torch.cuda.device(x.device):
+        _check(lib().dropit_compress(x.data_ptr(), shape, x.dim(), code, float(gamma),
+                                     vals.data_ptr() if k else None, idx.data_ptr() if k else None,
+                                     workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return vals[:k], idx[:k]
+
+
+def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, c_out: int, conv=None) -> int:
+    cs = _conv_struct(conv)
+    return int(lib().dropit_weight_grad_workspace_bytes(
+        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(c_out),
+        ctypes.byref(cs) if cs is not None else None))
+
+
+def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], dY: torch.Tensor,
+                c_out: int, conv=None, dW: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """dropit_weight_grad: dW (fp32) from the (vals, idx) pair of a tensor of ``x_shape``.
+    ``conv`` is None for a fully-connected layer, else (kh, kw, stride_h, stride_w, pad_h,
+    pad_w, dil_h, dil_w)."""
+    _require_device(vals, idx, dY, dW, workspace)
+    code = _dtype_code(dY.dtype)
+    if vals.dtype != dY.dtype or idx.dtype != torch.int32:
+        raise ValueError("vals must have dY's dtype and idx must be int32")
+    cs = _conv_struct(conv)
+    x_shape = [int(s) for s in x_shape]
+    if dW is None:
+        if cs is None:
+            dw_shape = (int(c_out), x_shape[-1])
+        else:
+            dw_shape = (int(c_out), x_shape[1], cs.kh, cs.kw)
+        dW = torch.empty(dw_shape, dtype=torch.float32, device=dY.device)
+    if workspace is None:
+        workspace = torch.empty(max(weight_grad_workspace_bytes(x_shape, dY.dtype, c_out, cs), 1),
+                                dtype=torch.uint8, device=dY.device)
+    k = int(vals.numel())
+    with torch.cuda.device(dY.device):
+        _check(lib().dropit_weight_grad(
+            vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
+            _shape_array(x_shape), len(x_shape), code, dY.data_ptr(), int(c_out),
+            ctypes.byref(cs) if cs is not None else None, dW.data_ptr(),
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dW

@@ -1,0 +1,212 @@
+// Weight gradient from the sparsified cache (Sec. 3.2): recover R(a^) (zeros at
+// dropped positions) and take the ordinary dense weight gradient,
+//   FC   : dW[j][c]       = sum_n dY[n][j] * R(a^)[n][c]            (Eq. fc_backward_elem_save)
+//   conv : dW[j][c][u][v] = sum_{n,oy,ox} dY[n][j][oy][ox] * R(a^)[n][c][oy+u-1][ox+v-1]
+//                                                                   (Eq. conv_backward_elem, 3x3/s1/p1)
+//
+// This file holds the host entry points and the generic fp32-FMA kernels
+// (exact fp32 products, fixed summation order).  They serve fp32 inputs and
+// any bf16 shape the MFMA kernels do not cover.
+#include "common.hpp"
+#include <algorithm>
+
+namespace dropit {
+namespace {
+
+__device__ inline float to_f32(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+__device__ inline float to_f32(uint32_t b) { return __uint_as_float(b); }
+
+// ---- recover R(a^) into a dense buffer of the input type ------------------
+__global__ void __launch_bounds__(256) zero_kernel(uint4 *p, size_t n16)
+{
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (size_t i = blockIdx.x * size_t(blockDim.x) + threadIdx.x; i < n16; i += size_t(gridDim.x) * blockDim.x)
+        p[i] = z;
+}
+
+template <typename RAW>
+__global__ void __launch_bounds__(256) scatter_kernel(const RAW *__restrict__ vals, const int32_t *__restrict__ idx,
+                                                      int64_t k, int64_t numel, RAW *__restrict__ dense)
+{
+    for (int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; j < k; j += int64_t(gridDim.x) * blockDim.x) {
+        const int64_t i = idx[j];
+        if (i >= 0 && i < numel) dense[i] = vals[j];   // an out-of-range index is ignored, never written
+    }
+}
+
+// ---- FC: 64x64 output tile per workgroup, 4x4 per thread, fp32 FMA --------
+constexpr int FT = 64;      // tile edge
+constexpr int FK = 16;      // tokens per step
+
+template <typename RAW>
+__global__ void __launch_bounds__(256)
+fc_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int64_t ntok, int cin, int cout,
+              float *__restrict__ dW)
+{
+    __shared__ float sA[FK][FT + 4];   // dY tile  [token][j]
+    __shared__ float sB[FK][FT + 4];   // x^ tile  [token][c]
+    const int tid = threadIdx.x;
+    const int j0 = blockIdx.y * FT, c0 = blockIdx.x * FT;
+    const int tj = (tid / 16) * 4, tc = (tid % 16) * 4;
+    float acc[4][4] = {};
+    for (int64_t n0 = 0; n0 < ntok; n0 += FK) {
+        for (int e = tid; e < FK * FT; e += 256) {
+            const int r = e / FT, q = e % FT;
+            const int64_t n = n0 + r;
+            sA[r][q] = (n < ntok && j0 + q < cout) ? to_f32(dY[n * cout + j0 + q]) : 0.f;
+            sB[r][q] = (n < ntok && c0 + q < cin) ? to_f32(xhat[n * cin + c0 + q]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < FK; ++r) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = sA[r][tj + i]; b[i] = sB[r][tc + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[i][q] = __builtin_fmaf(a[i], b[q], acc[i][q]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (j0 + tj + i < cout && c0 + tc + q < cin)
+                dW[int64_t(j0 + tj + i) * cin + c0 + tc + q] = acc[i][q];
+}
+
+// ---- conv 3x3 / stride 1 / pad 1: one workgroup per (j, c), fixed-order reduce
+template <typename RAW>
+__global__ void __launch_bounds__(256)
+conv3x3_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int N, int C, int H, int W, int cout,
+                   float *__restrict__ dW)
+{
+    __shared__ float red[256][9];
+    const int j = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+    float acc[9] = {};
+    const int plane = H * W;
+    for (int n = 0; n < N; ++n) {
+        const RAW *xp = xhat + (int64_t(n) * C + c) * plane;
+        const RAW *gp = dY + (int64_t(n) * cout + j) * plane;
+        for (int p = tid; p < plane; p += 256) {
+            const int oy = p / W, ox = p % W;
+            const float g = to_f32(gp[p]);
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                const int iy = oy + u - 1;
+#pragma unroll
+                for (int v = 0; v < 3; ++v) {
+                    const int ix = ox + v - 1;
+                    if (iy >= 0 && iy < H && ix >= 0 && ix < W)
+                        acc[u * 3 + v] = __builtin_fmaf(g, to_f32(xp[iy * W + ix]), acc[u * 3 + v]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 9; ++i) red[tid][i] = acc[i];
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s)
+#pragma unroll
+            for (int i = 0; i < 9; ++i) red[tid][i] += red[tid + s][i];
+        __syncthreads();
+    }
+    if (tid < 9) dW[(int64_t(j) * C + c) * 9 + tid] = red[0][tid];
+}
+
+struct Problem {
+    bool conv;
+    int64_t numel, ntok, cin, cout;
+    int64_t N, C, H, W;
+};
+
+// Validates shape arguments; returns DROPIT_OK and fills `p`.
+dropit_status describe(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t c_out,
+                       const dropit_conv2d *conv, Problem &p)
+{
+    if (dt != DROPIT_F32 && dt != DROPIT_BF16) return DROPIT_EINVAL;
+    p.numel = checked_numel(x_shape, ndim);
+    if (p.numel < 1 || c_out < 1 || c_out > INT32_MAX) return DROPIT_EINVAL;
+    p.cout = c_out;
+    p.conv = conv != nullptr;
+    if (!p.conv) {
+        p.cin = x_shape[ndim - 1];
+        p.ntok = p.numel / p.cin;
+        if (p.ntok * c_out > int64_t(1) << 40) return DROPIT_EINVAL;
+        return DROPIT_OK;
+    }
+    if (ndim != 4) return DROPIT_EINVAL;
+    if (conv->kh < 1 || conv->kw < 1 || conv->stride_h < 1 || conv->stride_w < 1 || conv->pad_h < 0 ||
+        conv->pad_w < 0 || conv->dil_h < 1 || conv->dil_w < 1)
+        return DROPIT_EINVAL;
+    if (conv->kh != 3 || conv->kw != 3 || conv->stride_h != 1 || conv->stride_w != 1 || conv->pad_h != 1 ||
+        conv->pad_w != 1 || conv->dil_h != 1 || conv->dil_w != 1)
+        return DROPIT_EUNSUPPORTED;
+    p.N = x_shape[0]; p.C = x_shape[1]; p.H = x_shape[2]; p.W = x_shape[3];
+    if (p.N * c_out * p.H * p.W > INT32_MAX * int64_t(16)) return DROPIT_EINVAL;
+    return DROPIT_OK;
+}
+
+size_t dense_bytes(const Problem &p, dropit_dtype dt)
+{
+    return round_up(size_t(p.numel) * (dt == DROPIT_F32 ? 4 : 2), 256);
+}
+
+template <typename RAW>
+dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx, int64_t k, const void *dY,
+                          float *dW, char *ws, size_t dense_sz, hipStream_t stream)
+{
+    RAW *dense = reinterpret_cast<RAW *>(ws);
+    zero_kernel<<<1024, 256, 0, stream>>>(reinterpret_cast<uint4 *>(dense), dense_sz / 16);
+    if (k > 0) {
+        const int blocks = static_cast<int>(std::min<int64_t>((k + 255) / 256, 4096));
+        scatter_kernel<RAW><<<blocks, 256, 0, stream>>>(static_cast<const RAW *>(vals), idx, k, p.numel, dense);
+    }
+    if (!p.conv) {
+        const dim3 grid((p.cin + FT - 1) / FT, (p.cout + FT - 1) / FT);
+        fc_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), p.ntok, int(p.cin),
+                                                      int(p.cout), dW);
+    } else {
+        const dim3 grid(p.C, p.cout);
+        conv3x3_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), int(p.N), int(p.C),
+                                                           int(p.H), int(p.W), int(p.cout), dW);
+    }
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace dropit
+
+using namespace dropit;
+
+extern "C" size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                                     int64_t c_out, const dropit_conv2d *conv)
+{
+    Problem p;
+    if (describe(x_shape, ndim, dt, c_out, conv, p) != DROPIT_OK) return 0;
+    return dense_bytes(p, dt);
+}
+
+extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k,
+                                            const int64_t *x_shape, int ndim, dropit_dtype dt, const void *dY,
+                                            int64_t c_out, const dropit_conv2d *conv, float *dW, void *workspace,
+                                            size_t workspace_bytes, void *hip_stream)
+{
+    Problem p;
+    const dropit_status st = describe(x_shape, ndim, dt, c_out, conv, p);
+    if (st != DROPIT_OK) return st;
+    if (k < 0 || k > p.numel) return DROPIT_EINVAL;
+    if (k > 0 && (vals == nullptr || idx == nullptr)) return DROPIT_EINVAL;
+    if (k > 0 && (!aligned(vals, dt == DROPIT_F32 ? 4 : 2) || !aligned(idx, 4))) return DROPIT_EINVAL;
+    if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
+    if (workspace == nullptr || !aligned(workspace, 256)) return DROPIT_EINVAL;
+    const size_t need = dense_bytes(p, dt);
+    if (workspace_bytes < need) return DROPIT_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
+    return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);
+}

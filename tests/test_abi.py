@@ -1,0 +1,85 @@
+"""The C-ABI library loads, exports every symbol include/dropit.h declares, and rejects
+bad arguments before touching the GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2202_13808_amd as dropit
+from paper_2202_13808_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dropit.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dropit_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert declared_symbols() == sorted([
+        "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
+        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad"])
+
+
+def test_library_exports_every_declared_symbol():
+    L = dropit.lib()
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_keep_count_matches_the_stated_rule():
+    assert dropit.keep_count(16384, 0.9) == 1638
+    assert dropit.keep_count(9682944, 0.9) == 968294
+    assert dropit.keep_count(38731776, 0.9) == 3873177
+    assert dropit.keep_count(12582912, 0.9) == 1258291
+    assert dropit.keep_count(50331648, 0.9) == 5033164
+    assert dropit.keep_count(12845056, 0.8) == 2569011
+    assert dropit.keep_count(100, 0.9) == 10
+    assert dropit.keep_count(1000, 0.0) == 1000 and dropit.keep_count(1000, 1.0) == 0
+    for bad in (-0.5, 1.5, float("nan")):
+        assert dropit.keep_count(10, bad) == -1
+    assert dropit.keep_count(2**31, 0.5) == -1 and dropit.keep_count(-3, 0.5) == -1
+
+
+def test_status_strings():
+    L = dropit.lib()
+    for code in range(5):
+        assert L.dropit_status_string(code).decode().startswith("DROPIT_")
+
+
+def _shape(*dims):
+    return (ctypes.c_int64 * len(dims))(*dims)
+
+
+def test_compress_rejects_bad_arguments_without_a_gpu():
+    L = dropit.lib()
+    fake = ctypes.c_void_p(0x1000)           # never dereferenced: validation fails first
+    ws = ctypes.c_void_p(0x10000)
+    big = 1 << 30
+    call = L.dropit_compress
+    assert call(None, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, None, 2, binding.BF16, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 0, binding.BF16, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 0), 2, binding.BF16, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(1 << 20, 1 << 12), 2, binding.BF16, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, 7, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    for g in (-0.1, 1.1, float("nan")):
+        assert call(fake, _shape(4, 4), 2, binding.BF16, g, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(ctypes.c_void_p(0x1004), _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, None, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, None, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, None, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, ws, 16, None) == binding.EWORKSPACE
+    # gamma = 1 keeps nothing: legal, nothing launched, outputs may be NULL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 1.0, None, None, None, 0, None) == binding.OK
+
+
+def test_workspace_queries():
+    assert dropit.compress_workspace_bytes(16384, __import__("torch").float32) > 0
+    L = dropit.lib()
+    assert L.dropit_compress_workspace_bytes(0, binding.BF16) == 0
+    assert L.dropit_compress_workspace_bytes(1 << 31, binding.BF16) == 0
+    assert L.dropit_compress_workspace_bytes(100, 9) == 0

@@ -1,0 +1,109 @@
+"""GPU parity: dropit_compress (through the C ABI) vs the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_13808_amd as dropit
+from dropit_inputs import WORKLOADS, activation, f32_to_bf16_bits
+from gpu_util import to_device, to_host
+from test_oracle_select import check_selection_invariants
+
+pytestmark = pytest.mark.gpu
+
+
+def run_and_compare(x: np.ndarray, gamma: float, tag=""):
+    print("compress case", tag, x.dtype, x.shape, "gamma", gamma, flush=True)
+    k = oracle.keep_count(x.size, gamma)
+    assert dropit.keep_count(x.size, gamma) == k
+    xd = to_device(x)
+    vals, idx = dropit.compress(xd, gamma)
+    torch.cuda.synchronize()
+    v, i = to_host(vals), to_host(idx)
+    want_v, want_i = oracle.compress(x, k)
+    assert i.shape == (k,) and v.shape == (k,)
+    assert np.array_equal(i, want_i), tag
+    assert v.tobytes() == want_v.tobytes(), tag
+    return v, i
+
+
+def test_config1_tiny_fc():
+    w = WORKLOADS["tiny_fc"]
+    x = activation(w.x_shape, w.x_dist, w.x_seed, w.dtype)
+    v, i = run_and_compare(x, w.gamma, "tiny_fc")
+    assert i.size == 1638
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("numel", [1, 7, 8, 9, 4095, 4097, 300003, (1 << 20) + 5, 5000011])
+def test_sizes_and_ragged_tails(dtype, numel):
+    x = activation((numel,), "normal", 31 + numel % 1000, dtype)
+    for gamma in (0.9, 0.5):
+        run_and_compare(x, gamma, "ragged")
+
+
+@pytest.mark.parametrize("dist,dtype", [("normal", "bf16"), ("gelu", "bf16"), ("relu", "bf16"),
+                                        ("relu", "f32"), ("gelu", "f32")])
+@pytest.mark.parametrize("gamma", [0.0, 0.3, 0.8, 0.9, 0.999, 1.0])
+def test_distributions_and_gammas(dist, dtype, gamma):
+    x = activation((1237, 769), dist, 77, dtype)          # spans many tiles, odd row length
+    run_and_compare(x, gamma, dist)
+
+
+def _adversarial(n, rng):
+    special = rng.standard_normal(n).astype(np.float32)
+    special[::7] = np.inf
+    special[1::11] = -np.inf
+    special[2::13] = np.nan
+    special[3::17] = -np.float32(np.nan)
+    return {
+        "constant": np.full(n, -1.5, np.float32),
+        "zeros_mixed_sign": np.where(rng.random(n) < 0.5, np.float32(0.0), np.float32(-0.0)).astype(np.float32),
+        "two_level": np.where(rng.random(n) < 0.05, np.float32(-8.0), np.float32(0.25)).astype(np.float32),
+        "few_values": rng.integers(-3, 4, n).astype(np.float32),
+        "denormal": rng.integers(0, 64, n).astype(np.uint32).view(np.float32),
+        "inf_nan": special,
+        "ascending": np.arange(n, dtype=np.float32),
+        "descending": np.arange(n, 0, -1).astype(np.float32),
+    }
+
+
+@pytest.mark.parametrize("n", [1000, 70001])
+def test_adversarial_ties(n):
+    rng = np.random.default_rng(n)
+    for name, x in _adversarial(n, rng).items():
+        for xx in (x, f32_to_bf16_bits(x)):
+            for gamma in (0.0, 0.25, 0.5, 0.9, 0.97):
+                run_and_compare(xx, gamma, name)
+
+
+@pytest.mark.parametrize("name", ["vitb_fc1", "vitb_fc2", "vitdet_fc1", "vitdet_fc2", "resnet_conv3x3"])
+def test_full_size_configs(name):
+    w = WORKLOADS[name]
+    x = activation(w.x_shape, w.x_dist, w.x_seed, w.dtype)
+    v, i = run_and_compare(x, w.gamma, name)
+    check_selection_invariants(x, i.size, v, i)
+
+
+def test_deterministic_and_workspace_contents_irrelevant():
+    x = activation((3001, 257), "gelu", 5, "bf16")
+    xd = to_device(x)
+    ws = torch.empty(dropit.compress_workspace_bytes(x.size, xd.dtype), dtype=torch.uint8, device="cuda:0")
+    outs = []
+    for fill in (0, 255, 0x5A):
+        ws.fill_(fill)
+        vals, idx = dropit.compress(xd, 0.9, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append((to_host(vals).tobytes(), to_host(idx).tobytes()))
+    assert outs[0] == outs[1] == outs[2]
+
+
+def test_does_not_write_past_k():
+    x = activation((100000,), "normal", 9, "bf16")
+    xd = to_device(x)
+    k = dropit.keep_count(x.size, 0.9)
+    vals = torch.full((k + 64,), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.full((k + 64,), -5, dtype=torch.int32, device="cuda:0")
+    dropit.compress(xd, 0.9, vals=vals, idx=idx)
+    torch.cuda.synchronize()
+    assert torch.all(idx[k:] == -5) and torch.all(vals[k:] == 7.0)
