@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the DropIT hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input:
+dropit_compress (min-k drop of the cached layer input) followed by
+dropit_weight_grad (dW from the sparse cache), both through the C ABI.
+Workload at N=1: ViT-B/16 FC1 input, batch 64 (x bf16 [12608, 768], gamma 0.9,
+dY bf16 [12608, 3072]).  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is whole-step throughput in dense-equivalent
+dW TFLOP/s (the paper keeps the dense GEMM, Sec. 3.2, so flops are the dense
+2*C_out*C_in*N_tok); the two halves of the metric are broken out under
+"halves", each with its own roofline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+# HBM traffic per launch of the dominant kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="vitb_fc1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold", action="store_true",
+                    help="rotate over several input copies so that x / dY never sit in the Infinity Cache")
+    return ap.parse_args()
+
+
+def event_ms(events):
+    return [events[i].elapsed_time(events[i + 1]) for i in range(len(events) - 1)]
+
+
+def cpu_baseline(w, flops_per_step):
+    """The oracle, as it stands, on this host's cores, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from dropit_inputs import make
+
+    x, dy = make(w)
+    k = oracle.keep_count(x.size, w.gamma)
+    t0 = time.perf_counter()
+    vals, idx = oracle.compress(x, k)
+    t_compress = time.perf_counter() - t0
+    xh = oracle.densify(vals, idx, x.shape)
+    dyw = oracle.widen(dy)
+    rows = min(w.c_out, 2 * oracle.num_threads())
+    t0 = time.perf_counter()
+    if w.conv is None:
+        oracle.dw_fc(xh, dyw, 0, rows)
+    else:
+        oracle.dw_conv(xh, dyw, w.conv[0], w.conv[1], (w.conv[2],) * 2, (w.conv[3],) * 2, (1, 1), 0, rows)
+    t_rows = time.perf_counter() - t0
+    t_step = t_compress + t_rows * (w.c_out / rows)
+    return {
+        "value": flops_per_step / t_step * 1e-12,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "full-sort compress of the whole tensor (%.2f s) + fp64 dW for %d of %d output rows "
+                  "(%.2f s), extrapolated to all rows" % (t_compress, rows, w.c_out, t_rows),
+        "compress_GBps": (x.nbytes + k * (x.itemsize + 4)) / t_compress * 1e-9,
+        "dw_GFLOPs": flops_per_step * (rows / w.c_out) / t_rows * 1e-9,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are not part of it.",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2202_13808_amd as dropit
+    from dropit_inputs import WORKLOADS, make
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    dropit.lib()  # fail loudly if the extension is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = WORKLOADS[args.workload]
+    xh, dyh = make(w)
+
+    def dev_tensor(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    copies = 1
+    if args.cold:
+        per = xh.nbytes + dyh.nbytes
+        copies = max(2, int(np.ceil(600e6 / per)))
+    xs = [dev_tensor(xh) for _ in range(copies)]
+    dys = [dev_tensor(dyh) for _ in range(copies)]
+    conv = None if w.conv is None else (w.conv[0], w.conv[1], w.conv[2], w.conv[2], w.conv[3], w.conv[3], 1, 1)
+
+    k = dropit.keep_count(w.numel, w.gamma)
+    vals = torch.empty(k, dtype=xs[0].dtype, device=dev)
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    dW = torch.empty(w.dw_shape, dtype=torch.float32, device=dev)
+    ws_c = torch.empty(dropit.compress_workspace_bytes(w.numel, xs[0].dtype), dtype=torch.uint8, device=dev)
+    ws_g = torch.empty(max(1, dropit.weight_grad_workspace_bytes(w.x_shape, xs[0].dtype, k, w.c_out, conv)),
+                       dtype=torch.uint8, device=dev)
+
+    def step(i):
+        x, dy = xs[i % copies], dys[i % copies]
+        dropit.compress(x, w.gamma, vals=vals, idx=idx, workspace=ws_c)
+        dropit.weight_grad(vals, idx, w.x_shape, dy, w.c_out, conv=conv, dW=dW, workspace=ws_g)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # ---- per-call and per-kernel durations with HIP events on the launch stream ----
+    n_meas = min(args.steps, 50)
+    ce = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(n_meas)]
+    ge = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(n_meas)]
+    for evs in ce + ge:                      # create the underlying handles
+        for e in evs:
+            e.record()
+    torch.cuda.synchronize()
+    n_c = n_g = 0
+    for i in range(n_meas):
+        x, dy = xs[i % copies], dys[i % copies]
+        dropit.trace_events(ce[i])
+        dropit.compress(x, w.gamma, vals=vals, idx=idx, workspace=ws_c)
+        dropit.trace_events(ge[i])
+        dropit.weight_grad(vals, idx, w.x_shape, dy, w.c_out, conv=conv, dW=dW, workspace=ws_g)
+        dropit.trace_events(None)
+    torch.cuda.synchronize()
+    bf16 = w.dtype == "bf16"
+    # marks actually recorded per call: compress bf16 = init,hist,count,compact,end (5); fp32 has two hist passes (6)
+    n_c = 5 if bf16 else 6
+    fc_mfma = bf16 and w.conv is None and w.c_out % 8 == 0
+    n_g = 4 if fc_mfma else 3                # prep, gemm, reduce, end  |  zero+scatter, gemm, end
+    c_ms = np.array([event_ms(e[:n_c]) for e in ce])          # [n_meas, n_c-1]
+    g_ms = np.array([event_ms(e[:n_g]) for e in ge])
+    c_med = np.median(c_ms, axis=0)
+    g_med = np.median(g_ms, axis=0)
+    c_names = ["init", "hist", "count", "compact"] if bf16 else ["init", "hist0", "hist1", "count", "compact"]
+    g_names = ["bucket_prep", "mfma_gemm", "splitk_reduce"] if fc_mfma else ["zero_scatter", "fma_gemm"]
+    compress_ms = float(c_med.sum())
+    grad_ms = float(g_med.sum())
+
+    esz = 2 if bf16 else 4
+    compress_bytes = w.numel * esz + k * (esz + 4)           # read x once + write k (value, index) pairs
+    flops = float(w.dense_flops)
+    main_idx = 1
+    main_ms = float(np.mean(g_ms[:, main_idx]))
+    dw_tflops_kernel = flops / (main_ms * 1e-3) * 1e-12
+    hist_ms = float(np.mean(c_ms[:, 1]))
+    hist_gbps = w.numel * esz / (hist_ms * 1e-3) * 1e-9
+
+    out = {
+        "metric": "min-k compress GB/s (% HBM peak) + sparse-input dW TFLOP/s (% MFMA peak)",
+        "value": flops / (ms_per_step * 1e-3) * 1e-12,
+        "unit": "TFLOP/s (dense-equivalent dW flops per whole compress+dW step)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: x %s %s gamma=%.2f, dY %s, dW %s fp32%s" % (
+            w.name, w.dtype, list(w.x_shape), w.gamma, list(w.dy_shape), list(w.dw_shape),
+            " (cold: %d rotating input copies)" % copies if args.cold else " (inputs warm in Infinity Cache)")},
+        "halves": {
+            "compress_GBps": compress_bytes / (compress_ms * 1e-3) * 1e-9,
+            "compress_pct_hbm_peak": 100.0 * compress_bytes / (compress_ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS,
+            "compress_ms": compress_ms,
+            "compress_kernels_ms": dict(zip(c_names, [float(v) for v in c_med])),
+            "dw_TFLOPs": flops / (grad_ms * 1e-3) * 1e-12,
+            "dw_pct_mfma_peak": 100.0 * flops / (grad_ms * 1e-3) * 1e-12 / MFMA_BF16_PEAK_TFLOPS,
+            "dw_ms": grad_ms,
+            "dw_kernels_ms": dict(zip(g_names, [float(v) for v in g_med])),
+        },
+        "roofline": {
+            "kernel": "fc_mfma_kernel" if fc_mfma else "fma kernel",
+            "bound": "mfma" if fc_mfma else "alu",
+            "achieved": dw_tflops_kernel,
+            "peak": MFMA_BF16_PEAK_TFLOPS if fc_mfma else 157.3,
+            "unit": "TFLOP/s",
+            "frac": dw_tflops_kernel / (MFMA_BF16_PEAK_TFLOPS if fc_mfma else 157.3),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "dw")),
+            "avg_kernel_ms": main_ms,
+        },
+        "roofline_compress": {
+            "kernel": "hist_kernel (first select pass, reads x once)",
+            "bound": "hbm",
+            "achieved": hist_gbps,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": hist_gbps / HBM_PEAK_GBPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "hist")),
+            "avg_kernel_ms": hist_ms,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, flops)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

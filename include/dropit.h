@@ -96,10 +96,10 @@ typedef struct {
     int64_t kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
 } dropit_conv2d;
 
-/* Bytes of device workspace dropit_weight_grad needs (0 on invalid or
- * unsupported arguments).  Arguments as for dropit_weight_grad. */
+/* Bytes of device workspace dropit_weight_grad needs for k retained pairs (0 on
+ * invalid or unsupported arguments).  Arguments as for dropit_weight_grad. */
 size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
-                                          int64_t c_out, const dropit_conv2d *conv);
+                                          int64_t k, int64_t c_out, const dropit_conv2d *conv);
 
 /*
  * Weight gradient from the sparsified cache (Sec. 3.2): the recover step R(a^)
@@ -134,6 +134,17 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
                                  const void *dY, int64_t c_out, const dropit_conv2d *conv,
                                  float *dW, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
+
+/*
+ * Measurement aid (not part of the method): per-kernel timing marks.
+ * `events` is a HOST array of `count` hipEvent_t handles created by the caller.
+ * The next dropit_compress / dropit_weight_grad call made from this host thread
+ * records events[0] before its first kernel, events[i] before its (i+1)-th
+ * kernel and one after its last, on the call's stream, until the array is
+ * used up.  Pass (NULL, 0) to switch it off.  The handles stay owned by the
+ * caller; this per-thread setting is the only state the library keeps.
+ */
+void dropit_trace_events(void **events, int count);
 
 #ifdef __cplusplus
 }

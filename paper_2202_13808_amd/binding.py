@@ -58,7 +58,9 @@ def lib() -> ctypes.CDLL:
         L.dropit_compress.restype = i32
         L.dropit_compress.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp, sz, vp]
         L.dropit_weight_grad_workspace_bytes.restype = sz
-        L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, pconv]
+        L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
+        L.dropit_trace_events.restype = None
+        L.dropit_trace_events.argtypes = [ctypes.POINTER(vp), i32]
         L.dropit_weight_grad.restype = i32
         L.dropit_weight_grad.argtypes = [vp, vp, i64, p64, i32, i32, vp, i64, pconv, vp, vp, sz, vp]
         _lib = L
@@ -139,10 +141,11 @@ def compress(x: torch.Tensor, gamma: float, vals: Optional[torch.Tensor] = None,
     return vals[:k], idx[:k]
 
 
-def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, c_out: int, conv=None) -> int:
+def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int,
+                                conv=None) -> int:
     cs = _conv_struct(conv)
     return int(lib().dropit_weight_grad_workspace_bytes(
-        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(c_out),
+        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out),
         ctypes.byref(cs) if cs is not None else None))
 
 
@@ -164,10 +167,10 @@ def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], d
         else:
             dw_shape = (int(c_out), x_shape[1], cs.kh, cs.kw)
         dW = torch.empty(dw_shape, dtype=torch.float32, device=dY.device)
-    if workspace is None:
-        workspace = torch.empty(max(weight_grad_workspace_bytes(x_shape, dY.dtype, c_out, cs), 1),
-                                dtype=torch.uint8, device=dY.device)
     k = int(vals.numel())
+    if workspace is None:
+        workspace = torch.empty(max(weight_grad_workspace_bytes(x_shape, dY.dtype, k, c_out, cs), 1),
+                                dtype=torch.uint8, device=dY.device)
     with torch.cuda.device(dY.device):
         _check(lib().dropit_weight_grad(
             vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
@@ -175,3 +178,14 @@ def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], d
             ctypes.byref(cs) if cs is not None else None, dW.data_ptr(),
             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dW
+
+
+def trace_events(events: Optional[Sequence[torch.cuda.Event]]) -> None:
+    """dropit_trace_events: record the given (already created, timing-enabled) events around
+    the kernels of the next compress / weight_grad call from this thread; None switches it off."""
+    if not events:
+        lib().dropit_trace_events(None, 0)
+        return
+    handles = (ctypes.c_void_p * len(events))(*[int(e.cuda_event) for e in events])
+    trace_events._keepalive = handles          # the library reads this array during the next call
+    lib().dropit_trace_events(handles, len(events))

@@ -34,6 +34,18 @@ inline dropit_status launch_status()
     return hipGetLastError() == hipSuccess ? DROPIT_OK : DROPIT_EHIP;
 }
 
+// ---- optional per-kernel timing marks (see dropit_trace_events) ---------
+struct TraceState {
+    hipEvent_t *events;
+    int count, next;
+};
+TraceState &trace_state();                       // per host thread; defined in compress.hip
+inline void trace_mark(hipStream_t stream)
+{
+    TraceState &t = trace_state();
+    if (t.next < t.count) (void)hipEventRecord(t.events[t.next++], stream);
+}
+
 // ---- wave / block primitives (64-wide wavefronts) -----------------------
 
 __device__ inline uint32_t wave_sum(uint32_t v)

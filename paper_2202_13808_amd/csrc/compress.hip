@@ -398,27 +398,47 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
     uint32_t *off_eq = reinterpret_cast<uint32_t *>(ws + SelWorkspace::offeq_off);
     const RAW *xr = static_cast<const RAW *>(x);
 
+    trace_mark(stream);
     init_kernel<<<32, 256, 0, stream>>>(reinterpret_cast<uint32_t *>(ws),
                                         static_cast<uint32_t>(SelWorkspace::zero_bytes / 4),
                                         static_cast<uint32_t>(k));
     const dim3 grid(g.chunks), block(SEL_THREADS);
+    trace_mark(stream);
     if constexpr (sizeof(RAW) == 2) {
         hist_kernel<RAW, 11><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, hist0, 4, 0);
+        trace_mark(stream);
         count_kernel<RAW, 4><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, table, off_gt, off_eq, 1);
     } else {
         hist_kernel<RAW, 13><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, hist0, 18, 0);
         hist_kernel<RAW, 13><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, hist1, 5, 1);
+        trace_mark(stream);
         count_kernel<RAW, 5><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, table, off_gt, off_eq, 2);
     }
+    trace_mark(stream);
     compact_kernel<RAW><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, off_gt, off_eq,
                                                     static_cast<RAW *>(vals), idx);
+    trace_mark(stream);
     return launch_status();
 }
 
 }  // namespace
 }  // namespace dropit
 
+dropit::TraceState &dropit::trace_state()
+{
+    static thread_local TraceState t = {nullptr, 0, 0};
+    return t;
+}
+
 using namespace dropit;
+
+extern "C" void dropit_trace_events(void **events, int count)
+{
+    TraceState &t = trace_state();
+    t.events = reinterpret_cast<hipEvent_t *>(events);
+    t.count = (events != nullptr && count > 0) ? count : 0;
+    t.next = 0;
+}
 
 extern "C" const char *dropit_status_string(dropit_status s)
 {

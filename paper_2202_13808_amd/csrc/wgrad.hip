@@ -8,7 +8,7 @@
 // (exact fp32 products, fixed summation order).  They serve fp32 inputs and
 // any bf16 shape the MFMA kernels do not cover.
 #include "common.hpp"
-#include <algorithm>
+#include "wgrad_internal.hpp"
 
 namespace dropit {
 namespace {
@@ -160,11 +160,13 @@ dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx
                           float *dW, char *ws, size_t dense_sz, hipStream_t stream)
 {
     RAW *dense = reinterpret_cast<RAW *>(ws);
+    trace_mark(stream);
     zero_kernel<<<1024, 256, 0, stream>>>(reinterpret_cast<uint4 *>(dense), dense_sz / 16);
     if (k > 0) {
         const int blocks = static_cast<int>(std::min<int64_t>((k + 255) / 256, 4096));
         scatter_kernel<RAW><<<blocks, 256, 0, stream>>>(static_cast<const RAW *>(vals), idx, k, p.numel, dense);
     }
+    trace_mark(stream);
     if (!p.conv) {
         const dim3 grid((p.cin + FT - 1) / FT, (p.cout + FT - 1) / FT);
         fc_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), p.ntok, int(p.cin),
@@ -174,6 +176,7 @@ dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx
         conv3x3_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), int(p.N), int(p.C),
                                                            int(p.H), int(p.W), int(p.cout), dW);
     }
+    trace_mark(stream);
     return launch_status();
 }
 
@@ -182,12 +185,23 @@ dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx
 
 using namespace dropit;
 
+// Workspace need of the path dropit_weight_grad will take for this problem.
+static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
+{
+    if (!p.conv && dt == DROPIT_BF16) {
+        const FcProblem fp = {p.ntok, p.cin, p.cout, k};
+        if (fc_mfma_supported(fp)) return fc_mfma_plan(fp).total();
+    }
+    return dense_bytes(p, dt);
+}
+
 extern "C" size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
-                                                     int64_t c_out, const dropit_conv2d *conv)
+                                                     int64_t k, int64_t c_out, const dropit_conv2d *conv)
 {
     Problem p;
     if (describe(x_shape, ndim, dt, c_out, conv, p) != DROPIT_OK) return 0;
-    return dense_bytes(p, dt);
+    if (k < 0 || k > p.numel) return 0;
+    return workspace_need(p, dt, k);
 }
 
 extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k,
@@ -203,10 +217,14 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
     if (k > 0 && (!aligned(vals, dt == DROPIT_F32 ? 4 : 2) || !aligned(idx, 4))) return DROPIT_EINVAL;
     if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
     if (workspace == nullptr || !aligned(workspace, 256)) return DROPIT_EINVAL;
-    const size_t need = dense_bytes(p, dt);
+    const size_t need = workspace_need(p, dt, k);
     if (workspace_bytes < need) return DROPIT_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
+    if (!p.conv && dt == DROPIT_BF16 && k > 0) {
+        const FcProblem fp = {p.ntok, p.cin, p.cout, k};
+        if (fc_mfma_supported(fp)) return fc_mfma_run(fp, fc_mfma_plan(fp), vals, idx, dY, dW, ws, stream);
+    }
     if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
     return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);
 }

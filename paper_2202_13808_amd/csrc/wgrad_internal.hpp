@@ -1,0 +1,26 @@
+// Internal interfaces between the weight-gradient host entry point and its kernels.
+#pragma once
+
+#include <algorithm>
+
+#include "common.hpp"
+
+namespace dropit {
+
+struct FcProblem {
+    int64_t ntok, cin, cout, k;
+};
+
+struct FcPlan {
+    int nkb, nb_count, mb_count, splits;
+    size_t packed_bytes, tileptr_bytes, partial_bytes;
+    size_t total() const { return packed_bytes + tileptr_bytes + partial_bytes; }
+};
+
+// bf16 fully-connected weight gradient on the matrix cores (wgrad_fc_mfma.hip)
+bool fc_mfma_supported(const FcProblem &p);
+FcPlan fc_mfma_plan(const FcProblem &p);
+dropit_status fc_mfma_run(const FcProblem &p, const FcPlan &plan, const void *vals, const int32_t *idx,
+                          const void *dY, float *dW, char *ws, hipStream_t stream);
+
+}  // namespace dropit

@@ -21,7 +21,7 @@ def declared_symbols():
 def test_header_declares_the_expected_entry_points():
     assert declared_symbols() == sorted([
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
-        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad"])
+        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events"])
 
 
 def test_library_exports_every_declared_symbol():
