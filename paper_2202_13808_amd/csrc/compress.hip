@@ -26,8 +26,8 @@
 namespace dropit {
 namespace {
 
-constexpr int SEL_THREADS = 512;
-constexpr int SEL_MAX_CHUNKS = 1024;
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_MAX_CHUNKS = 512;
 constexpr int SEL_UNROLL = 4;
 constexpr int MAX_HIST_BITS = 13;
 constexpr int MAX_LAST_BINS = 32;
@@ -64,34 +64,15 @@ template <> struct KeyTraits<uint32_t> {
     static constexpr uint32_t MASK = 0x7FFFFFFFu;
 };
 
-__device__ inline void unpack(const uint4 &q, uint16_t (&r)[8])
+// Calls f(raw_bits, e) for the VEC elements of one 16-byte vector, e ascending.
+template <typename F> __device__ inline void for_each_raw(uint16_t, const uint4 &q, F f)
 {
-    r[0] = q.x & 0xFFFF; r[1] = q.x >> 16; r[2] = q.y & 0xFFFF; r[3] = q.y >> 16;
-    r[4] = q.z & 0xFFFF; r[5] = q.z >> 16; r[6] = q.w & 0xFFFF; r[7] = q.w >> 16;
+    f(q.x & 0xFFFFu, 0); f(q.x >> 16, 1); f(q.y & 0xFFFFu, 2); f(q.y >> 16, 3);
+    f(q.z & 0xFFFFu, 4); f(q.z >> 16, 5); f(q.w & 0xFFFFu, 6); f(q.w >> 16, 7);
 }
-__device__ inline void unpack(const uint4 &q, uint32_t (&r)[4])
+template <typename F> __device__ inline void for_each_raw(uint32_t, const uint4 &q, F f)
 {
-    r[0] = q.x; r[1] = q.y; r[2] = q.z; r[3] = q.w;
-}
-
-// Loads vector v (VEC consecutive elements, 16 bytes) of x; returns the number
-// of valid elements (VEC except in the ragged last vector, 0 if v >= nvec).
-template <typename RAW>
-__device__ inline int load_vec(const RAW *__restrict__ x, int64_t v, int64_t nvec, int64_t numel,
-                               RAW (&r)[KeyTraits<RAW>::VEC])
-{
-    constexpr int VEC = KeyTraits<RAW>::VEC;
-    if (v >= nvec) return 0;
-    const int64_t base = v * VEC;
-    if (base + VEC <= numel) {
-        const uint4 q = reinterpret_cast<const uint4 *>(x)[v];
-        unpack(q, r);
-        return VEC;
-    }
-    const int nv = static_cast<int>(numel - base);
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) r[e] = (e < nv) ? x[base + e] : RAW(0);
-    return nv;
+    f(q.x, 0); f(q.y, 1); f(q.z, 2); f(q.w, 3);
 }
 
 __global__ void __launch_bounds__(256) init_kernel(uint32_t *ws, uint32_t nwords, uint32_t k)
@@ -101,24 +82,21 @@ __global__ void __launch_bounds__(256) init_kernel(uint32_t *ws, uint32_t nwords
 }
 
 // Ticket: true in every thread of exactly one workgroup, the last to arrive.
+// The fences make every earlier workgroup's global writes visible to the
+// ordinary loads the last workgroup issues afterwards.
 __device__ inline bool last_block_to_arrive(uint32_t *ticket)
 {
     __shared__ uint32_t s_last;
-    __threadfence();                       // publish this workgroup's global writes
-    __syncthreads();
+    __syncthreads();                       // the whole workgroup's global writes are issued
     if (threadIdx.x == 0) {
+        __threadfence();                   // release them (one fence per workgroup: it is device-wide)
         const uint32_t t = atomicAdd(ticket, 1u);
-        s_last = (t == gridDim.x - 1) ? 1u : 0u;
+        const bool last = t == gridDim.x - 1;
+        if (last) __threadfence();         // acquire every other workgroup's writes
+        s_last = last ? 1u : 0u;
     }
     __syncthreads();
-    const bool last = s_last != 0;
-    if (last) __threadfence();             // see every other workgroup's writes
-    return last;
-}
-
-__device__ inline uint32_t coherent_load(const uint32_t *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return s_last != 0;
 }
 
 // One workgroup: find the digit d with  #{digit > d} < k_rem <= #{digit >= d}
@@ -133,7 +111,7 @@ __device__ inline void resolve_digit(const uint32_t *hist, SelState *st, uint32_
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-        c[i] = (lo + i < NB) ? coherent_load(hist + lo + i) : 0u;
+        c[i] = (lo + i < NB) ? hist[lo + i] : 0u;
         mine += c[i];
     }
     // inclusive suffix sum over threads: scan[tid] = sum of `mine` for threads >= tid
@@ -162,46 +140,54 @@ __device__ inline void resolve_digit(const uint32_t *hist, SelState *st, uint32_
     }
 }
 
-template <typename RAW, int BITS>
+// Digit histogram of the keys whose higher digits equal the resolved prefix.
+// x is walked as `nvf` full 16-byte vectors split into contiguous chunks of
+// `vpc` vectors (one per workgroup); the last workgroup also takes the
+// numel % VEC ragged elements.  The inner loop is branch-free: a key that does
+// not match, or whose digit is 0 (exact zeros are common after ReLU), is
+// counted in a per-lane spill slot instead of a shared bin.
+template <typename RAW, int SHIFT, int BITS, bool FIRST>
 __global__ void __launch_bounds__(SEL_THREADS)
-hist_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc, SelState *st,
-            uint32_t *ghist, int shift, int pass)
+hist_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, SelState *st,
+            uint32_t *ghist, int pass)
 {
     constexpr int VEC = KeyTraits<RAW>::VEC;
+    constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
     constexpr int NB = 1 << BITS;
-    __shared__ uint32_t lh[NB];
+    __shared__ uint32_t lh[NB + 2 * WAVE];
     __shared__ uint32_t scan[SEL_THREADS];
-    const int tid = threadIdx.x;
-    for (int i = tid; i < NB; i += SEL_THREADS) lh[i] = 0;
-    const uint32_t prefix = st->prefix;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    for (int i = tid; i < NB + 2 * WAVE; i += SEL_THREADS) lh[i] = 0;
+    const uint32_t prefix = FIRST ? 0u : st->prefix;
     __syncthreads();
 
+    const uint32_t zslot = NB + lane, dslot = NB + WAVE + lane;
+    auto count = [&](uint32_t raw, int) {
+        const uint32_t key = raw & MASK;
+        const uint32_t d = (key >> SHIFT) & (NB - 1);
+        uint32_t a = d ? d : zslot;
+        if (!FIRST) a = ((key >> (SHIFT + BITS)) == prefix) ? a : dslot;
+        atomicAdd(&lh[a], 1u);
+    };
+    const uint4 *xv = reinterpret_cast<const uint4 *>(x);
     const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
-    const int64_t v1 = min(v0 + vpc, nvec);
-    uint32_t zero_digit = 0;               // digit 0 is counted in registers (exact zeros are common)
-    for (int64_t vb = v0; vb < v1; vb += SEL_THREADS * SEL_UNROLL) {
-        RAW r[SEL_UNROLL][VEC];
-        int nv[SEL_UNROLL];
+    const int64_t v1 = min(v0 + vpc, nvf);
+    int64_t vb = v0;
+    for (; vb + SEL_THREADS * SEL_UNROLL <= v1; vb += SEL_THREADS * SEL_UNROLL) {
+        uint4 q[SEL_UNROLL];
 #pragma unroll
-        for (int u = 0; u < SEL_UNROLL; ++u) {
-            const int64_t v = vb + u * SEL_THREADS + tid;
-            nv[u] = load_vec<RAW>(x, v < v1 ? v : nvec, nvec, numel, r[u]);
-        }
+        for (int u = 0; u < SEL_UNROLL; ++u) q[u] = xv[vb + u * SEL_THREADS + tid];
 #pragma unroll
-        for (int u = 0; u < SEL_UNROLL; ++u) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const uint32_t key = r[u][e] & KeyTraits<RAW>::MASK;
-                if (e < nv[u] && (key >> (shift + BITS)) == prefix) {
-                    const uint32_t d = (key >> shift) & (NB - 1);
-                    if (d == 0) ++zero_digit;
-                    else atomicAdd(&lh[d], 1u);
-                }
-            }
-        }
+        for (int u = 0; u < SEL_UNROLL; ++u) for_each_raw(RAW(0), q[u], count);
     }
-    zero_digit = wave_sum(zero_digit);
-    if ((tid & (WAVE - 1)) == 0 && zero_digit) atomicAdd(&lh[0], zero_digit);
+    for (int64_t v = vb + tid; v < v1; v += SEL_THREADS) for_each_raw(RAW(0), xv[v], count);
+    if (blockIdx.x == gridDim.x - 1 && tid == 0)
+        for (int64_t i = nvf * VEC; i < numel; ++i) count(x[i], 0);
+    __syncthreads();
+    if (tid < WAVE) {                      // fold the digit-0 spill slots into bin 0
+        const uint32_t z = wave_sum(lh[NB + tid]);
+        if (tid == 0) lh[0] += z;
+    }
     __syncthreads();
     for (int i = tid; i < NB; i += SEL_THREADS) {
         const uint32_t c = lh[i];
@@ -211,61 +197,60 @@ hist_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc,
     resolve_digit<NB, BITS>(ghist, st, scan);
 }
 
+// Last digit + per-chunk bookkeeping for the ordered compaction.
 template <typename RAW, int LAST_BITS>
 __global__ void __launch_bounds__(SEL_THREADS)
-count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc, SelState *st,
+count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, SelState *st,
              uint32_t *table /*[LB+1][G]*/, uint32_t *off_gt, uint32_t *off_eq, int pass)
 {
     constexpr int VEC = KeyTraits<RAW>::VEC;
+    constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
     constexpr int LB = 1 << LAST_BITS;
-    __shared__ uint32_t lh[LB + 1];
+    constexpr int NW = SEL_THREADS / WAVE;
+    __shared__ uint32_t lh[LB + 1 + WAVE];
     __shared__ uint32_t s_digit;
-    __shared__ unsigned long long wave_tot[SEL_THREADS / WAVE];
-    const int tid = threadIdx.x;
+    __shared__ unsigned long long wave_tot[NW];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int G = gridDim.x;
-    if (tid <= LB) lh[tid] = 0;
-    const uint32_t prefix = st->prefix;    // == key >> LAST_BITS of the threshold
+    for (int i = tid; i < LB + 1 + WAVE; i += SEL_THREADS) lh[i] = 0;
+    const uint32_t prefix = st->prefix;    // == (threshold key) >> LAST_BITS
     __syncthreads();
 
-    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
-    const int64_t v1 = min(v0 + vpc, nvec);
+    const uint32_t dslot = LB + 1 + lane;
     uint32_t above = 0;
-    for (int64_t vb = v0; vb < v1; vb += SEL_THREADS * SEL_UNROLL) {
-        RAW r[SEL_UNROLL][VEC];
-        int nv[SEL_UNROLL];
+    auto count = [&](uint32_t raw, int) {
+        const uint32_t key = raw & MASK;
+        const uint32_t hi = key >> LAST_BITS;
+        above += (hi > prefix) ? 1u : 0u;
+        atomicAdd(&lh[(hi == prefix) ? (key & (LB - 1)) : dslot], 1u);
+    };
+    const uint4 *xv = reinterpret_cast<const uint4 *>(x);
+    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
+    const int64_t v1 = min(v0 + vpc, nvf);
+    int64_t vb = v0;
+    for (; vb + SEL_THREADS * SEL_UNROLL <= v1; vb += SEL_THREADS * SEL_UNROLL) {
+        uint4 q[SEL_UNROLL];
 #pragma unroll
-        for (int u = 0; u < SEL_UNROLL; ++u) {
-            const int64_t v = vb + u * SEL_THREADS + tid;
-            nv[u] = load_vec<RAW>(x, v < v1 ? v : nvec, nvec, numel, r[u]);
-        }
+        for (int u = 0; u < SEL_UNROLL; ++u) q[u] = xv[vb + u * SEL_THREADS + tid];
 #pragma unroll
-        for (int u = 0; u < SEL_UNROLL; ++u) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const uint32_t key = r[u][e] & KeyTraits<RAW>::MASK;
-                const uint32_t hi = key >> LAST_BITS;
-                if (e < nv[u]) {
-                    if (hi > prefix) ++above;
-                    else if (hi == prefix) atomicAdd(&lh[key & (LB - 1)], 1u);
-                }
-            }
-        }
+        for (int u = 0; u < SEL_UNROLL; ++u) for_each_raw(RAW(0), q[u], count);
     }
+    for (int64_t v = vb + tid; v < v1; v += SEL_THREADS) for_each_raw(RAW(0), xv[v], count);
+    if (blockIdx.x == gridDim.x - 1 && tid == 0)
+        for (int64_t i = nvf * VEC; i < numel; ++i) count(x[i], 0);
     above = wave_sum(above);
-    if ((tid & (WAVE - 1)) == 0 && above) atomicAdd(&lh[LB], above);
+    if (lane == 0 && above) atomicAdd(&lh[LB], above);
     __syncthreads();
     if (tid <= LB) table[tid * G + blockIdx.x] = lh[tid];
     if (!last_block_to_arrive(&st->ticket[pass])) return;
 
     // ---- last workgroup: resolve the final digit, then per-chunk offsets ----
-    if (tid <= LB) lh[tid] = 0;
-    __syncthreads();
-    for (int c = tid; c < G; c += SEL_THREADS) {
-#pragma unroll
-        for (int b = 0; b < LB; ++b) {
-            const uint32_t n = coherent_load(table + b * G + c);
-            if (n) atomicAdd(&lh[b], n);
-        }
+    // totals per bin: each wavefront sums whole rows of table[b][0..G)
+    for (int b = tid / WAVE; b < LB; b += NW) {
+        uint32_t s = 0;
+        for (int c = lane; c < G; c += WAVE) s += table[b * G + c];
+        s = wave_sum(s);
+        if (lane == 0) lh[b] = s;
     }
     __syncthreads();
     if (tid == 0) {
@@ -282,8 +267,8 @@ count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc
     }
     __syncthreads();
     const int d = static_cast<int>(s_digit);
-    // exclusive scan over chunks of (#{key > t}, #{key == t}); two chunks per thread
-    constexpr int CPT = SEL_MAX_CHUNKS / SEL_THREADS;
+    // exclusive scan over chunks of (#{key > t}, #{key == t}); consecutive chunks per thread
+    constexpr int CPT = (SEL_MAX_CHUNKS + SEL_THREADS - 1) / SEL_THREADS;
     uint32_t gt[CPT], eq[CPT];
     unsigned long long mine = 0;
 #pragma unroll
@@ -291,10 +276,14 @@ count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc
         const int c = tid * CPT + i;
         gt[i] = eq[i] = 0;
         if (c < G) {
-            uint32_t g = coherent_load(table + LB * G + c);
-            for (int b = d + 1; b < LB; ++b) g += coherent_load(table + b * G + c);
+            uint32_t g = table[LB * G + c];
+#pragma unroll
+            for (int b = 0; b < LB; ++b) {
+                const uint32_t n = table[b * G + c];
+                g += (b > d) ? n : 0u;
+                eq[i] = (b == d) ? n : eq[i];
+            }
             gt[i] = g;
-            eq[i] = coherent_load(table + d * G + c);
         }
         mine += (static_cast<unsigned long long>(eq[i]) << 32) | gt[i];
     }
@@ -311,62 +300,85 @@ count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc
     }
 }
 
+// Ordered compaction of one chunk per workgroup.
 template <typename RAW>
 __global__ void __launch_bounds__(SEL_THREADS)
-compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvec, int64_t vpc,
+compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc,
                const SelState *__restrict__ st, const uint32_t *__restrict__ off_gt,
                const uint32_t *__restrict__ off_eq, RAW *__restrict__ vals, int32_t *__restrict__ idx)
 {
     constexpr int VEC = KeyTraits<RAW>::VEC;
+    constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
     __shared__ uint32_t wave_tot[SEL_THREADS / WAVE];
     const int tid = threadIdx.x;
     const uint32_t t = st->t;
     const uint32_t m = st->m;
     uint32_t run_gt = off_gt[blockIdx.x];  // #{key > t} before this tile
     uint32_t run_eq = off_eq[blockIdx.x];  // #{key == t} before this tile
+    const uint4 *xv = reinterpret_cast<const uint4 *>(x);
     const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
-    const int64_t v1 = min(v0 + vpc, nvec);
+    const int64_t v1 = min(v0 + vpc, nvf);
     for (int64_t vb = v0; vb < v1; vb += SEL_THREADS) {
         const int64_t v = vb + tid;
-        RAW r[VEC];
-        const int nv = load_vec<RAW>(x, v < v1 ? v : nvec, nvec, numel, r);
-        uint32_t cnt = 0;                  // low 16 bits: #gt, high 16 bits: #eq (tile <= 4096 elements)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const uint32_t key = r[e] & KeyTraits<RAW>::MASK;
-            if (e < nv) cnt += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
-        }
+        const bool live = v < v1;
+        uint4 q = make_uint4(0, 0, 0, 0);
+        if (live) q = xv[v];
+        uint32_t cnt = 0;                  // low 16 bits: #gt, high 16 bits: #eq (tile <= 8192 elements)
+        for_each_raw(RAW(0), q, [&](uint32_t raw, int) {
+            const uint32_t key = raw & MASK;
+            cnt += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
+        });
+        if (!live) cnt = 0;
         uint32_t total;
         const uint32_t excl = block_exclusive_scan<SEL_THREADS>(cnt, wave_tot, total);
         uint32_t my_gt = run_gt + (excl & 0xFFFFu);
         uint32_t my_eq = run_eq + (excl >> 16);
         const int64_t base = v * VEC;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            if (e < nv) {
-                const uint32_t key = r[e] & KeyTraits<RAW>::MASK;
+        if (live && cnt) {
+            for_each_raw(RAW(0), q, [&](uint32_t raw, int e) {
+                const uint32_t key = raw & MASK;
                 if (key > t) {
                     const uint32_t pos = my_gt + min(my_eq, m);
-                    vals[pos] = r[e];
+                    vals[pos] = static_cast<RAW>(raw);
                     idx[pos] = static_cast<int32_t>(base + e);
                     ++my_gt;
                 } else if (key == t) {
                     if (my_eq < m) {
                         const uint32_t pos = my_gt + my_eq;
-                        vals[pos] = r[e];
+                        vals[pos] = static_cast<RAW>(raw);
                         idx[pos] = static_cast<int32_t>(base + e);
                     }
                     ++my_eq;
                 }
-            }
+            });
         }
         run_gt += total & 0xFFFFu;
         run_eq += total >> 16;
     }
+    // ragged tail (numel % VEC elements) after the last full vector
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+        for (int64_t i = nvf * VEC; i < numel; ++i) {
+            const RAW raw = x[i];
+            const uint32_t key = raw & MASK;
+            if (key > t) {
+                const uint32_t pos = run_gt + min(run_eq, m);
+                vals[pos] = raw;
+                idx[pos] = static_cast<int32_t>(i);
+                ++run_gt;
+            } else if (key == t) {
+                if (run_eq < m) {
+                    const uint32_t pos = run_gt + run_eq;
+                    vals[pos] = raw;
+                    idx[pos] = static_cast<int32_t>(i);
+                }
+                ++run_eq;
+            }
+        }
+    }
 }
 
 struct Geometry {
-    int64_t nvec, vpc;
+    int64_t nvf, vpc;      // full 16-byte vectors, vectors per chunk
     int chunks;
 };
 
@@ -375,13 +387,15 @@ Geometry geometry(int64_t numel)
 {
     constexpr int VEC = KeyTraits<RAW>::VEC;
     Geometry g;
-    g.nvec = (numel + VEC - 1) / VEC;
-    int64_t chunks = (g.nvec + SEL_THREADS - 1) / SEL_THREADS;
+    g.nvf = numel / VEC;
+    int64_t chunks = (g.nvf + SEL_THREADS - 1) / SEL_THREADS;
     if (chunks > SEL_MAX_CHUNKS) chunks = SEL_MAX_CHUNKS;
     if (chunks < 1) chunks = 1;
-    g.vpc = (g.nvec + chunks - 1) / chunks;
+    g.vpc = (g.nvf + chunks - 1) / chunks;
     g.vpc = (g.vpc + 7) / 8 * 8;           // chunk starts on 128-byte lines
-    g.chunks = static_cast<int>((g.nvec + g.vpc - 1) / g.vpc);
+    if (g.vpc < 8) g.vpc = 8;
+    g.chunks = static_cast<int>((g.nvf + g.vpc - 1) / g.vpc);
+    if (g.chunks < 1) g.chunks = 1;        // a tensor shorter than one vector still needs a workgroup
     return g;
 }
 
@@ -405,17 +419,17 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
     const dim3 grid(g.chunks), block(SEL_THREADS);
     trace_mark(stream);
     if constexpr (sizeof(RAW) == 2) {
-        hist_kernel<RAW, 11><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, hist0, 4, 0);
+        hist_kernel<RAW, 4, 11, true><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, hist0, 0);
         trace_mark(stream);
-        count_kernel<RAW, 4><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, table, off_gt, off_eq, 1);
+        count_kernel<RAW, 4><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, table, off_gt, off_eq, 1);
     } else {
-        hist_kernel<RAW, 13><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, hist0, 18, 0);
-        hist_kernel<RAW, 13><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, hist1, 5, 1);
+        hist_kernel<RAW, 18, 13, true><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, hist0, 0);
+        hist_kernel<RAW, 5, 13, false><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, hist1, 1);
         trace_mark(stream);
-        count_kernel<RAW, 5><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, table, off_gt, off_eq, 2);
+        count_kernel<RAW, 5><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, table, off_gt, off_eq, 2);
     }
     trace_mark(stream);
-    compact_kernel<RAW><<<grid, block, 0, stream>>>(xr, numel, g.nvec, g.vpc, st, off_gt, off_eq,
+    compact_kernel<RAW><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, off_gt, off_eq,
                                                     static_cast<RAW *>(vals), idx);
     trace_mark(stream);
     return launch_status();
