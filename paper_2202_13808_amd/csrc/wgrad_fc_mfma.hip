@@ -16,6 +16,11 @@
 // separate kernel), so dW is bit-reproducible.
 #include "common.hpp"
 #include "wgrad_internal.hpp"
+#include <cstdlib>
+
+#ifndef DROPIT_ABLATE
+#define DROPIT_ABLATE 0          // development only: bit mask of pipeline parts to leave out (wrong results)
+#endif
 
 namespace dropit {
 namespace {
@@ -25,8 +30,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-constexpr int THREADS = 256;
+constexpr int THREADS = 256;      // prep (bucket) kernel workgroup size
+
 
 // ---------------------------------------------------------------------------
 // Cooperative lower_bound over a sorted int32 array: number of elements < target.
@@ -110,37 +117,53 @@ fc_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ 
 
 // ---------------------------------------------------------------------------
 // GEMM: one workgroup = one BM x BN tile of dW over a contiguous range of token
-// blocks (split `blockIdx.z` of `splits`).  4 wavefronts in a 2x2 grid, each
-// (BM/2) x (BN/2) built from 32x32x16 bf16 MFMAs.
-template <int BM, int BN, int BK>
-struct FcTile {
-    static constexpr int PITCH_A = (BM + 32) * 2;          // bytes; == 64 mod 256 for BM = 128/256
-    static constexpr int PITCH_B = BK * 2 + 16;            // bytes; odd multiple of 16
+// blocks (one of `splits` K-slices).  WAVES_M x WAVES_N wavefronts, each a
+// (BM/WAVES_M) x (BN/WAVES_N) sub-tile built from 32x32x16 bf16 MFMAs.
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int WPE_, int STAGES_>
+struct FcCfg {
+    static constexpr int STAGES = STAGES_;                 // register stages = global-load prefetch depth (even)
+    static_assert(STAGES_ >= 2 && STAGES_ % 2 == 0, "prefetch depth must be even");
+    static constexpr int WPE = WPE_;                       // wavefronts per SIMD the register budget must allow
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int NTHREADS = WAVE * WAVES_M * WAVES_N;
+    static constexpr int PITCH_A = (BM + 32) * 2;          // bytes; rows 64 bytes apart mod 256: conflict-free transpose reads
+    static constexpr int PITCH_B = BK * 2 + 16;            // bytes; odd multiple of 16: conflict-free 16-byte row reads
     static constexpr int A_BYTES = BK * PITCH_A;
-    static constexpr int B_BYTES = BN * PITCH_B;
+    static constexpr int B_BYTES = (BN * PITCH_B + NTHREADS * 16 - 1) / (NTHREADS * 16) * (NTHREADS * 16);  // whole 16-byte stores per thread
     static constexpr int LDS_BYTES = 2 * A_BYTES + 3 * B_BYTES;
-    static constexpr int WM = BM / 2, WN = BN / 2;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int FM = WM / 32, FN = WN / 32;
-    static constexpr int A_VECS = BK * (BM / 8) / THREADS; // 16-byte global loads per thread per step
-    static constexpr int B_VEC16 = B_BYTES / 16;
-    static constexpr int B_ZERO = (B_VEC16 + THREADS - 1) / THREADS;  // 16-byte zero stores per thread per step
-    static constexpr int ENT = 4;                          // packed pairs prefetched per thread per step
-    static_assert(BK * (BM / 8) % THREADS == 0, "A tile must divide over the block");
+    static constexpr int A_VECS = BK * (BM / 8) / NTHREADS; // 16-byte global loads per thread per step
+    static constexpr int B_ZERO = B_BYTES / 16 / NTHREADS;
+    static constexpr int ENT = (BK * BN / 4 / NTHREADS) < 2 ? 2 : (BK * BN / 4 / NTHREADS);  // prefetch depth: 25% density
+    static_assert(BK * (BM / 8) % NTHREADS == 0, "A tile must divide over the block");
+    static_assert(BN * PITCH_B < 65536, "packed LDS offsets are 16-bit");
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "MFMA 32x32x16 tiling");
 };
 
-template <int BM, int BN, int BK>
-__global__ void __launch_bounds__(THREADS)
+template <typename C>
+__global__ void __launch_bounds__(C::NTHREADS) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
 fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ packed,
-               const uint32_t *__restrict__ tile_ptr, int64_t ntok, int M, int N, int nb_count,
-               int nkb, int splits, float *__restrict__ out /* dW or partials [splits][M][N] */)
+               const uint32_t *__restrict__ tile_ptr, int64_t n_pairs, int64_t ntok, int M, int N, int nb_count,
+               int mb_count, int nkb, int splits, float *__restrict__ out /* dW or partials [splits][M][N] */)
 {
-    using T = FcTile<BM, BN, BK>;
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NTHREADS;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char *ldsA = lds;                         // [2][BK][PITCH_A]
-    char *ldsB = lds + 2 * T::A_BYTES;        // [3][BN][PITCH_B]
+    char *ldsB = lds + 2 * C::A_BYTES;        // [3][BN][PITCH_B]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int nb = blockIdx.x, mb = blockIdx.y, split = blockIdx.z;
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+
+    // Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-number so
+    // that the workgroups sharing one XCD's L2 are consecutive tiles: same rows of
+    // dY (mb), neighbouring column blocks (nb).
+    const int total = nb_count * mb_count * splits;
+    const int per_xcd = gridDim.x / 8;
+    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (v >= total) return;
+    const int nb = v % nb_count;
+    const int mb = (v / nb_count) % mb_count;
+    const int split = v / (nb_count * mb_count);
     const int m0 = mb * BM;
 
     // token blocks of this split: an even partition of [0, nkb)
@@ -148,124 +171,205 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
     const int kb_end = int(int64_t(nkb) * (split + 1) / splits);
     const int steps = kb_end - kb_begin;
 
-    f32x16 acc[T::FM][T::FN];
+    f32x16 acc[C::FM][C::FN];
 #pragma unroll
-    for (int i = 0; i < T::FM; ++i)
+    for (int i = 0; i < C::FM; ++i)
 #pragma unroll
-        for (int j = 0; j < T::FN; ++j)
+        for (int j = 0; j < C::FN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // per-thread A load geometry: vector v covers row (v / (BM/8)), columns 8*(v % (BM/8))
-    uint4 a_reg[T::A_VECS];
-    uint32_t e_reg[T::ENT];
-    uint32_t e_lo = 0, e_hi = 0;              // packed range of the prefetched step
+    // One pipeline stage held in registers: the dY vectors and packed pairs of one token block.
+    struct Stage {
+        u32x4 a[C::A_VECS];
+        uint32_t e[C::ENT];
+        uint32_t lo, hi;                      // packed range of the step
+    };
+    constexpr int R = C::STAGES;
+    Stage st[R];
+    if (DROPIT_ABLATE & 1) {                  // keep the registers defined when loads are left out
+        for (int r = 0; r < R; ++r) {
+            st[r].lo = st[r].hi = 0;
+            for (int i = 0; i < C::A_VECS; ++i) st[r].a[i] = u32x4{0, 0, 0, 0};
+            for (int i = 0; i < C::ENT; ++i) st[r].e[i] = 0;
+        }
+    }
 
-    auto load_step = [&](int kb) {
+    // Branch-free on purpose: every load is issued unconditionally from a clamped,
+    // valid address, so the compiler can count exactly how many newer loads may stay in
+    // flight when an older stage is consumed.  Rows past the last token re-read the last
+    // token (their a^ rows are zero, so they add nothing), columns past M re-read valid
+    // columns (those outputs are never stored), pair slots past the end of the tile's
+    // range re-read the last pair of the whole stream (ignored at scatter time).
+    const int64_t tok_last = ntok - 1;
+    const uint32_t pair_last = uint32_t(n_pairs - 1);
+    // L2 warm-up: one dword per 128-byte line of the dY block PF_DIST steps ahead.  The
+    // value is never used; the register stays live across the loop so that the late
+    // write cannot land in a reused register, and is drained after the loop.
+    uint32_t touch = 0;
+    auto touch_step = [&](int kb) {
+        constexpr int LINES = BK * (BM * 2 / 128);
+        const int row = (tid % LINES) / (BM * 2 / 128), line = tid % (BM * 2 / 128);
+        const int64_t tok = min(int64_t(kb) * BK + row, tok_last);
+        const int m = min(m0 + line * 64, M - 8);
+        const uint16_t *p = dY + tok * M + m;
+        asm volatile("global_load_dword %0, %1, off" : "+v"(touch) : "v"(p) : "memory");
+    };
+    auto load_step = [&](Stage &st, int kb) {
+        if (DROPIT_ABLATE & 1) return;
+#ifdef DROPIT_PF_DIST
+        touch_step(min(kb + DROPIT_PF_DIST, kb_end - 1));
+#endif
         const int64_t tok0 = int64_t(kb) * BK;
 #pragma unroll
-        for (int i = 0; i < T::A_VECS; ++i) {
-            const int v = tid + i * THREADS;
-            const int row = v / (BM / 8), cv = v % (BM / 8);
-            const int64_t tok = tok0 + row;
-            const int m = m0 + cv * 8;
-            uint4 q = make_uint4(0, 0, 0, 0);
-            if (tok < ntok && m < M) q = *reinterpret_cast<const uint4 *>(dY + tok * M + m);
-            a_reg[i] = q;
+        for (int i = 0; i < C::A_VECS; ++i) {
+            const int vv = tid + i * NT;
+            const int row = vv / (BM / 8), cv = vv % (BM / 8);
+            const int64_t tok = min(tok0 + row, tok_last);
+            const int m = min(m0 + cv * 8, M - 8);
+            st.a[i] = *reinterpret_cast<const u32x4 *>(dY + tok * M + m);
         }
-        e_lo = tile_ptr[int64_t(kb) * (nb_count + 1) + nb];
-        e_hi = tile_ptr[int64_t(kb) * (nb_count + 1) + nb + 1];
+        st.lo = tile_ptr[int64_t(kb) * (nb_count + 1) + nb];
+        st.hi = tile_ptr[int64_t(kb) * (nb_count + 1) + nb + 1];
 #pragma unroll
-        for (int i = 0; i < T::ENT; ++i) {
-            const uint32_t j = e_lo + tid + i * THREADS;
-            e_reg[i] = (j < e_hi) ? packed[j] : 0xFFFFFFFFu;
+        for (int i = 0; i < C::ENT; ++i) st.e[i] = packed[min(st.lo + tid + i * NT, pair_last)];
+    };
+    // What was scattered into a B buffer, kept until the buffer is cleared again.
+    struct Dirty {
+        uint32_t off[C::ENT];                 // LDS byte offsets (low 16 bits used)
+        uint32_t lo, hi;
+    };
+    Dirty dirty[2];                           // by parity of the step
+    dirty[0].lo = dirty[0].hi = dirty[1].lo = dirty[1].hi = 0;
+#pragma unroll
+    for (int i = 0; i < C::ENT; ++i) dirty[0].off[i] = dirty[1].off[i] = 0;
+
+    auto store_step = [&](const Stage &st, Dirty &d, int abuf, int bbuf) {
+        if (DROPIT_ABLATE & 2) return;
+        char *a = ldsA + abuf * C::A_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::A_VECS; ++i) {
+            const int vv = tid + i * NT;
+            const int row = vv / (BM / 8), cv = vv % (BM / 8);
+            *reinterpret_cast<u32x4 *>(a + row * C::PITCH_A + cv * 16) = st.a[i];
+        }
+        char *b = ldsB + bbuf * C::B_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::ENT; ++i) {
+            const uint32_t p = st.e[i];
+            d.off[i] = p;
+            if (st.lo + tid + i * NT < st.hi) *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
+        }
+        d.lo = st.lo;
+        d.hi = st.hi;
+        // pairs beyond the prefetch depth (dense tiles): fetched and scattered in place
+        if (st.hi - st.lo > uint32_t(C::ENT * NT)) {
+            for (uint32_t j = st.lo + tid + C::ENT * NT; j < st.hi; j += NT) {
+                const uint32_t p = packed[j];
+                *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
+            }
         }
     };
-    auto store_step = [&](int abuf, int bbuf) {
-        char *a = ldsA + abuf * T::A_BYTES;
+    // Clears exactly the slots store_step filled (about a tenth of the tile) instead of
+    // re-zeroing the whole buffer.
+    auto clear_step = [&](const Dirty &d, int bbuf) {
+        if (DROPIT_ABLATE & 4) return;
+        char *b = ldsB + bbuf * C::B_BYTES;
 #pragma unroll
-        for (int i = 0; i < T::A_VECS; ++i) {
-            const int v = tid + i * THREADS;
-            const int row = v / (BM / 8), cv = v % (BM / 8);
-            *reinterpret_cast<uint4 *>(a + row * T::PITCH_A + cv * 16) = a_reg[i];
-        }
-        char *b = ldsB + bbuf * T::B_BYTES;
-#pragma unroll
-        for (int i = 0; i < T::ENT; ++i) {
-            const uint32_t p = e_reg[i];
-            if (p != 0xFFFFFFFFu) *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
-        }
-        // pairs beyond the prefetch depth (dense tiles): fetched and scattered in place
-        for (uint32_t j = e_lo + tid + T::ENT * THREADS; j < e_hi; j += THREADS) {
-            const uint32_t p = packed[j];
-            *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
+        for (int i = 0; i < C::ENT; ++i)
+            if (d.lo + tid + i * NT < d.hi) *reinterpret_cast<uint16_t *>(b + (d.off[i] & 0xFFFFu)) = uint16_t(0);
+        if (d.hi - d.lo > uint32_t(C::ENT * NT)) {
+            for (uint32_t j = d.lo + tid + C::ENT * NT; j < d.hi; j += NT)
+                *reinterpret_cast<uint16_t *>(b + (packed[j] & 0xFFFFu)) = uint16_t(0);
         }
     };
     auto zero_b = [&](int bbuf) {
-        char *b = ldsB + bbuf * T::B_BYTES;
+        char *b = ldsB + bbuf * C::B_BYTES;
 #pragma unroll
-        for (int i = 0; i < T::B_ZERO; ++i)
-            if (tid + i * THREADS < T::B_VEC16)
-                *reinterpret_cast<uint4 *>(b + (tid + i * THREADS) * 16) = make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < C::B_ZERO; ++i)
+            *reinterpret_cast<uint4 *>(b + (tid + i * NT) * 16) = make_uint4(0, 0, 0, 0);
     };
     auto compute = [&](int abuf, int bbuf) {
-        const char *a = ldsA + abuf * T::A_BYTES;
-        const char *b = ldsB + bbuf * T::B_BYTES;
+        if (DROPIT_ABLATE & 8) return;
+        const char *a = ldsA + abuf * C::A_BYTES;
+        const char *b = ldsB + bbuf * C::B_BYTES;
         const int g = lane >> 4, p16 = lane & 15;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[T::FM], bfv[T::FN];
+            bf16x8 af[C::FM], bfv[C::FN];
 #pragma unroll
-            for (int i = 0; i < T::FM; ++i) {
+            for (int i = 0; i < C::FM; ++i) {
                 const int krow = kk * 16 + (g >> 1) * 8 + (p16 >> 2);
-                const int mcol = wm * T::WM + i * 32 + (g & 1) * 16 + (p16 & 3) * 4;
-                const char *p = a + krow * T::PITCH_A + mcol * 2;
+                const int mcol = wm * C::WM + i * 32 + (g & 1) * 16 + (p16 & 3) * 4;
+                const char *p = a + krow * C::PITCH_A + mcol * 2;
                 const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-                const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * T::PITCH_A));
+                const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * C::PITCH_A));
                 const s16x8 full = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
                 af[i] = __builtin_bit_cast(bf16x8, full);
             }
 #pragma unroll
-            for (int j = 0; j < T::FN; ++j) {
-                const int ncol = wn * T::WN + j * 32 + (lane & 31);
-                const char *p = b + ncol * T::PITCH_B + (kk * 16 + (lane >> 5) * 8) * 2;
+            for (int j = 0; j < C::FN; ++j) {
+                const int ncol = wn * C::WN + j * 32 + (lane & 31);
+                const char *p = b + ncol * C::PITCH_B + (kk * 16 + (lane >> 5) * 8) * 2;
                 bfv[j] = *reinterpret_cast<const bf16x8 *>(p);
             }
 #pragma unroll
-            for (int i = 0; i < T::FM; ++i)
+            for (int i = 0; i < C::FM; ++i)
 #pragma unroll
-                for (int j = 0; j < T::FN; ++j)
+                for (int j = 0; j < C::FN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
         }
     };
 
+        // Software pipeline with R register stages: the block of token step t lives in stage
+    // t % R from its global load until its LDS store, R - 1 steps later.  Iteration s:
+    //   clear what step s-1 scattered (B buffer (s+2)%3), store step s+1 (registers -> A
+    //   buffer (s+1)%2, B buffer (s+1)%3), reload that stage with step s+1+R, multiply
+    //   step s, barrier.
+    // The B buffer being read, the one being filled and the one being cleared are always
+    // different; register stage indices are compile-time (the loop is unrolled R times),
+    // LDS buffer indices are scalars.
     if (steps > 0) {
+        // Loads and stores past the last block are clamped to it instead of branched
+        // around: the loop body stays straight-line, so every wait counts exactly the
+        // newer loads it may leave in flight.  The duplicates land in LDS buffers that
+        // are never multiplied.
+        const int kb_last = kb_end - 1;
         zero_b(0);
         zero_b(1);
-        load_step(kb_begin);
+        zero_b(2);
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_step(st[r], min(kb_begin + r, kb_last));
         __syncthreads();
-        store_step(0, 0);
-        if (steps > 1) load_step(kb_begin + 1);
+        store_step(st[0], dirty[0], 0, 0);
+        load_step(st[0], min(kb_begin + R, kb_last));
         __syncthreads();
-        for (int s = 0; s < steps; ++s) {
-            if (s + 1 < steps) store_step((s + 1) & 1, (s + 1) % 3);
-            if (s + 2 < steps) load_step(kb_begin + s + 2);
-            zero_b((s + 2) % 3);
-            compute(s & 1, s % 3);
-            __syncthreads();
+        for (int s0 = 0; s0 < steps; s0 += R) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int s = s0 + r;
+                clear_step(dirty[(r + 1) & 1], (s + 2) % 3);          // step s-1 (nothing on the first pass)
+                store_step(st[(r + 1) % R], dirty[(r + 1) & 1], (s + 1) & 1, (s + 1) % 3);
+                load_step(st[(r + 1) % R], min(kb_begin + s + 1 + R, kb_last));
+                if (s < steps) compute(s & 1, s % 3);
+                __syncthreads();
+            }
         }
     }
 
+#ifdef DROPIT_PF_DIST
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(touch) : : "memory");
+#endif
     // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block
     float *dst = out + int64_t(split) * M * N;
 #pragma unroll
-    for (int i = 0; i < T::FM; ++i)
+    for (int i = 0; i < C::FM; ++i)
 #pragma unroll
-        for (int j = 0; j < T::FN; ++j)
+        for (int j = 0; j < C::FN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * T::WM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                const int n = nb * BN + wn * T::WN + j * 32 + (lane & 31);
+                const int m = m0 + wm * C::WM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                const int n = nb * BN + wn * C::WN + j * 32 + (lane & 31);
                 if (m < M && n < N) dst[int64_t(m) * N + n] = acc[i][j][e];
             }
 }
@@ -284,32 +388,43 @@ splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int splits,
     }
 }
 
-constexpr int BM = 128, BN = 128, BK = 32;
-using Tile = FcTile<BM, BN, BK>;
+#ifndef DROPIT_FC_CFG
+#define DROPIT_FC_CFG 256, 256, 32, 2, 4, 2, 2
+#endif
+using Cfg = FcCfg<DROPIT_FC_CFG>;
+
+int tuned_splits(int tiles, int nkb)
+{
+    // one workgroup per compute unit (a tile's LDS footprint allows no more): as many
+    // K-slices as fill the 256 compute units without starting a second round
+    int splits = 256 / tiles;
+#ifdef DROPIT_TUNING
+    if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
+#endif
+    if (splits > nkb) splits = nkb;
+    if (splits < 1) splits = 1;
+    if (splits > 64) splits = 64;
+    return splits;
+}
 
 }  // namespace
 
 bool fc_mfma_supported(const FcProblem &p)
 {
     // 16-byte dY vectors need c_out % 8 == 0; packed offsets and counters are 32-bit
-    return p.cout % 8 == 0 && p.cin >= 1 && (p.cin + BN - 1) / BN <= 2 * THREADS && p.cout * p.cin % 4 == 0;
+    return p.cout % 8 == 0 && p.cin >= 1 && (p.cin + Cfg::BN - 1) / Cfg::BN <= 2 * THREADS;
 }
 
 FcPlan fc_mfma_plan(const FcProblem &p)
 {
     FcPlan plan;
-    plan.nkb = int((p.ntok + BK - 1) / BK);
-    plan.nb_count = int((p.cin + BN - 1) / BN);
-    plan.mb_count = int((p.cout + BM - 1) / BM);
-    const int tiles = plan.nb_count * plan.mb_count;
-    int splits = (2 * 256 + tiles - 1) / tiles;        // about two workgroups per compute unit
-    if (splits > plan.nkb) splits = plan.nkb;
-    if (splits < 1) splits = 1;
-    if (splits > 64) splits = 64;
-    plan.splits = splits;
+    plan.nkb = int((p.ntok + Cfg::BK - 1) / Cfg::BK);
+    plan.nb_count = int((p.cin + Cfg::BN - 1) / Cfg::BN);
+    plan.mb_count = int((p.cout + Cfg::BM - 1) / Cfg::BM);
+    plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
     plan.packed_bytes = round_up(size_t(p.k > 0 ? p.k : 1) * 4, 256);
     plan.tileptr_bytes = round_up(size_t(plan.nkb) * (plan.nb_count + 1) * 4, 256);
-    plan.partial_bytes = splits > 1 ? round_up(size_t(splits) * p.cout * p.cin * 4, 256) : 0;
+    plan.partial_bytes = plan.splits > 1 ? round_up(size_t(plan.splits) * p.cout * p.cin * 4, 256) : 0;
     return plan;
 }
 
@@ -322,22 +437,23 @@ dropit_status fc_mfma_run(const FcProblem &p, const FcPlan &plan, const void *va
 
     trace_mark(stream);
     const size_t bucket_lds = size_t(2 * plan.nb_count + 1) * 4;
-    fc_bucket_kernel<BK, BN, Tile::PITCH_B><<<plan.nkb, THREADS, bucket_lds, stream>>>(
+    fc_bucket_kernel<Cfg::BK, Cfg::BN, Cfg::PITCH_B><<<plan.nkb, THREADS, bucket_lds, stream>>>(
         static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, int(p.cin), plan.nb_count, packed, tile_ptr);
 
     trace_mark(stream);
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(fc_mfma_kernel<BM, BN, BK>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, Tile::LDS_BYTES) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(fc_mfma_kernel<Cfg>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) != hipSuccess)
             return DROPIT_EHIP;
         attr_set = true;
     }
-    const dim3 grid(plan.nb_count, plan.mb_count, plan.splits);
+    const int total = plan.nb_count * plan.mb_count * plan.splits;
+    const int grid = (total + 7) / 8 * 8;
     float *out = plan.splits > 1 ? partial : dW;
-    fc_mfma_kernel<BM, BN, BK><<<grid, THREADS, Tile::LDS_BYTES, stream>>>(
-        static_cast<const uint16_t *>(dY), packed, tile_ptr, p.ntok, int(p.cout), int(p.cin), plan.nb_count,
-        plan.nkb, plan.splits, out);
+    fc_mfma_kernel<Cfg><<<grid, Cfg::NTHREADS, Cfg::LDS_BYTES, stream>>>(
+        static_cast<const uint16_t *>(dY), packed, tile_ptr, p.k, p.ntok, int(p.cout), int(p.cin), plan.nb_count,
+        plan.mb_count, plan.nkb, plan.splits, out);
 
     trace_mark(stream);
     if (plan.splits > 1) {
