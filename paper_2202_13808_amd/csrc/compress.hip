@@ -424,6 +424,7 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
         count_kernel<RAW, 4><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, table, off_gt, off_eq, 1);
     } else {
         hist_kernel<RAW, 18, 13, true><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, hist0, 0);
+        trace_mark(stream);
         hist_kernel<RAW, 5, 13, false><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, hist1, 1);
         trace_mark(stream);
         count_kernel<RAW, 5><<<grid, block, 0, stream>>>(xr, numel, g.nvf, g.vpc, st, table, off_gt, off_eq, 2);
