@@ -158,13 +158,16 @@ def main():
     # marks actually recorded per call: compress bf16 = init,hist,count,compact,end (5); fp32 has two hist passes (6)
     n_c = 5 if bf16 else 6
     fc_mfma = bf16 and w.conv is None and w.c_out % 8 == 0
-    n_g = 4 if fc_mfma else 3                # prep, gemm, reduce, end  |  zero+scatter, gemm, end
+    conv_mfma = bf16 and w.conv is not None and w.x_shape[3] % 8 == 0
+    mfma = fc_mfma or conv_mfma
+    n_g = 4 if mfma else 3                   # prep, gemm, reduce, end  |  zero+scatter, gemm, end
     c_ms = np.array([event_ms(e[:n_c]) for e in ce])          # [n_meas, n_c-1]
     g_ms = np.array([event_ms(e[:n_g]) for e in ge])
     c_med = np.median(c_ms, axis=0)
     g_med = np.median(g_ms, axis=0)
     c_names = ["init", "hist", "count", "compact"] if bf16 else ["init", "hist0", "hist1", "count", "compact"]
-    g_names = ["bucket_prep", "mfma_gemm", "splitk_reduce"] if fc_mfma else ["zero_scatter", "fma_gemm"]
+    g_names = (["bucket_prep", "mfma_gemm", "splitk_reduce"] if fc_mfma else
+               ["bucket_prep", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
     grad_ms = float(g_med.sum())
 
@@ -204,12 +207,12 @@ def main():
             "dw_kernels_ms": dict(zip(g_names, [float(v) for v in g_med])),
         },
         "roofline": {
-            "kernel": "fc_mfma_kernel" if fc_mfma else "fma kernel",
-            "bound": "mfma" if fc_mfma else "alu",
+            "kernel": "fc_mfma_kernel" if fc_mfma else "conv3x3_mfma_kernel" if conv_mfma else "fma kernel",
+            "bound": "mfma" if mfma else "alu",
             "achieved": dw_tflops_kernel,
-            "peak": MFMA_BF16_PEAK_TFLOPS if fc_mfma else 157.3,
+            "peak": MFMA_BF16_PEAK_TFLOPS if mfma else 157.3,
             "unit": "TFLOP/s",
-            "frac": dw_tflops_kernel / (MFMA_BF16_PEAK_TFLOPS if fc_mfma else 157.3),
+            "frac": dw_tflops_kernel / (MFMA_BF16_PEAK_TFLOPS if mfma else 157.3),
             "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "dw")),
             "avg_kernel_ms": main_ms,
         },

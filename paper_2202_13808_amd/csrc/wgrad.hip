@@ -192,6 +192,10 @@ static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
         if (fc_mfma_supported(fp)) return fc_mfma_plan(fp).total();
     }
+    if (p.conv && dt == DROPIT_BF16) {
+        const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
+        if (conv_mfma_supported(cp)) return conv_mfma_plan(cp).total();
+    }
     return dense_bytes(p, dt);
 }
 
@@ -224,6 +228,10 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
     if (!p.conv && dt == DROPIT_BF16 && k > 0) {
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
         if (fc_mfma_supported(fp)) return fc_mfma_run(fp, fc_mfma_plan(fp), vals, idx, dY, dW, ws, stream);
+    }
+    if (p.conv && dt == DROPIT_BF16 && k > 0) {
+        const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
+        if (conv_mfma_supported(cp)) return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
     }
     if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
     return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);

@@ -203,23 +203,8 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
     // range re-read the last pair of the whole stream (ignored at scatter time).
     const int64_t tok_last = ntok - 1;
     const uint32_t pair_last = uint32_t(n_pairs - 1);
-    // L2 warm-up: one dword per 128-byte line of the dY block PF_DIST steps ahead.  The
-    // value is never used; the register stays live across the loop so that the late
-    // write cannot land in a reused register, and is drained after the loop.
-    uint32_t touch = 0;
-    auto touch_step = [&](int kb) {
-        constexpr int LINES = BK * (BM * 2 / 128);
-        const int row = (tid % LINES) / (BM * 2 / 128), line = tid % (BM * 2 / 128);
-        const int64_t tok = min(int64_t(kb) * BK + row, tok_last);
-        const int m = min(m0 + line * 64, M - 8);
-        const uint16_t *p = dY + tok * M + m;
-        asm volatile("global_load_dword %0, %1, off" : "+v"(touch) : "v"(p) : "memory");
-    };
     auto load_step = [&](Stage &st, int kb) {
         if (DROPIT_ABLATE & 1) return;
-#ifdef DROPIT_PF_DIST
-        touch_step(min(kb + DROPIT_PF_DIST, kb_end - 1));
-#endif
         const int64_t tok0 = int64_t(kb) * BK;
 #pragma unroll
         for (int i = 0; i < C::A_VECS; ++i) {
@@ -357,9 +342,6 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
         }
     }
 
-#ifdef DROPIT_PF_DIST
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(touch) : : "memory");
-#endif
     // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block
     float *dst = out + int64_t(split) * M * N;
 #pragma unroll

@@ -23,4 +23,20 @@ FcPlan fc_mfma_plan(const FcProblem &p);
 dropit_status fc_mfma_run(const FcProblem &p, const FcPlan &plan, const void *vals, const int32_t *idx,
                           const void *dY, float *dW, char *ws, hipStream_t stream);
 
+struct ConvProblem {
+    int64_t N, C, H, W, J, k;
+};
+
+struct ConvPlan {
+    int cb_count, jb_count, bands, rb, pitch_c;
+    size_t lds_bytes, packed_bytes, rowptr_bytes, partial_bytes;
+    size_t total() const { return packed_bytes + rowptr_bytes + partial_bytes; }
+};
+
+// bf16 3x3/s1/p1 convolution weight gradient on the matrix cores (wgrad_conv_mfma.hip)
+bool conv_mfma_supported(const ConvProblem &p);
+ConvPlan conv_mfma_plan(const ConvProblem &p);
+dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const void *vals, const int32_t *idx,
+                            const void *dY, float *dW, char *ws, hipStream_t stream);
+
 }  // namespace dropit
