@@ -22,6 +22,7 @@
 // Nothing here synchronises with the host; counts are integer, so the result
 // does not depend on the order in which workgroups run.
 #include "common.hpp"
+#include <type_traits>
 
 namespace dropit {
 namespace {
@@ -38,7 +39,9 @@ struct SelState {
     uint32_t t;          // threshold key (valid after the count pass)
     uint32_t m;          // how many keys equal to t are kept (lowest flat index first)
     uint32_t ticket[4];  // arrival counters, one per pass
-    uint32_t pad[56];
+    uint32_t barrier;    // arrivals at the fused kernel's grid barriers (monotone within a call)
+    uint32_t error;      // set if a grid barrier ran out of patience (results are then invalid)
+    uint32_t pad[54];
 };
 static_assert(sizeof(SelState) == 256, "state block is 256 bytes");
 
@@ -65,12 +68,14 @@ template <> struct KeyTraits<uint32_t> {
 };
 
 // Calls f(raw_bits, e) for the VEC elements of one 16-byte vector, e ascending.
-template <typename F> __device__ inline void for_each_raw(uint16_t, const uint4 &q, F f)
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;   // plain register vector (no class wrapper)
+
+template <typename V, typename F> __device__ inline void for_each_raw(uint16_t, const V &q, F f)
 {
     f(q.x & 0xFFFFu, 0); f(q.x >> 16, 1); f(q.y & 0xFFFFu, 2); f(q.y >> 16, 3);
     f(q.z & 0xFFFFu, 4); f(q.z >> 16, 5); f(q.w & 0xFFFFu, 6); f(q.w >> 16, 7);
 }
-template <typename F> __device__ inline void for_each_raw(uint32_t, const uint4 &q, F f)
+template <typename V, typename F> __device__ inline void for_each_raw(uint32_t, const V &q, F f)
 {
     f(q.x, 0); f(q.y, 1); f(q.z, 2); f(q.w, 3);
 }
@@ -377,6 +382,330 @@ compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vp
     }
 }
 
+// ---------------------------------------------------------------------------
+// Fused path: the whole select + compaction as ONE cooperative kernel with one
+// workgroup per compute unit.  Each workgroup parks the first FUSED_RES x 16 KB of its
+// chunk in LDS across all phases (the whole chunk for tensors up to ~25 MB; anything
+// beyond is re-read, mostly from the Infinity Cache), and the phases are separated by
+// grid barriers instead of kernel boundaries.  Loops over the parked vectors are rolled
+// on purpose: unrolling them 8x made the kernel 48 KB of code and instruction-fetch bound.  Every workgroup resolves the digits itself
+// from the merged histogram, so the select state lives in registers.
+//
+// Everything workgroups exchange (histogram, per-chunk table, barrier counter) is
+// accessed ONLY with device-scope atomics, which are coherent by themselves, so no
+// device-wide fence is needed: on this 8-XCD part such a fence writes back and
+// invalidates a whole L2 and was measured at 5-8 us per grid barrier.
+constexpr int FUSED_RES = 6;             // 16-byte vectors per thread parked in LDS
+constexpr uint32_t SPIN_LIMIT = 1u << 22;   // grid-barrier patience; every wave exits even if it runs out
+
+__device__ inline uint32_t dev_load(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void dev_store(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// All workgroups of the (cooperatively launched, hence co-resident) grid meet here.
+// __syncthreads() makes every wave wait for its own outstanding atomics first.
+__device__ inline void grid_barrier(SelState *st, uint32_t target)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t spins = 0;
+        while (dev_load(&st->barrier) < target) {
+            if (++spins > SPIN_LIMIT) {
+                dev_store(&st->error, 1u);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    __syncthreads();
+}
+
+// Finds the digit d with #{digit > d} < k_rem <= #{digit >= d} in the merged histogram
+// and folds it into the workgroup's copy of the select state.  Thread t owns the bins
+// of reversed rank t, so an ordinary exclusive prefix scan counts the keys above it.
+template <int NB, int BITS>
+__device__ inline void resolve_digit_local(const uint32_t *hist, uint32_t &prefix, uint32_t &k_rem,
+                                           uint32_t *wave_tot, uint32_t *bcast /*[2]*/)
+{
+    constexpr int PER = (NB + SEL_THREADS - 1) / SEL_THREADS;
+    const int tid = threadIdx.x;
+    const int hi_bin = NB - 1 - tid * PER;           // this thread's highest bin; it owns hi_bin, hi_bin-1, ...
+    uint32_t c[PER];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        c[i] = (hi_bin - i >= 0) ? dev_load(hist + hi_bin - i) : 0u;
+        mine += c[i];
+    }
+    uint32_t total;
+    uint32_t above = block_exclusive_scan<SEL_THREADS>(mine, wave_tot, total);
+    if (above < k_rem && k_rem <= above + mine) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (above + c[i] >= k_rem) {
+                bcast[0] = (prefix << BITS) | static_cast<uint32_t>(hi_bin - i);
+                bcast[1] = k_rem - above;
+                break;
+            }
+            above += c[i];
+        }
+    }
+    __syncthreads();
+    prefix = bcast[0];
+    k_rem = bcast[1];
+    __syncthreads();
+}
+
+template <typename RAW>
+__global__ void __launch_bounds__(SEL_THREADS)
+select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k, SelState *st,
+                    uint32_t *hist0, uint32_t *hist1, uint32_t *table, RAW *__restrict__ vals,
+                    int32_t *__restrict__ idx)
+{
+    constexpr int VEC = KeyTraits<RAW>::VEC;
+    constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
+    constexpr bool F32 = sizeof(RAW) == 4;
+    constexpr int BITS1 = F32 ? 13 : 11, SHIFT1 = F32 ? 18 : 4;   // first digit
+    constexpr int BITS2 = 13, SHIFT2 = 5;                         // second digit (fp32 only)
+    constexpr int LAST_BITS = F32 ? 5 : 4;
+    constexpr int LB = 1 << LAST_BITS;
+    constexpr int NW = SEL_THREADS / WAVE;
+    constexpr int TILE = SEL_THREADS * VEC;                       // elements per compaction tile
+    // The histogram and the compaction staging buffers share storage: never live together.
+    extern __shared__ __attribute__((aligned(16))) u32x4 dyn_smem[];
+    u32x4 *res = dyn_smem;                                            // [FUSED_RES][SEL_THREADS]
+    uint32_t *smem = reinterpret_cast<uint32_t *>(dyn_smem + FUSED_RES * SEL_THREADS);
+    uint32_t *lh = smem;
+    int32_t *stage_idx = reinterpret_cast<int32_t *>(smem);
+    RAW *stage_val = reinterpret_cast<RAW *>(smem + TILE);
+    __shared__ uint32_t bcast[4];
+    __shared__ uint32_t wave_tot[NW];
+    __shared__ unsigned long long wave_tot64[NW];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int G = gridDim.x;
+    const bool last_chunk = blockIdx.x == gridDim.x - 1;
+    const u32x4 *xv = reinterpret_cast<const u32x4 *>(x);
+    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
+    const int64_t v1 = min(v0 + vpc, nvf);
+
+    // ---- park the head of the chunk in LDS (each thread only ever reads its own slots) --
+    const int nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
+    if (nvf > 0) {
+        u32x4 q[FUSED_RES];
+#pragma unroll
+        for (int i = 0; i < FUSED_RES; ++i)     // unconditional, clamped: all loads in flight at once
+            q[i] = xv[min(v0 + int64_t(i) * SEL_THREADS + tid, nvf - 1)];
+#pragma unroll
+        for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
+    }
+    const int64_t v_stream = v0 + int64_t(nres) * SEL_THREADS;        // first vector that is not parked
+    // visits every element of the chunk: f(raw bits)
+    auto for_chunk = [&](auto f) {
+        for (int i = 0; i < nres; ++i) {
+            const int64_t v = v0 + int64_t(i) * SEL_THREADS + tid;
+            if (v < v1) for_each_raw(RAW(0), res[i * SEL_THREADS + tid], [&](uint32_t raw, int) { f(raw); });
+        }
+        int64_t vb = v_stream;
+        for (; vb + SEL_THREADS * SEL_UNROLL <= v1; vb += SEL_THREADS * SEL_UNROLL) {
+            u32x4 q[SEL_UNROLL];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) q[u] = xv[vb + u * SEL_THREADS + tid];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) for_each_raw(RAW(0), q[u], [&](uint32_t raw, int) { f(raw); });
+        }
+        for (int64_t v = vb + tid; v < v1; v += SEL_THREADS)
+            for_each_raw(RAW(0), xv[v], [&](uint32_t raw, int) { f(raw); });
+        if (last_chunk && tid == 0)
+            for (int64_t i = nvf * VEC; i < numel; ++i) f(x[i]);
+    };
+
+    uint32_t prefix = 0, k_rem = k;
+    uint32_t barriers = 0;
+#ifdef DROPIT_TUNING
+    int stamp_i = 0;
+#define STAMP() do { if (tid == 0 && blockIdx.x == gridDim.x / 2) reinterpret_cast<unsigned long long *>(st->pad + 6)[stamp_i] = wall_clock64(); ++stamp_i; } while (0)
+#else
+#define STAMP() do { } while (0)
+#endif
+    STAMP();
+
+    // ---- digit histograms ---------------------------------------------------------
+    auto hist_pass = [&](auto shift_c, auto bits_c, auto first_c, uint32_t *ghist) {
+        constexpr int SHIFT = decltype(shift_c)::value, BITS = decltype(bits_c)::value;
+        constexpr bool FIRST = decltype(first_c)::value;
+        constexpr int NB = 1 << BITS;
+        for (int i = tid; i < NB + 2 * WAVE; i += SEL_THREADS) lh[i] = 0;
+        __syncthreads();
+        const uint32_t zslot = NB + lane, dslot = NB + WAVE + lane;
+        for_chunk([&](uint32_t raw) {
+            const uint32_t key = raw & MASK;
+            const uint32_t d = (key >> SHIFT) & (NB - 1);
+            uint32_t a = d ? d : zslot;
+            if (!FIRST) a = ((key >> (SHIFT + BITS)) == prefix) ? a : dslot;
+            atomicAdd(&lh[a], 1u);
+        });
+        __syncthreads();
+        if (tid < WAVE) {
+            const uint32_t z = wave_sum(lh[NB + tid]);
+            if (tid == 0) lh[0] += z;
+        }
+        __syncthreads();
+        for (int i = tid; i < NB; i += SEL_THREADS) {
+            const uint32_t c = lh[i];
+            if (c) atomicAdd(&ghist[i], c);
+        }
+        STAMP();
+        grid_barrier(st, ++barriers * G);
+        STAMP();
+        resolve_digit_local<NB, BITS>(ghist, prefix, k_rem, wave_tot, bcast);
+        STAMP();
+    };
+    hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{}, std::true_type{}, hist0);
+    if constexpr (F32)
+        hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{}, std::false_type{}, hist1);
+
+    // ---- last digit and per-chunk counts -------------------------------------------
+    for (int i = tid; i < LB + 1 + WAVE; i += SEL_THREADS) lh[i] = 0;
+    __syncthreads();
+    {
+        const uint32_t dslot = LB + 1 + lane;
+        uint32_t above = 0;
+        for_chunk([&](uint32_t raw) {
+            const uint32_t key = raw & MASK;
+            const uint32_t hi = key >> LAST_BITS;
+            above += (hi > prefix) ? 1u : 0u;
+            atomicAdd(&lh[(hi == prefix) ? (key & (LB - 1)) : dslot], 1u);
+        });
+        above = wave_sum(above);
+        if (lane == 0 && above) atomicAdd(&lh[LB], above);
+    }
+    __syncthreads();
+    if (tid <= LB) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
+    STAMP();
+    grid_barrier(st, ++barriers * G);
+    STAMP();
+
+    for (int b = tid / WAVE; b < LB; b += NW) {      // totals per bin over all chunks
+        uint32_t s = 0;
+        for (int c = lane; c < G; c += WAVE) s += dev_load(&table[b * G + c]);
+        s = wave_sum(s);
+        if (lane == 0) lh[b] = s;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t acc = 0;
+        int d = 0;
+        for (int b = LB - 1; b >= 0; --b) {
+            if (acc + lh[b] >= k_rem) { d = b; break; }
+            acc += lh[b];
+        }
+        bcast[0] = (prefix << LAST_BITS) | static_cast<uint32_t>(d);
+        bcast[1] = k_rem - acc;
+        bcast[2] = static_cast<uint32_t>(d);
+    }
+    __syncthreads();
+    const uint32_t t = bcast[0], m = bcast[1];
+    const int d = static_cast<int>(bcast[2]);
+    // exclusive offsets of this chunk: sums over the chunks before it
+    unsigned long long mine = 0;
+    for (int c = tid; c < static_cast<int>(blockIdx.x); c += SEL_THREADS) {
+        uint32_t n[LB + 1];
+#pragma unroll
+        for (int b = 0; b <= LB; ++b) n[b] = dev_load(&table[b * G + c]);
+        uint32_t g = n[LB], e = 0;
+#pragma unroll
+        for (int b = 0; b < LB; ++b) {
+            g += (b > d) ? n[b] : 0u;
+            e = (b == d) ? n[b] : e;
+        }
+        mine += (static_cast<unsigned long long>(e) << 32) | g;
+    }
+    unsigned long long before;
+    (void)block_exclusive_scan<SEL_THREADS>(mine, wave_tot64, before);
+    uint32_t run_gt = static_cast<uint32_t>(before & 0xFFFFFFFFull);   // #{key > t} before this chunk
+    uint32_t run_eq = static_cast<uint32_t>(before >> 32);             // #{key == t} before this chunk
+    STAMP();
+
+    // ---- ordered compaction -------------------------------------------------------
+    // The kept elements of a tile occupy consecutive output slots; they are gathered in
+    // LDS first so that the global stores are contiguous.
+    auto keep = [&](uint32_t pos, uint32_t raw, int64_t i) {
+        if (pos < k) {                     // always true unless a grid barrier gave up
+            vals[pos] = static_cast<RAW>(raw);
+            idx[pos] = static_cast<int32_t>(i);
+        }
+    };
+    auto emit_tile = [&](const u32x4 &q, int64_t v, bool live) {
+        uint32_t cnt = 0;
+        for_each_raw(RAW(0), q, [&](uint32_t raw, int) {
+            const uint32_t key = raw & MASK;
+            cnt += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
+        });
+        if (!live) cnt = 0;
+        uint32_t total;
+        const uint32_t excl = block_exclusive_scan<SEL_THREADS>(cnt, wave_tot, total);
+        const uint32_t tile_first = run_gt + min(run_eq, m);           // output slot of the tile's first kept element
+        uint32_t my_gt = run_gt + (excl & 0xFFFFu);
+        uint32_t my_eq = run_eq + (excl >> 16);
+        const int64_t base = v * VEC;
+        if (cnt) {
+            // a kept element (key > t, or one of the first m keys == t) goes to output slot
+            // #gt-before + min(#eq-before, m): one formula for both cases
+            for_each_raw(RAW(0), q, [&](uint32_t raw, int e) {
+                const uint32_t key = raw & MASK;
+                const bool gt = key > t, eq = key == t;
+                const uint32_t slot = my_gt + min(my_eq, m) - tile_first;
+                if (gt || (eq && my_eq < m)) {
+                    stage_val[slot] = static_cast<RAW>(raw);
+                    stage_idx[slot] = static_cast<int32_t>(base + e);
+                }
+                my_gt += gt ? 1u : 0u;
+                my_eq += eq ? 1u : 0u;
+            });
+        }
+        run_gt += total & 0xFFFFu;
+        run_eq += total >> 16;
+        const uint32_t tile_kept = run_gt + min(run_eq, m) - tile_first;
+        __syncthreads();
+        for (uint32_t s = tid; s < tile_kept; s += SEL_THREADS)
+            if (tile_first + s < k) {      // always true unless a grid barrier gave up
+                vals[tile_first + s] = stage_val[s];
+                idx[tile_first + s] = stage_idx[s];
+            }
+        // the next tile's scan starts with a barrier, which also protects the staging buffers
+    };
+    __syncthreads();                       // histogram storage becomes staging storage
+    for (int64_t vb = v0, i = 0; vb < v1; vb += SEL_THREADS, ++i) {
+        const int64_t v = vb + tid;
+        const bool live = v < v1;
+        u32x4 q = u32x4{0, 0, 0, 0};
+        if (i < nres) q = res[i * SEL_THREADS + tid];
+        else if (live) q = xv[v];
+        emit_tile(q, v, live);
+    }
+    STAMP();
+    if (last_chunk && tid == 0) {
+        for (int64_t i = nvf * VEC; i < numel; ++i) {
+            const RAW raw = x[i];
+            const uint32_t key = raw & MASK;
+            if (key > t) {
+                keep(run_gt + min(run_eq, m), raw, i);
+                ++run_gt;
+            } else if (key == t) {
+                if (run_eq < m) keep(run_gt + run_eq, raw, i);
+                ++run_eq;
+            }
+        }
+    }
+#undef STAMP
+}
+
 struct Geometry {
     int64_t nvf, vpc;      // full 16-byte vectors, vectors per chunk
     int chunks;
@@ -416,6 +745,52 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
     init_kernel<<<32, 256, 0, stream>>>(reinterpret_cast<uint32_t *>(ws),
                                         static_cast<uint32_t>(SelWorkspace::zero_bytes / 4),
                                         static_cast<uint32_t>(k));
+    // Preferred: one cooperative kernel, one workgroup per compute unit.
+    {
+        static int cus = 0;
+        if (cus == 0) {
+            hipDeviceProp_t prop;
+            int dev = 0;
+            if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+                cus = prop.multiProcessorCount;
+            if (cus <= 0 || cus > SEL_MAX_CHUNKS) cus = cus > SEL_MAX_CHUNKS ? SEL_MAX_CHUNKS : -1;
+        }
+        if (cus > 0) {
+            constexpr int VEC = KeyTraits<RAW>::VEC;
+            int64_t nvf = numel / VEC;
+            int64_t chunks = (nvf + SEL_THREADS - 1) / SEL_THREADS;
+            if (chunks > cus) chunks = cus;
+            if (chunks < 1) chunks = 1;
+            int64_t vpc = (nvf + chunks - 1) / chunks;
+            vpc = (vpc + 7) / 8 * 8;
+            if (vpc < 8) vpc = 8;
+            chunks = (nvf + vpc - 1) / vpc;
+            if (chunks < 1) chunks = 1;
+            uint32_t k32 = static_cast<uint32_t>(k);
+            RAW *vals_t = static_cast<RAW *>(vals);
+            void *args[] = {(void *)&xr, (void *)&numel, (void *)&nvf, (void *)&vpc, (void *)&k32, (void *)&st,
+                            (void *)&hist0, (void *)&hist1, (void *)&table, (void *)&vals_t, (void *)&idx};
+            trace_mark(stream);
+            constexpr int TILE_WORDS = SEL_THREADS * VEC + SEL_THREADS * VEC * int(sizeof(RAW)) / 4;
+            constexpr int HIST_WORDS = (sizeof(RAW) == 4 ? (1 << 13) : (1 << 11)) + 2 * WAVE;
+            constexpr size_t smem_bytes = size_t(FUSED_RES) * SEL_THREADS * 16 +
+                                          4 * size_t(TILE_WORDS > HIST_WORDS ? TILE_WORDS : HIST_WORDS);
+            static bool attr_set = false;
+            if (!attr_set) {
+                attr_set = hipFuncSetAttribute(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               static_cast<int>(smem_bytes)) == hipSuccess;
+            }
+            if (attr_set &&
+                hipLaunchCooperativeKernel(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
+                                           dim3(static_cast<unsigned>(chunks)), dim3(SEL_THREADS), args,
+                                           smem_bytes, stream) == hipSuccess) {
+                trace_mark(stream);
+                return launch_status();
+            }
+            (void)hipGetLastError();       // cooperative launch unavailable (e.g. stream capture): separate kernels
+        }
+    }
     const dim3 grid(g.chunks), block(SEL_THREADS);
     trace_mark(stream);
     if constexpr (sizeof(RAW) == 2) {
