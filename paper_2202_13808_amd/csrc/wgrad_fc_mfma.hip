@@ -195,29 +195,37 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
         }
     }
 
-    // Branch-free on purpose: every load is issued unconditionally from a clamped,
-    // valid address, so the compiler can count exactly how many newer loads may stay in
-    // flight when an older stage is consumed.  Rows past the last token re-read the last
-    // token (their a^ rows are zero, so they add nothing), columns past M re-read valid
-    // columns (those outputs are never stored), pair slots past the end of the tile's
-    // range re-read the last pair of the whole stream (ignored at scatter time).
-    const int64_t tok_last = ntok - 1;
-    const uint32_t pair_last = uint32_t(n_pairs - 1);
+    // Branch-free on purpose: every load is issued unconditionally from a valid address, so
+    // the compiler can count exactly how many newer loads may stay in flight when an older
+    // stage is consumed.  Rows past the last token re-read the last token (their a^ rows are
+    // zero, so they add nothing), columns past M re-read valid columns (those outputs are never
+    // stored), pair slots past the end of the tile's range read into the slack the packed buffer
+    // ends with (ignored at scatter time).
+    // Addresses are a per-step scalar base plus a per-thread 32-bit offset computed once, so a
+    // step issues its loads without any vector address arithmetic.
+    uint32_t a_off[C::A_VECS], a_off_tail[C::A_VECS];   // byte offsets inside a token block
+    const int kb_tail = int((ntok - 1) / BK);           // the (possibly partial) last token block
+    const int rows_tail = int(ntok - int64_t(kb_tail) * BK);
+#pragma unroll
+    for (int i = 0; i < C::A_VECS; ++i) {
+        const int vv = tid + i * NT;
+        const int row = vv / (BM / 8), cv = vv % (BM / 8);
+        const int m = min(m0 + cv * 8, M - 8);
+        a_off[i] = uint32_t(row * M + m) * 2u;
+        a_off_tail[i] = uint32_t(min(row, rows_tail - 1) * M + m) * 2u;
+    }
     auto load_step = [&](Stage &st, int kb) {
         if (DROPIT_ABLATE & 1) return;
-        const int64_t tok0 = int64_t(kb) * BK;
+        const char *abase = reinterpret_cast<const char *>(dY) + int64_t(kb) * BK * M * 2;
+        const bool tail = kb == kb_tail;
 #pragma unroll
-        for (int i = 0; i < C::A_VECS; ++i) {
-            const int vv = tid + i * NT;
-            const int row = vv / (BM / 8), cv = vv % (BM / 8);
-            const int64_t tok = min(tok0 + row, tok_last);
-            const int m = min(m0 + cv * 8, M - 8);
-            st.a[i] = *reinterpret_cast<const u32x4 *>(dY + tok * M + m);
-        }
+        for (int i = 0; i < C::A_VECS; ++i)
+            st.a[i] = *reinterpret_cast<const u32x4 *>(abase + (tail ? a_off_tail[i] : a_off[i]));
         st.lo = tile_ptr[int64_t(kb) * (nb_count + 1) + nb];
         st.hi = tile_ptr[int64_t(kb) * (nb_count + 1) + nb + 1];
+        const uint32_t *pbase = packed + st.lo;
 #pragma unroll
-        for (int i = 0; i < C::ENT; ++i) st.e[i] = packed[min(st.lo + tid + i * NT, pair_last)];
+        for (int i = 0; i < C::ENT; ++i) st.e[i] = pbase[uint32_t(tid + i * NT)];
     };
     // What was scattered into a B buffer, kept until the buffer is cleared again.
     struct Dirty {
@@ -371,15 +379,15 @@ splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int splits,
 }
 
 #ifndef DROPIT_FC_CFG
-#define DROPIT_FC_CFG 256, 256, 32, 2, 4, 2, 2
+#define DROPIT_FC_CFG 256, 128, 32, 2, 2, 2, 2
 #endif
 using Cfg = FcCfg<DROPIT_FC_CFG>;
 
 int tuned_splits(int tiles, int nkb)
 {
-    // one workgroup per compute unit (a tile's LDS footprint allows no more): as many
-    // K-slices as fill the 256 compute units without starting a second round
-    int splits = 256 / tiles;
+    // two workgroups per compute unit (LDS and registers allow exactly two): as many K-slices
+    // as fill 2 x 256 slots without starting a second round
+    int splits = 512 / tiles;
 #ifdef DROPIT_TUNING
     if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
 #endif
@@ -404,7 +412,8 @@ FcPlan fc_mfma_plan(const FcProblem &p)
     plan.nb_count = int((p.cin + Cfg::BN - 1) / Cfg::BN);
     plan.mb_count = int((p.cout + Cfg::BM - 1) / Cfg::BM);
     plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
-    plan.packed_bytes = round_up(size_t(p.k > 0 ? p.k : 1) * 4, 256);
+    // slack: a step may read up to ENT * NTHREADS pair slots past the end of its range
+    plan.packed_bytes = round_up(size_t(p.k > 0 ? p.k : 1) * 4 + size_t(Cfg::ENT) * Cfg::NTHREADS * 4, 256);
     plan.tileptr_bytes = round_up(size_t(plan.nkb) * (plan.nb_count + 1) * 4, 256);
     plan.partial_bytes = plan.splits > 1 ? round_up(size_t(plan.splits) * p.cout * p.cin * 4, 256) : 0;
     return plan;
