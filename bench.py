@@ -26,9 +26,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
-# HBM traffic per launch of the dominant kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled
+# by what the same counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0); see
+# profiles/fc_mfma_select_fused_vitb_fc1_hbm_traffic.txt.  None for workloads that were not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("vitb_fc1", "dw"): int((43654.6 * 2.0 + 64512.0) * 1024),       # fc_mfma_kernel: 89.4 MB read + 66.1 MB written
+    ("vitb_fc1", "hist"): int((12509.5 * 2.0 + 5983.8) * 1024),      # select_fused_kernel: 25.6 MB read + 6.1 MB written
+}
 
 
 def parse_args():
@@ -38,6 +42,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vitb_fc1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cold", action="store_true",
                     help="rotate over several input copies so that x / dY never sit in the Infinity Cache")
     return ap.parse_args()
@@ -136,6 +142,14 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
+
+    if args.copy_calibration:
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- per-call and per-kernel durations with HIP events on the launch stream ----
     n_meas = min(args.steps, 50)
