@@ -66,13 +66,19 @@ def cpu_baseline(w, flops_per_step):
     t_compress = time.perf_counter() - t0
     xh = oracle.densify(vals, idx, x.shape)
     dyw = oracle.widen(dy)
-    rows = min(w.c_out, 2 * oracle.num_threads())
-    t0 = time.perf_counter()
-    if w.conv is None:
-        oracle.dw_fc(xh, dyw, 0, rows)
-    else:
-        oracle.dw_conv(xh, dyw, w.conv[0], w.conv[1], (w.conv[2],) * 2, (w.conv[3],) * 2, (1, 1), 0, rows)
-    t_rows = time.perf_counter() - t0
+    def run_rows(r0, r1):
+        t0 = time.perf_counter()
+        if w.conv is None:
+            oracle.dw_fc(xh, dyw, r0, r1)
+        else:
+            oracle.dw_conv(xh, dyw, w.conv[0], w.conv[1], (w.conv[2],) * 2, (w.conv[3],) * 2, (1, 1), r0, r1)
+        return time.perf_counter() - t0
+
+    probe_rows = min(w.c_out, 2 * oracle.num_threads())
+    t_probe = run_rows(0, probe_rows)
+    # then as many output rows as fit in about ten seconds of CPU time (all of them if possible)
+    rows = int(min(w.c_out, max(probe_rows, probe_rows * 10.0 / max(t_probe, 1e-6))))
+    t_rows = run_rows(0, rows) if rows > probe_rows else t_probe
     t_step = t_compress + t_rows * (w.c_out / rows)
     return {
         "value": flops_per_step / t_step * 1e-12,
@@ -159,6 +165,15 @@ def main():
         for e in evs:
             e.record()
     torch.cuda.synchronize()
+    # An event pair with nothing between them still reads a few microseconds (the marks are barrier
+    # packets on the queue).  Measure that on the same stream and take it out of every interval, so the
+    # per-kernel figures agree with a rocprofv3 kernel trace.
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(65)]
+    dropit.compress(xs[0], w.gamma, vals=vals, idx=idx, workspace=ws_c)   # keep the queue busy ahead of the marks
+    for e in pe:
+        e.record()
+    torch.cuda.synchronize()
+    event_overhead_ms = float(np.median(event_ms(pe)))
     n_c = n_g = 0
     for i in range(n_meas):
         x, dy = xs[i % copies], dys[i % copies]
@@ -176,8 +191,8 @@ def main():
     conv_mfma = bf16 and w.conv is not None and w.x_shape[3] % 8 == 0
     mfma = fc_mfma or conv_mfma
     n_g = 4 if mfma else 3                   # prep, gemm, reduce, end  |  zero+scatter, gemm, end
-    c_ms = np.array([event_ms(e[:n_c]) for e in ce])          # [n_meas, n_c-1]
-    g_ms = np.array([event_ms(e[:n_g]) for e in ge])
+    c_ms = np.maximum(np.array([event_ms(e[:n_c]) for e in ce]) - event_overhead_ms, 0.0)   # [n_meas, n_c-1]
+    g_ms = np.maximum(np.array([event_ms(e[:n_g]) for e in ge]) - event_overhead_ms, 0.0)
     c_med = np.median(c_ms, axis=0)
     g_med = np.median(g_ms, axis=0)
     c_names = (["init", "select_fused"] if fused_select else
@@ -212,6 +227,7 @@ def main():
         "config": {"workload": "%s: x %s %s gamma=%.2f, dY %s, dW %s fp32%s" % (
             w.name, w.dtype, list(w.x_shape), w.gamma, list(w.dy_shape), list(w.dw_shape),
             " (cold: %d rotating input copies)" % copies if args.cold else " (inputs warm in Infinity Cache)")},
+        "event_overhead_ms": event_overhead_ms,
         "halves": {
             "compress_GBps": compress_bytes / (compress_ms * 1e-3) * 1e-9,
             "compress_pct_hbm_peak": 100.0 * compress_bytes / (compress_ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS,

@@ -136,13 +136,23 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
                                  void *hip_stream);
 
 /*
+ * dropit_compress runs, when it can, as a single cooperative kernel (one workgroup per
+ * compute unit, grid barriers between its phases).  Cooperative launches cannot be
+ * recorded into a HIP graph; a caller that captures the stream selects mode 1, which runs
+ * the same select as separate ordinary kernels (no memset nodes).  Mode 0 (default) tries
+ * the cooperative kernel first and falls back to mode 1 if that launch is refused.
+ * The setting is per host thread.  Returns DROPIT_EINVAL for any other mode.
+ */
+dropit_status dropit_set_select_mode(int mode);
+
+/*
  * Measurement aid (not part of the method): per-kernel timing marks.
  * `events` is a HOST array of `count` hipEvent_t handles created by the caller.
  * The next dropit_compress / dropit_weight_grad call made from this host thread
  * records events[0] before its first kernel, events[i] before its (i+1)-th
  * kernel and one after its last, on the call's stream, until the array is
  * used up.  Pass (NULL, 0) to switch it off.  The handles stay owned by the
- * caller; this per-thread setting is the only state the library keeps.
+ * caller; these per-thread settings are the only state the library keeps.
  */
 void dropit_trace_events(void **events, int count);
 

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     keep_count,
     lib,
     lib_path,
+    set_select_mode,
     trace_events,
     weight_grad,
     weight_grad_workspace_bytes,

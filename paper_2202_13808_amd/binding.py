@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.dropit_compress.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp, sz, vp]
         L.dropit_weight_grad_workspace_bytes.restype = sz
         L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
+        L.dropit_set_select_mode.restype = i32
+        L.dropit_set_select_mode.argtypes = [i32]
         L.dropit_trace_events.restype = None
         L.dropit_trace_events.argtypes = [ctypes.POINTER(vp), i32]
         L.dropit_weight_grad.restype = i32
@@ -178,6 +180,12 @@ def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], d
             ctypes.byref(cs) if cs is not None else None, dW.data_ptr(),
             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dW
+
+
+def set_select_mode(mode: int) -> None:
+    """dropit_set_select_mode: 0 = cooperative fused select when possible (default),
+    1 = separate ordinary kernels (the form that can be captured into a HIP graph)."""
+    _check(lib().dropit_set_select_mode(int(mode)))
 
 
 def trace_events(events: Optional[Sequence[torch.cuda.Event]]) -> None:

@@ -46,6 +46,9 @@ inline void trace_mark(hipStream_t stream)
     if (t.next < t.count) (void)hipEventRecord(t.events[t.next++], stream);
 }
 
+// 0 = cooperative fused select when possible, 1 = separate kernels (see dropit_set_select_mode)
+int &select_mode();                              // per host thread; defined in compress.hip
+
 // ---- wave / block primitives (64-wide wavefronts) -----------------------
 
 __device__ inline uint32_t wave_sum(uint32_t v)

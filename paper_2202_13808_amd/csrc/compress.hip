@@ -755,7 +755,7 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
                 cus = prop.multiProcessorCount;
             if (cus <= 0 || cus > SEL_MAX_CHUNKS) cus = cus > SEL_MAX_CHUNKS ? SEL_MAX_CHUNKS : -1;
         }
-        if (cus > 0) {
+        if (cus > 0 && select_mode() == 0) {
             constexpr int VEC = KeyTraits<RAW>::VEC;
             int64_t nvf = numel / VEC;
             int64_t chunks = (nvf + SEL_THREADS - 1) / SEL_THREADS;
@@ -820,7 +820,20 @@ dropit::TraceState &dropit::trace_state()
     return t;
 }
 
+int &dropit::select_mode()
+{
+    static thread_local int mode = 0;
+    return mode;
+}
+
 using namespace dropit;
+
+extern "C" dropit_status dropit_set_select_mode(int mode)
+{
+    if (mode != 0 && mode != 1) return DROPIT_EINVAL;
+    select_mode() = mode;
+    return DROPIT_OK;
+}
 
 extern "C" void dropit_trace_events(void **events, int count)
 {

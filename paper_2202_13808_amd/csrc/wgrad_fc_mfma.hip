@@ -187,7 +187,7 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
     };
     constexpr int R = C::STAGES;
     Stage st[R];
-    if (DROPIT_ABLATE & 1) {                  // keep the registers defined when loads are left out
+    if (DROPIT_ABLATE & (1 | 16 | 32)) {      // keep the registers defined when loads are left out
         for (int r = 0; r < R; ++r) {
             st[r].lo = st[r].hi = 0;
             for (int i = 0; i < C::A_VECS; ++i) st[r].a[i] = u32x4{0, 0, 0, 0};
@@ -218,9 +218,12 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
         if (DROPIT_ABLATE & 1) return;
         const char *abase = reinterpret_cast<const char *>(dY) + int64_t(kb) * BK * M * 2;
         const bool tail = kb == kb_tail;
+        if (!(DROPIT_ABLATE & 16)) {
 #pragma unroll
-        for (int i = 0; i < C::A_VECS; ++i)
-            st.a[i] = *reinterpret_cast<const u32x4 *>(abase + (tail ? a_off_tail[i] : a_off[i]));
+            for (int i = 0; i < C::A_VECS; ++i)
+                st.a[i] = *reinterpret_cast<const u32x4 *>(abase + (tail ? a_off_tail[i] : a_off[i]));
+        }
+        if (DROPIT_ABLATE & 32) return;
         st.lo = tile_ptr[int64_t(kb) * (nb_count + 1) + nb];
         st.hi = tile_ptr[int64_t(kb) * (nb_count + 1) + nb + 1];
         const uint32_t *pbase = packed + st.lo;

@@ -21,7 +21,7 @@ def declared_symbols():
 def test_header_declares_the_expected_entry_points():
     assert declared_symbols() == sorted([
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
-        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events"])
+        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode"])
 
 
 def test_library_exports_every_declared_symbol():
@@ -75,6 +75,14 @@ def test_compress_rejects_bad_arguments_without_a_gpu():
     assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, ws, 16, None) == binding.EWORKSPACE
     # gamma = 1 keeps nothing: legal, nothing launched, outputs may be NULL
     assert call(fake, _shape(4, 4), 2, binding.BF16, 1.0, None, None, None, 0, None) == binding.OK
+
+
+def test_select_mode_switch_validates():
+    L = dropit.lib()
+    assert L.dropit_set_select_mode(1) == binding.OK
+    assert L.dropit_set_select_mode(0) == binding.OK
+    assert L.dropit_set_select_mode(2) == binding.EINVAL
+    assert L.dropit_set_select_mode(-1) == binding.EINVAL
 
 
 def test_workspace_queries():

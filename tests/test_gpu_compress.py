@@ -107,3 +107,52 @@ def test_does_not_write_past_k():
     dropit.compress(xd, 0.9, vals=vals, idx=idx)
     torch.cuda.synchronize()
     assert torch.all(idx[k:] == -5) and torch.all(vals[k:] == 7.0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_separate_kernel_mode_matches_oracle(dtype):
+    """Mode 1 (ordinary kernels, the graph-capturable form) gives the same bytes as the oracle."""
+    dropit.set_select_mode(1)
+    try:
+        for numel in (9, 4097, 300003, (1 << 20) + 5):
+            x = activation((numel,), "relu", 500 + numel % 97, dtype)
+            for gamma in (0.9, 0.3):
+                run_and_compare(x, gamma, "separate-kernels")
+        w = WORKLOADS["vitb_fc1"]
+        if dtype == "bf16":
+            run_and_compare(activation(w.x_shape, w.x_dist, w.x_seed, w.dtype), w.gamma, "separate-kernels vitb_fc1")
+    finally:
+        dropit.set_select_mode(0)
+
+
+def test_separate_kernel_mode_in_a_hip_graph():
+    """The ordinary-kernel form replays correctly from a captured graph (no memset nodes inside)."""
+    x = activation((123457,), "gelu", 77, "bf16")
+    xd = to_device(x)
+    k = dropit.keep_count(x.size, 0.9)
+    vals = torch.zeros(k, dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.zeros(k, dtype=torch.int32, device="cuda:0")
+    ws = torch.empty(dropit.compress_workspace_bytes(x.size, xd.dtype), dtype=torch.uint8, device="cuda:0")
+    want_v, want_i = oracle.compress(x, k)
+    dropit.set_select_mode(1)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            dropit.compress(xd, 0.9, vals=vals, idx=idx, workspace=ws)       # warm-up outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            dropit.compress(xd, 0.9, vals=vals, idx=idx, workspace=ws)
+        for replay in range(3):
+            vals.zero_()
+            idx.zero_()
+            ws.fill_(replay * 37)                                            # eager work between replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(to_host(idx), want_i), replay
+            assert to_host(vals).tobytes() == want_v.tobytes(), replay
+    finally:
+        dropit.set_select_mode(0)

@@ -91,7 +91,11 @@ def test_k_zero_gives_zero_gradient():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("N,C,H,W,J", [(2, 5, 9, 11, 7), (1, 1, 3, 3, 1), (3, 16, 14, 14, 32), (2, 64, 56, 56, 64),
-                                       (2, 8, 7, 30, 8)])
+                                       (2, 8, 7, 30, 8),
+                                       # shapes the matrix-core path takes (W % 8 == 0): ragged channel blocks,
+                                       # odd and single rows, several (j, c) blocks, several row bands
+                                       (2, 5, 9, 16, 7), (1, 70, 6, 8, 130), (3, 64, 1, 24, 64), (2, 16, 28, 32, 24),
+                                       (1, 130, 5, 40, 66), (300, 8, 3, 8, 8), (1, 3, 61, 120, 5)])
 def test_conv3x3_shapes(dtype, N, C, H, W, J):
     print("wgrad conv", dtype, N, C, H, W, J, flush=True)
     x = activation((N, C, H, W), "relu", 300 + H, dtype)
