@@ -119,24 +119,30 @@ fc_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ 
 // GEMM: one workgroup = one BM x BN tile of dW over a contiguous range of token
 // blocks (one of `splits` K-slices).  WAVES_M x WAVES_N wavefronts, each a
 // (BM/WAVES_M) x (BN/WAVES_N) sub-tile built from 32x32x16 bf16 MFMAs.
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int WPE_, int STAGES_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int WPE_, int STAGES_, int PROD_ = 0>
 struct FcCfg {
+    // PROD = 0: every wavefront both moves data and multiplies.  PROD > 0: that many extra wavefronts do all
+    // the data movement (global loads, LDS stores, scatter, clear) while the WAVES_M x WAVES_N others only
+    // read LDS and issue MFMAs, so a step's memory waits never sit in front of its matrix work.
+    static constexpr int PROD = PROD_;
+    static constexpr int CONS_WAVES = WAVES_M_ * WAVES_N_;
     static constexpr int STAGES = STAGES_;                 // register stages = global-load prefetch depth (even)
     static_assert(STAGES_ >= 2 && STAGES_ % 2 == 0, "prefetch depth must be even");
     static constexpr int WPE = WPE_;                       // wavefronts per SIMD the register budget must allow
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-    static constexpr int NTHREADS = WAVE * WAVES_M * WAVES_N;
+    static constexpr int NTHREADS = WAVE * (WAVES_M * WAVES_N + PROD);
+    static constexpr int MOVERS = PROD ? WAVE * PROD : NTHREADS;   // threads that move data
     static constexpr int PITCH_A = (BM + 32) * 2;          // bytes; rows 64 bytes apart mod 256: conflict-free transpose reads
     static constexpr int PITCH_B = BK * 2 + 16;            // bytes; odd multiple of 16: conflict-free 16-byte row reads
     static constexpr int A_BYTES = BK * PITCH_A;
-    static constexpr int B_BYTES = (BN * PITCH_B + NTHREADS * 16 - 1) / (NTHREADS * 16) * (NTHREADS * 16);  // whole 16-byte stores per thread
+    static constexpr int B_BYTES = (BN * PITCH_B + MOVERS * 16 - 1) / (MOVERS * 16) * (MOVERS * 16);  // whole 16-byte stores per thread
     static constexpr int LDS_BYTES = 2 * A_BYTES + 3 * B_BYTES;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int FM = WM / 32, FN = WN / 32;
-    static constexpr int A_VECS = BK * (BM / 8) / NTHREADS; // 16-byte global loads per thread per step
-    static constexpr int B_ZERO = B_BYTES / 16 / NTHREADS;
-    static constexpr int ENT = (BK * BN / 4 / NTHREADS) < 2 ? 2 : (BK * BN / 4 / NTHREADS);  // prefetch depth: 25% density
-    static_assert(BK * (BM / 8) % NTHREADS == 0, "A tile must divide over the block");
+    static constexpr int A_VECS = BK * (BM / 8) / MOVERS; // 16-byte global loads per thread per step
+    static constexpr int B_ZERO = B_BYTES / 16 / MOVERS;
+    static constexpr int ENT = (BK * BN / 4 / MOVERS) < 2 ? 2 : (BK * BN / 4 / MOVERS);  // prefetch depth: 25% density
+    static_assert(BK * (BM / 8) % MOVERS == 0, "A tile must divide over the block");
     static_assert(BN * PITCH_B < 65536, "packed LDS offsets are 16-bit");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "MFMA 32x32x16 tiling");
 };
@@ -147,12 +153,15 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
                const uint32_t *__restrict__ tile_ptr, int64_t n_pairs, int64_t ntok, int M, int N, int nb_count,
                int mb_count, int nkb, int splits, float *__restrict__ out /* dW or partials [splits][M][N] */)
 {
-    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NTHREADS;
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::MOVERS;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char *ldsA = lds;                         // [2][BK][PITCH_A]
     char *ldsB = lds + 2 * C::A_BYTES;        // [3][BN][PITCH_B]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool is_mover = C::PROD == 0 || wave >= C::CONS_WAVES;
+    const bool is_consumer = C::PROD == 0 || wave < C::CONS_WAVES;
+    const int tid = C::PROD ? int(threadIdx.x) - WAVE * C::CONS_WAVES : int(threadIdx.x);   // index among the movers
+    const int wm = (wave % C::CONS_WAVES) / C::WAVES_N, wn = wave % C::WAVES_N;
 
     // Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-number so
     // that the workgroups sharing one XCD's L2 are consecutive tiles: same rows of
@@ -250,11 +259,16 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
             *reinterpret_cast<u32x4 *>(a + row * C::PITCH_A + cv * 16) = st.a[i];
         }
         char *b = ldsB + bbuf * C::B_BYTES;
+        // A masked LDS store costs a wavefront ~30 cycles even with no lane enabled, so whole
+        // slots past the end of the range are skipped with a scalar branch.
+        const uint32_t count = st.hi - st.lo;
 #pragma unroll
         for (int i = 0; i < C::ENT; ++i) {
             const uint32_t p = st.e[i];
             d.off[i] = p;
-            if (st.lo + tid + i * NT < st.hi) *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
+            if (uint32_t(i * NT) < count) {
+                if (uint32_t(tid + i * NT) < count) *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
+            }
         }
         d.lo = st.lo;
         d.hi = st.hi;
@@ -271,9 +285,12 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
     auto clear_step = [&](const Dirty &d, int bbuf) {
         if (DROPIT_ABLATE & 4) return;
         char *b = ldsB + bbuf * C::B_BYTES;
+        const uint32_t count = d.hi - d.lo;
 #pragma unroll
         for (int i = 0; i < C::ENT; ++i)
-            if (d.lo + tid + i * NT < d.hi) *reinterpret_cast<uint16_t *>(b + (d.off[i] & 0xFFFFu)) = uint16_t(0);
+            if (uint32_t(i * NT) < count) {
+                if (uint32_t(tid + i * NT) < count) *reinterpret_cast<uint16_t *>(b + (d.off[i] & 0xFFFFu)) = uint16_t(0);
+            }
         if (d.hi - d.lo > uint32_t(C::ENT * NT)) {
             for (uint32_t j = d.lo + tid + C::ENT * NT; j < d.hi; j += NT)
                 *reinterpret_cast<uint16_t *>(b + (packed[j] & 0xFFFFu)) = uint16_t(0);
@@ -325,35 +342,91 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
     // The B buffer being read, the one being filled and the one being cleared are always
     // different; register stage indices are compile-time (the loop is unrolled R times),
     // LDS buffer indices are scalars.
+#ifdef DROPIT_PHASE_CLOCK          // development only: where does a mover wavefront's step go
+    unsigned long long pc_t[5] = {0, 0, 0, 0, 0}, pc_sum[4] = {0, 0, 0, 0};
+#define PHASE_CLOCK(i)                                                        \
+    do {                                                                      \
+        pc_t[i] = wall_clock64();                                             \
+        if ((i) > 0) pc_sum[(i) - 1] += pc_t[i] - pc_t[(i) - 1];              \
+    } while (0)
+#else
+#define PHASE_CLOCK(i) do { } while (0)
+#endif
     if (steps > 0) {
         // Loads and stores past the last block are clamped to it instead of branched
         // around: the loop body stays straight-line, so every wait counts exactly the
         // newer loads it may leave in flight.  The duplicates land in LDS buffers that
         // are never multiplied.
         const int kb_last = kb_end - 1;
-        zero_b(0);
-        zero_b(1);
-        zero_b(2);
+        const int rounds = (steps + R - 1) / R * R;       // every wavefront passes 2 + rounds barriers
+        if (C::PROD == 0) {
+            zero_b(0);
+            zero_b(1);
+            zero_b(2);
 #pragma unroll
-        for (int r = 0; r < R; ++r) load_step(st[r], min(kb_begin + r, kb_last));
-        __syncthreads();
-        store_step(st[0], dirty[0], 0, 0);
-        load_step(st[0], min(kb_begin + R, kb_last));
-        __syncthreads();
-        for (int s0 = 0; s0 < steps; s0 += R) {
+            for (int r = 0; r < R; ++r) load_step(st[r], min(kb_begin + r, kb_last));
+            __syncthreads();
+            store_step(st[0], dirty[0], 0, 0);
+            load_step(st[0], min(kb_begin + R, kb_last));
+            __syncthreads();
+            for (int s0 = 0; s0 < rounds; s0 += R) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int s = s0 + r;
-                clear_step(dirty[(r + 1) & 1], (s + 2) % 3);          // step s-1 (nothing on the first pass)
-                store_step(st[(r + 1) % R], dirty[(r + 1) & 1], (s + 1) & 1, (s + 1) % 3);
-                load_step(st[(r + 1) % R], min(kb_begin + s + 1 + R, kb_last));
+                for (int r = 0; r < R; ++r) {
+                    const int s = s0 + r;
+                    clear_step(dirty[(r + 1) & 1], (s + 2) % 3);          // step s-1 (nothing on the first pass)
+                    store_step(st[(r + 1) % R], dirty[(r + 1) & 1], (s + 1) & 1, (s + 1) % 3);
+                    load_step(st[(r + 1) % R], min(kb_begin + s + 1 + R, kb_last));
+                    if (s < steps) compute(s & 1, s % 3);
+                    __syncthreads();
+                }
+            }
+        } else if (is_mover) {
+            // data-movement wavefronts: same schedule without the multiply (separate loop, so that
+            // their registers and the accumulators of the other wavefronts are never live together)
+            zero_b(0);
+            zero_b(1);
+            zero_b(2);
+#pragma unroll
+            for (int r = 0; r < R; ++r) load_step(st[r], min(kb_begin + r, kb_last));
+            __syncthreads();
+            store_step(st[0], dirty[0], 0, 0);
+            load_step(st[0], min(kb_begin + R, kb_last));
+            __syncthreads();
+            for (int s0 = 0; s0 < rounds; s0 += R) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int s = s0 + r;
+                    PHASE_CLOCK(0);
+                    clear_step(dirty[(r + 1) & 1], (s + 2) % 3);
+                    PHASE_CLOCK(1);
+                    store_step(st[(r + 1) % R], dirty[(r + 1) & 1], (s + 1) & 1, (s + 1) % 3);
+                    PHASE_CLOCK(2);
+                    load_step(st[(r + 1) % R], min(kb_begin + s + 1 + R, kb_last));
+                    PHASE_CLOCK(3);
+                    __syncthreads();
+                    PHASE_CLOCK(4);
+                }
+            }
+        } else {
+            // matrix wavefronts: LDS reads and MFMAs only
+            __syncthreads();
+            __syncthreads();
+            for (int s = 0; s < rounds; ++s) {
                 if (s < steps) compute(s & 1, s % 3);
                 __syncthreads();
             }
         }
     }
 
+#ifdef DROPIT_PHASE_CLOCK
+    if (v == total / 2 && tid == 0 && is_mover) {
+        float *o = out + int64_t(splits) * M * N;      // scratch past the partials (the test over-allocates)
+        for (int i = 0; i < 4; ++i) o[i] = float(pc_sum[i]);
+        o[4] = float(steps);
+    }
+#endif
     // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block
+    if (!is_consumer) return;
     float *dst = out + int64_t(split) * M * N;
 #pragma unroll
     for (int i = 0; i < C::FM; ++i)
@@ -382,15 +455,15 @@ splitk_reduce_kernel(const float4 *__restrict__ partial, int64_t n4, int splits,
 }
 
 #ifndef DROPIT_FC_CFG
-#define DROPIT_FC_CFG 256, 128, 32, 2, 2, 2, 2
+#define DROPIT_FC_CFG 256, 256, 32, 2, 4, 3, 2, 4
 #endif
 using Cfg = FcCfg<DROPIT_FC_CFG>;
 
 int tuned_splits(int tiles, int nkb)
 {
-    // two workgroups per compute unit (LDS and registers allow exactly two): as many K-slices
-    // as fill 2 x 256 slots without starting a second round
-    int splits = 512 / tiles;
+    // one workgroup (8 matrix + 4 data-movement wavefronts) per compute unit: as many K-slices
+    // as fill the 256 compute units without starting a second round
+    int splits = 256 / tiles;
 #ifdef DROPIT_TUNING
     if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
 #endif
@@ -416,7 +489,7 @@ FcPlan fc_mfma_plan(const FcProblem &p)
     plan.mb_count = int((p.cout + Cfg::BM - 1) / Cfg::BM);
     plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
     // slack: a step may read up to ENT * NTHREADS pair slots past the end of its range
-    plan.packed_bytes = round_up(size_t(p.k > 0 ? p.k : 1) * 4 + size_t(Cfg::ENT) * Cfg::NTHREADS * 4, 256);
+    plan.packed_bytes = round_up(size_t(p.k > 0 ? p.k : 1) * 4 + size_t(Cfg::ENT) * Cfg::MOVERS * 4, 256);
     plan.tileptr_bytes = round_up(size_t(plan.nkb) * (plan.nb_count + 1) * 4, 256);
     plan.partial_bytes = plan.splits > 1 ? round_up(size_t(plan.splits) * p.cout * p.cin * 4, 256) : 0;
     return plan;
