@@ -32,85 +32,126 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-constexpr int THREADS = 256;      // prep (bucket) kernel workgroup size
-
+constexpr int THREADS = 1024;     // prep (bucket) kernel workgroup size
+constexpr int PREP_CACHE = 12;    // pairs per thread the prep kernel keeps in registers between its two phases
 
 // ---------------------------------------------------------------------------
-// Cooperative lower_bound over a sorted int32 array: number of elements < target.
+// Cooperative lower_bound over a sorted int32 array for two targets at once
+// (number of elements < t0 and < t1): THREADS-ary search, both targets share the
+// rounds, so ~3 rounds of one load each for a million elements.
 // All THREADS threads of the block must call it (contains barriers).
-__device__ inline int64_t block_lower_bound(const int32_t *__restrict__ idx, int64_t n, int64_t target)
+__device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64_t n, int64_t t0, int64_t t1,
+                                          int64_t &r0, int64_t &r1)
 {
-    int64_t lo = 0, hi = n;
-    while (hi > lo) {
-        const int64_t span = hi - lo;
-        const int64_t step = (span + THREADS - 1) / THREADS;
-        const int64_t pos = lo + int64_t(threadIdx.x) * step;
-        const int pred = (pos < hi) && (int64_t(idx[pos]) < target);
-        const int c = __syncthreads_count(pred);   // probes are monotone: the first c are true
-        if (c == 0) {
-            hi = lo;
-        } else {
-            const int64_t nlo = lo + int64_t(c - 1) * step + 1;
-            const int64_t nhi = min(lo + int64_t(c) * step, hi);
-            lo = nlo;
-            hi = nhi;
+    int64_t lo[2] = {0, 0}, hi[2] = {n, n};
+    const int64_t target[2] = {t0, t1};
+    while (hi[0] > lo[0] || hi[1] > lo[1]) {
+        int pred[2];
+        int64_t step[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int64_t span = hi[q] - lo[q];
+            step[q] = (span + THREADS - 1) / THREADS;
+            const int64_t pos = lo[q] + int64_t(threadIdx.x) * step[q];
+            pred[q] = (pos < hi[q]) && (int64_t(idx[pos]) < target[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c = __syncthreads_count(pred[q]);   // probes are monotone: the first c are true
+            if (hi[q] > lo[q]) {
+                if (c == 0) {
+                    hi[q] = lo[q];
+                } else {
+                    const int64_t nlo = lo[q] + int64_t(c - 1) * step[q] + 1;
+                    const int64_t nhi = min(lo[q] + int64_t(c) * step[q], hi[q]);
+                    lo[q] = nlo;
+                    hi[q] = nhi;
+                }
+            }
         }
     }
-    return lo;
+    r0 = lo[0];
+    r1 = lo[1];
 }
 
 // ---------------------------------------------------------------------------
 // Prep: one workgroup per token block.  Re-buckets that block's pairs by column
 // block and packs them for the GEMM's LDS scatter.  The order of pairs inside a
 // bucket is arbitrary (each targets a distinct LDS slot), so it cannot affect dW.
+// A returning LDS atomic hands every pair its slot inside its bucket while the
+// buckets are being counted, and the packed words wait in registers for the bucket
+// bases, so the block's pairs are read once.
 template <int BK, int BN, int PITCH_B /*bytes*/>
 __global__ void __launch_bounds__(THREADS)
 fc_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int64_t ntok,
                  int n_cols, int nb_count, uint32_t *__restrict__ packed, uint32_t *__restrict__ tile_ptr)
 {
-    extern __shared__ uint32_t s_cnt[];               // [2 * nb_count + 1]: counts / bases, then fill cursors
-    uint32_t *s_fill = s_cnt + nb_count + 1;
+    extern __shared__ uint32_t s_cnt[];               // [nb_count + 1]: counts, then exclusive bases
     __shared__ uint32_t s_wave[THREADS / WAVE];
     const int tid = threadIdx.x;
     const int64_t kb = blockIdx.x;
     const int64_t seg_first = kb * BK * int64_t(n_cols);               // first flat index of the block
     const int64_t seg_elems = min<int64_t>(BK, ntok - kb * BK) * n_cols;
-    const int64_t lo = block_lower_bound(idx, k, seg_first);
-    const int64_t hi = block_lower_bound(idx, k, seg_first + seg_elems);
-    for (int i = tid; i < 2 * nb_count + 1; i += THREADS) s_cnt[i] = 0;
+    int64_t lo, hi;
+    block_lower_bound2(idx, k, seg_first, seg_first + seg_elems, lo, hi);
+    for (int i = tid; i <= nb_count; i += THREADS) s_cnt[i] = 0;
     __syncthreads();
-    for (int64_t j = lo + tid; j < hi; j += THREADS) {
+
+    // phase 1: count, and remember (packed word, bucket, slot in bucket) per pair
+    uint32_t word[PREP_CACHE], where[PREP_CACHE];     // where = bucket << 16 | slot
+    auto classify = [&](int64_t j, uint32_t &w, uint32_t &nb) -> bool {
         const int64_t r = int64_t(idx[j]) - seg_first;
-        if (r >= 0 && r < seg_elems) {
-            const uint32_t col = uint32_t(r) % uint32_t(n_cols);
-            atomicAdd(&s_cnt[col / BN], 1u);
+        if (r < 0 || r >= seg_elems) return false;    // never for a sorted, in-range index array
+        const uint32_t kl = uint32_t(r) / uint32_t(n_cols);
+        const uint32_t col = uint32_t(r) - kl * uint32_t(n_cols);
+        nb = col / BN;
+        w = (uint32_t(vals[j]) << 16) | ((col - nb * BN) * PITCH_B + kl * 2);
+        return true;
+    };
+#pragma unroll
+    for (int i = 0; i < PREP_CACHE; ++i) {
+        const int64_t j = lo + tid + int64_t(i) * THREADS;
+        where[i] = 0xFFFFFFFFu;
+        word[i] = 0;
+        uint32_t nb;
+        if (j < hi && classify(j, word[i], nb)) where[i] = (nb << 16) | atomicAdd(&s_cnt[nb], 1u);
+    }
+    const int64_t j_rest = lo + int64_t(PREP_CACHE) * THREADS;         // pairs beyond the register cache (dense blocks)
+    uint32_t *s_fill = s_cnt + nb_count + 1;                           // [nb_count] cursors of the uncached tail
+    if (j_rest < hi) {                                                 // uniform
+        __syncthreads();                                               // cached pairs own slots [0, cached count)
+        for (int i = tid; i < nb_count; i += THREADS) s_fill[i] = s_cnt[i];
+        __syncthreads();
+        for (int64_t j = j_rest + tid; j < hi; j += THREADS) {
+            uint32_t w, nb;
+            if (classify(j, w, nb)) atomicAdd(&s_cnt[nb], 1u);
         }
     }
     __syncthreads();
-    // exclusive scan of the bucket counts (nb_count <= 2*THREADS handled per pass of THREADS)
+    // exclusive scan of the bucket counts
     uint32_t carry = 0;
     for (int base = 0; base < nb_count; base += THREADS) {
         const int b = base + tid;
         const uint32_t c = (b < nb_count) ? s_cnt[b] : 0u;
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<THREADS>(c, s_wave, total);
+        __syncthreads();
         if (b < nb_count) s_cnt[b] = carry + ex;
         carry += total;
-        __syncthreads();
     }
     if (tid == 0) s_cnt[nb_count] = carry;
     __syncthreads();
     uint32_t *tp = tile_ptr + kb * (nb_count + 1);
     for (int b = tid; b <= nb_count; b += THREADS) tp[b] = uint32_t(lo) + s_cnt[b];
-    for (int64_t j = lo + tid; j < hi; j += THREADS) {
-        const int64_t r = int64_t(idx[j]) - seg_first;
-        if (r >= 0 && r < seg_elems) {
-            const uint32_t kl = uint32_t(r) / uint32_t(n_cols);
-            const uint32_t col = uint32_t(r) - kl * uint32_t(n_cols);
-            const uint32_t nb = col / BN;
-            const uint32_t nl = col - nb * BN;
-            const uint32_t slot = atomicAdd(&s_fill[nb], 1u);
-            packed[lo + s_cnt[nb] + slot] = (uint32_t(vals[j]) << 16) | (nl * PITCH_B + kl * 2);
+    // phase 2: place
+#pragma unroll
+    for (int i = 0; i < PREP_CACHE; ++i)
+        if (where[i] != 0xFFFFFFFFu) packed[lo + s_cnt[where[i] >> 16] + (where[i] & 0xFFFFu)] = word[i];
+    if (j_rest < hi) {
+        // the uncached tail takes the slots after the cached pairs of its bucket
+        for (int64_t j = j_rest + tid; j < hi; j += THREADS) {
+            uint32_t w, nb;
+            if (classify(j, w, nb)) packed[lo + s_cnt[nb] + atomicAdd(&s_fill[nb], 1u)] = w;
         }
     }
 }
@@ -180,6 +221,14 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
     const int kb_end = int(int64_t(nkb) * (split + 1) / splits);
     const int steps = kb_end - kb_begin;
 
+    constexpr int TP_CAP = 512;                // token blocks whose pair ranges are kept in LDS
+    __shared__ uint2 s_tp[TP_CAP];
+    for (int i = threadIdx.x; i < min(steps, TP_CAP); i += C::NTHREADS) {
+        const uint32_t *tp = tile_ptr + int64_t(kb_begin + i) * (nb_count + 1) + nb;
+        s_tp[i] = make_uint2(tp[0], tp[1]);
+    }
+    __syncthreads();
+
     f32x16 acc[C::FM][C::FN];
 #pragma unroll
     for (int i = 0; i < C::FM; ++i)
@@ -233,8 +282,17 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
                 st.a[i] = *reinterpret_cast<const u32x4 *>(abase + (tail ? a_off_tail[i] : a_off[i]));
         }
         if (DROPIT_ABLATE & 32) return;
-        st.lo = tile_ptr[int64_t(kb) * (nb_count + 1) + nb];
-        st.hi = tile_ptr[int64_t(kb) * (nb_count + 1) + nb + 1];
+        // pair range of this (token block, column block): read from the LDS copy made in the
+        // prologue -- a load from global memory here would put its full latency into every step
+        const int rel = kb - kb_begin;
+        if (rel < TP_CAP) {
+            const uint2 r2 = s_tp[rel];
+            st.lo = r2.x;
+            st.hi = r2.y;
+        } else {
+            st.lo = tile_ptr[int64_t(kb) * (nb_count + 1) + nb];
+            st.hi = tile_ptr[int64_t(kb) * (nb_count + 1) + nb + 1];
+        }
         const uint32_t *pbase = packed + st.lo;
 #pragma unroll
         for (int i = 0; i < C::ENT; ++i) st.e[i] = pbase[uint32_t(tid + i * NT)];
@@ -249,6 +307,7 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
 #pragma unroll
     for (int i = 0; i < C::ENT; ++i) dirty[0].off[i] = dirty[1].off[i] = 0;
 
+    uint32_t keep_alive = 0;                  // development only (ablation): keeps otherwise dead loads alive
     auto store_step = [&](const Stage &st, Dirty &d, int abuf, int bbuf) {
         if (DROPIT_ABLATE & 2) return;
         char *a = ldsA + abuf * C::A_BYTES;
@@ -266,7 +325,9 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
         for (int i = 0; i < C::ENT; ++i) {
             const uint32_t p = st.e[i];
             d.off[i] = p;
-            if (uint32_t(i * NT) < count) {
+            if (DROPIT_ABLATE & 64) {
+                keep_alive ^= p;
+            } else if (uint32_t(i * NT) < count) {
                 if (uint32_t(tid + i * NT) < count) *reinterpret_cast<uint16_t *>(b + (p & 0xFFFFu)) = uint16_t(p >> 16);
             }
         }
@@ -425,6 +486,7 @@ fc_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ pac
         o[4] = float(steps);
     }
 #endif
+    if ((DROPIT_ABLATE & 64) && keep_alive == 0x12345678u) out[0] = 1.f;
     // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block
     if (!is_consumer) return;
     float *dst = out + int64_t(split) * M * N;
@@ -503,7 +565,7 @@ dropit_status fc_mfma_run(const FcProblem &p, const FcPlan &plan, const void *va
     float *partial = reinterpret_cast<float *>(ws + plan.packed_bytes + plan.tileptr_bytes);
 
     trace_mark(stream);
-    const size_t bucket_lds = size_t(2 * plan.nb_count + 1) * 4;
+    const size_t bucket_lds = size_t(2 * plan.nb_count + 2) * 4;
     fc_bucket_kernel<Cfg::BK, Cfg::BN, Cfg::PITCH_B><<<plan.nkb, THREADS, bucket_lds, stream>>>(
         static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, int(p.cin), plan.nb_count, packed, tile_ptr);
 
