@@ -197,7 +197,7 @@ def main():
     g_med = np.median(g_ms, axis=0)
     c_names = (["init", "select_fused"] if fused_select else
                ["init", "hist", "count", "compact"] if bf16 else ["init", "hist0", "hist1", "count", "compact"])
-    g_names = (["bucket_prep", "mfma_gemm", "splitk_reduce"] if fc_mfma else
+    g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
                ["bucket_prep", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
     grad_ms = float(g_med.sum())
@@ -239,7 +239,7 @@ def main():
             "dw_kernels_ms": dict(zip(g_names, [float(v) for v in g_med])),
         },
         "roofline": {
-            "kernel": "fc_mfma_kernel" if fc_mfma else "conv3x3_mfma_kernel" if conv_mfma else "fma kernel",
+            "kernel": "fc_dense_kernel" if fc_mfma else "conv3x3_mfma_kernel" if conv_mfma else "fma kernel",
             "bound": "mfma" if mfma else "alu",
             "achieved": dw_tflops_kernel,
             "peak": MFMA_BF16_PEAK_TFLOPS if mfma else 157.3,

@@ -9,6 +9,7 @@
 // any bf16 shape the MFMA kernels do not cover.
 #include "common.hpp"
 #include "wgrad_internal.hpp"
+#include <cstdlib>
 
 namespace dropit {
 namespace {
@@ -22,6 +23,12 @@ __global__ void __launch_bounds__(256) zero_kernel(uint4 *p, size_t n16)
     const uint4 z = make_uint4(0, 0, 0, 0);
     for (size_t i = blockIdx.x * size_t(blockDim.x) + threadIdx.x; i < n16; i += size_t(gridDim.x) * blockDim.x)
         p[i] = z;
+}
+
+__global__ void __launch_bounds__(256) zero_f32_kernel(float *p, int64_t n)
+{
+    for (int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; i < n; i += int64_t(gridDim.x) * blockDim.x)
+        p[i] = 0.f;
 }
 
 template <typename RAW>
@@ -185,12 +192,14 @@ dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx
 
 using namespace dropit;
 
+static bool use_fc_dense(const FcProblem &fp) { return fc_dense_supported(fp); }
+
 // Workspace need of the path dropit_weight_grad will take for this problem.
 static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
 {
     if (!p.conv && dt == DROPIT_BF16) {
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
-        if (fc_mfma_supported(fp)) return fc_mfma_plan(fp).total();
+        if (use_fc_dense(fp)) return fc_dense_plan(fp).total();
     }
     if (p.conv && dt == DROPIT_BF16) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
@@ -225,9 +234,14 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
     if (workspace_bytes < need) return DROPIT_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
+    if (k == 0) {                                  // everything was dropped: R(a^) = 0, so dW = 0
+        const int64_t n = p.conv ? p.cout * p.C * 9 : p.cout * p.cin;
+        zero_f32_kernel<<<int(std::min<int64_t>((n + 255) / 256, 2048)), 256, 0, stream>>>(dW, n);
+        return launch_status();
+    }
     if (!p.conv && dt == DROPIT_BF16 && k > 0) {
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
-        if (fc_mfma_supported(fp)) return fc_mfma_run(fp, fc_mfma_plan(fp), vals, idx, dY, dW, ws, stream);
+        if (use_fc_dense(fp)) return fc_dense_run(fp, fc_dense_plan(fp), vals, idx, dY, dW, ws, stream);
     }
     if (p.conv && dt == DROPIT_BF16 && k > 0) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};

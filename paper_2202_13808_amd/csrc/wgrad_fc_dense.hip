@@ -1,0 +1,584 @@
+// FC weight gradient dW = dY^T * R(a^) on the gfx950 matrix cores
+// (Sec. 3.2: recover R(a^), then the ordinary backward of Eq. fc_backward_elem_save).
+//
+//   1. recover : one pass over the (value, index) pairs rebuilds R(a^) as a dense
+//                bf16 matrix [tokens padded to BK][c_in padded to 8] in the workspace.
+//                It is transient (one layer at a time), as in the method itself.
+//   2. GEMM    : M = c_out (columns of dY), N = c_in (columns of R(a^)), reduction over
+//                tokens.  Both operands have the token axis slow, so both tiles are
+//                [k][m] row blocks.  They go from global memory straight into LDS
+//                (16-byte direct loads, no registers in between), STAGES deep, and the
+//                MFMA fragments come out through the LDS transpose read
+//                (ds_read_b64_tr_b16).  A direct load writes 64 lanes x 16 bytes to
+//                consecutive LDS bytes, so rows cannot be padded; bank conflicts of the
+//                transpose reads are avoided by an XOR swizzle instead: the 64-byte unit
+//                u of row r is kept at unit u ^ (r & 3).  The swizzle costs nothing at run
+//                time: on the way in it only permutes which global address a lane asks
+//                for, on the way out it is folded into per-lane constants.
+//   3. reduce  : split-K partials are summed in ascending split order.
+// Products are exact (bf16 x bf16 in fp32), accumulation is fp32 in a fixed order,
+// so dW is bit-reproducible.
+#include "common.hpp"
+#include "wgrad_internal.hpp"
+#include <cstdlib>
+#include <type_traits>
+
+#ifndef DROPIT_ABLATE
+#define DROPIT_ABLATE 0          // development only: bit mask of pipeline parts to leave out (wrong results)
+#endif
+
+namespace dropit {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+#define DROPIT_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define DROPIT_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+constexpr int RECOVER_THREADS = 1024;
+constexpr int RECOVER_ELEMS = 32768;      // dense elements (64 KB of LDS) one recover workgroup builds
+
+// ---------------------------------------------------------------------------
+// Cooperative lower_bound over a sorted int32 array for two targets at once
+// (number of elements < t0 and < t1): THREADS-ary search, both targets share the
+// rounds, so ~3 rounds of one load each for a million elements.
+// All threads of the block must call it (contains barriers).
+template <int THREADS>
+__device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64_t n, int64_t t0, int64_t t1,
+                                          int64_t &r0, int64_t &r1)
+{
+    int64_t lo[2] = {0, 0}, hi[2] = {n, n};
+    const int64_t target[2] = {t0, t1};
+    while (hi[0] > lo[0] || hi[1] > lo[1]) {
+        int pred[2];
+        int64_t step[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int64_t span = hi[q] - lo[q];
+            step[q] = (span + THREADS - 1) / THREADS;
+            const int64_t pos = lo[q] + int64_t(threadIdx.x) * step[q];
+            pred[q] = (pos < hi[q]) && (int64_t(idx[pos]) < target[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c = __syncthreads_count(pred[q]);   // probes are monotone: the first c are true
+            if (hi[q] > lo[q]) {
+                if (c == 0) {
+                    hi[q] = lo[q];
+                } else {
+                    const int64_t nlo = lo[q] + int64_t(c - 1) * step[q] + 1;
+                    const int64_t nhi = min(lo[q] + int64_t(c) * step[q], hi[q]);
+                    lo[q] = nlo;
+                    hi[q] = nhi;
+                }
+            }
+        }
+    }
+    r0 = lo[0];
+    r1 = lo[1];
+}
+
+// ---------------------------------------------------------------------------
+// Recover R(a^): workgroup b owns rows [b * rows_per_wg, ...) of the padded dense
+// matrix.  Its pairs are one contiguous run of the index-sorted arrays (found by
+// search), so the rows are assembled in LDS (zero fill, one 16-bit store per pair)
+// and leave as full 16-byte stores: every byte of the dense matrix is written exactly
+// once, no separate zero-fill pass.
+__global__ void __launch_bounds__(RECOVER_THREADS)
+fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int64_t ntok,
+                  int64_t ntok_pad, int cin, int pitch, int rows_per_wg, uint16_t *__restrict__ dense)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [rows_per_wg][pitch]
+    const int tid = threadIdx.x;
+    const int64_t r0 = int64_t(blockIdx.x) * rows_per_wg;
+    const int64_t r1 = min(r0 + rows_per_wg, ntok_pad);
+    const int rows = int(r1 - r0);
+    const int chunks = rows * (pitch / 8);                            // 16-byte units
+    u32x4 *tile16 = reinterpret_cast<u32x4 *>(tile);
+    for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
+
+    const int64_t first = min(r0, ntok) * cin, last = min(r1, ntok) * cin;   // flat index range of these rows
+    int64_t lo, hi;
+    block_lower_bound2<RECOVER_THREADS>(idx, k, first, last, lo, hi);  // its barriers also order the zero fill
+    const uint32_t span = uint32_t(last - first);
+    for (int64_t j = lo + tid; j < hi; j += RECOVER_THREADS) {
+        const uint32_t rel = uint32_t(int64_t(idx[j]) - first);
+        if (rel >= span) continue;                                    // never for a sorted, in-range index array
+        uint32_t pos = rel;
+        if (pitch != cin) {
+            const uint32_t row = rel / uint32_t(cin);
+            pos = row * uint32_t(pitch) + (rel - row * uint32_t(cin));
+        }
+        tile[pos] = vals[j];
+    }
+    __syncthreads();
+    u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
+    for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
+}
+
+// ---------------------------------------------------------------------------
+// GEMM: one workgroup = one BM x BN tile of dW over a contiguous range of token
+// blocks (one of `splits` K-slices).  WAVES_M x WAVES_N wavefronts, each a
+// (BM/WAVES_M) x (BN/WAVES_N) sub-tile built from 32x32x16 bf16 MFMAs.
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_>
+struct GemmCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    static constexpr int NWAVES = WAVES_M * WAVES_N;
+    static constexpr int NTHREADS = WAVE * NWAVES;
+    static constexpr int ROW_A = BM * 2, ROW_B = BN * 2;            // bytes per LDS row (one token)
+    static constexpr int A_BYTES = BK * ROW_A, B_BYTES = BK * ROW_B;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int A_LOADS = A_BYTES / 1024 / NWAVES;          // 1 KB direct loads per wavefront per step
+    static constexpr int B_LOADS = B_BYTES / 1024 / NWAVES;
+    static constexpr int LOADS = A_LOADS + B_LOADS;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int FM = WM / 32, FN = WN / 32;
+    static_assert(STAGES >= 2, "at least double buffering");
+    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tiles must divide over the wavefronts");
+    static_assert(ROW_A % 256 == 0 && ROW_B % 256 == 0, "the swizzle permutes the four 64-byte units of a 256-byte group");
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "MFMA 32x32x16 tiling");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+};
+
+template <int N>
+__device__ inline void wait_loads()          // until at most N of this wavefront's global loads are in flight
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int N>
+__device__ inline void lgkm_wait()           // until at most N of this wavefront's LDS reads are in flight
+{
+    static_assert(N >= 0 && N <= 15, "4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ inline void workgroup_barrier()
+{
+    if (DROPIT_ABLATE & 16) return;          // development only, and only together with bits 1|4 (no LDS traffic at all)
+    asm volatile("s_barrier" ::: "memory");
+}
+
+// LDS transpose read: lane i of each 16-lane group receives column i of the 4 x 16 block of
+// 16-bit elements whose lane p supplied row p / 4, columns 4 * (p % 4)..+3.  Result valid after lgkm_wait.
+template <int OFFSET>
+__device__ inline s16x4 tr_read(uint32_t lds_addr)
+{
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "16-bit immediate");
+    s16x4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(lds_addr), "n"(OFFSET) : "memory");
+    return r;
+}
+
+template <int I, int N, typename F>
+__device__ inline void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+template <typename C>
+__global__ void __launch_bounds__(C::NTHREADS)
+fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd, int64_t ntok, int M, int N,
+                int pitch, int nb_count, int mb_count, int nkb, int splits,
+                float *__restrict__ out /* dW or partials [splits][M][N] */)
+{
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];     // [STAGES][A tile | B tile]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+
+    // Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-number so
+    // that the workgroups sharing one XCD's L2 are consecutive tiles: same rows of
+    // dY (mb), neighbouring column blocks (nb).
+    const int total = nb_count * mb_count * splits;
+    const int per_xcd = gridDim.x / 8;
+    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (v >= total) return;
+    const int nb = v % nb_count;
+    const int mb = (v / nb_count) % mb_count;
+    const int split = v / (nb_count * mb_count);
+    const int m0 = mb * BM, n0 = nb * BN;
+
+    // token blocks of this K-slice: an even partition of [0, nkb)
+    const int kb_begin = int(int64_t(nkb) * split / splits);
+    const int kb_end = int(int64_t(nkb) * (split + 1) / splits);
+    const int steps = kb_end - kb_begin;
+
+    f32x16 acc[C::FM][C::FN];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // ---- global -> LDS -----------------------------------------------------------
+    // Direct load q of a tile fills LDS bytes [q * 1024, (q + 1) * 1024): lane L lands at
+    // byte o = q * 1024 + L * 16, i.e. row r = o / ROW, byte b' = o % ROW of that row, and
+    // therefore asks for byte b = b' ^ ((r & 3) << 6) of global row r (the swizzle).
+    // Every load is issued unconditionally from a valid address, so waits can count loads:
+    // columns past M (or the padded c_in) re-read valid columns (those outputs are never
+    // stored); rows past the last token re-read the last token (the matching rows of the
+    // padded R(a^) are zero, so they add nothing that the last token does not add already).
+    const int kb_tail = int((ntok - 1) / BK);           // the (possibly partial) last token block
+    const int rows_tail = int(ntok - int64_t(kb_tail) * BK);
+    uint32_t a_off[C::A_LOADS], a_off_tail[C::A_LOADS], b_off[C::B_LOADS];   // byte offsets inside a token block
+#pragma unroll
+    for (int i = 0; i < C::A_LOADS; ++i) {
+        const int o = (wave * C::A_LOADS + i) * 1024 + lane * 16;
+        const int r = o / C::ROW_A;
+        const int b = (o % C::ROW_A) ^ ((r & 3) << 6);
+        const int m = min(m0 + b / 2, M - 8);
+        a_off[i] = uint32_t(r * M + m) * 2u;
+        a_off_tail[i] = uint32_t(min(r, rows_tail - 1) * M + m) * 2u;
+        if (DROPIT_ABLATE & 64) a_off[i] = a_off_tail[i] = 0;       // development only: every lane asks for the same 16 bytes
+    }
+#pragma unroll
+    for (int i = 0; i < C::B_LOADS; ++i) {
+        const int o = (wave * C::B_LOADS + i) * 1024 + lane * 16;
+        const int r = o / C::ROW_B;
+        const int b = (o % C::ROW_B) ^ ((r & 3) << 6);
+        const int n = min(n0 + b / 2, pitch - 8);
+        b_off[i] = uint32_t(r * pitch + n) * 2u;
+        if (DROPIT_ABLATE & 64) b_off[i] = 0;
+    }
+    // load number q (0 .. LOADS-1) of a step: the A loads first, then the B loads
+    auto issue_load = [&](auto q_, int stage, int kb) {
+        constexpr int q = decltype(q_)::value;
+        if (DROPIT_ABLATE & 1) return;
+        if constexpr (q < C::A_LOADS) {
+            const char *abase = reinterpret_cast<const char *>(dY) + int64_t(kb) * BK * M * 2;
+            char *sa = lds + stage * C::STAGE_BYTES + wave * (C::A_LOADS * 1024);
+            __builtin_amdgcn_global_load_lds(DROPIT_GPTR(abase + (kb == kb_tail ? a_off_tail[q] : a_off[q])),
+                                             DROPIT_LPTR(sa + q * 1024), 16, 0, 0);
+        } else {
+            constexpr int i = q - C::A_LOADS;
+            const char *bbase = reinterpret_cast<const char *>(xd) + int64_t(kb) * BK * pitch * 2;
+            char *sb = lds + stage * C::STAGE_BYTES + C::A_BYTES + wave * (C::B_LOADS * 1024);
+            __builtin_amdgcn_global_load_lds(DROPIT_GPTR(bbase + b_off[i]), DROPIT_LPTR(sb + i * 1024), 16, 0, 0);
+        }
+    };
+    auto issue_loads = [&](int stage, int kb) {
+        static_for<0, C::LOADS>([&](auto q_) { issue_load(q_, stage, kb); });
+    };
+
+    // ---- LDS -> MFMA fragments -----------------------------------------------------
+    // A 32x32x16 operand wants, in lane l, row (l % 32) and k = 8 * (l / 32) + 0..7.  One
+    // transpose read hands lane i of a 16-lane group column i of a 4(k) x 16(m) block whose
+    // lane p supplied row p / 4, columns 4 * (p % 4)..+3; two of them (k and k + 4) make an
+    // operand.  The token row of a lane is 4-aligned plus p / 4, so its swizzle term is the
+    // per-lane constant (p / 4) << 6.
+    const int g = lane >> 4, p16 = lane & 15;
+    const int krow = (g >> 1) * 8 + (p16 >> 2);
+    const int sw = (p16 >> 2) << 6;
+    uint32_t a_frag[C::FM], b_frag[C::FN];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i)
+        a_frag[i] = krow * C::ROW_A + (((wm * C::WM + i * 32 + (g & 1) * 16 + (p16 & 3) * 4) * 2) ^ sw);
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+        b_frag[j] = C::A_BYTES + krow * C::ROW_B + (((wn * C::WN + j * 32 + (g & 1) * 16 + (p16 & 3) * 4) * 2) ^ sw);
+
+    // The fragment reads, the waits and the barrier are written as asm on purpose.  The compiler
+    // cannot tell which direct load fills which LDS bytes, so it would drain every load in flight
+    // (vmcnt(0)) in front of each LDS read and barrier it knows about, which serialises the pipeline.
+    // Here the dependency is kept by hand: wait_loads<>() + barrier before a stage is read, and
+    // lgkm_wait<>() before the registers of a batch of reads are used (the empty "+v" asm statements
+    // tie the MFMA operands to that wait).
+    constexpr int KK = BK / 16;                        // 16-token sub-steps (one MFMA depth) per token block
+    constexpr int NM = C::FM * C::FN;                  // MFMAs per sub-step
+    constexpr int SET_READS = 2 * (C::FM + C::FN);     // LDS reads per sub-step
+    constexpr int READS_PER_MFMA = (SET_READS + NM / 2 - 1) / (NM / 2);   // all reads go out with the first half
+    static_assert(KK % 2 == 0, "fragment sets alternate per sub-step and must line up across token blocks");
+    static_assert(NM >= 2, "the reads of a sub-step go out with the first half of the previous one's MFMAs");
+    const uint32_t lds_base = uint32_t(size_t(DROPIT_LPTR(lds)));
+    s16x4 fa[2][C::FM][2], fb[2][C::FN][2];            // two fragment sets: one multiplying, one being read
+    if (DROPIT_ABLATE & 4) {
+        for (int q = 0; q < 2; ++q) {
+            for (int i = 0; i < C::FM; ++i) fa[q][i][0] = fa[q][i][1] = s16x4{0, 0, 0, 0};
+            for (int j = 0; j < C::FN; ++j) fb[q][j][0] = fb[q][j][1] = s16x4{0, 0, 0, 0};
+        }
+    }
+    // read number r (0 .. SET_READS-1) of sub-step kk of the stage at `stage_base`, into fragment set `set`
+    auto issue_read = [&](auto set_, auto kk_, auto r_, uint32_t stage_base) {
+        constexpr int set = decltype(set_)::value, kk = decltype(kk_)::value, r = decltype(r_)::value;
+        if (DROPIT_ABLATE & 4) return;
+        if constexpr (r < 2 * C::FM) {
+            constexpr int i = r / 2, h = r % 2;
+            fa[set][i][h] = tr_read<(kk * 16 + h * 4) * C::ROW_A>(stage_base + a_frag[i]);
+        } else {
+            constexpr int j = (r - 2 * C::FM) / 2, h = r % 2;
+            fb[set][j][h] = tr_read<(kk * 16 + h * 4) * C::ROW_B>(stage_base + b_frag[j]);
+        }
+    };
+    // One sub-step: the MFMAs of fragment set `set`, with the LDS reads of the next sub-step (into
+    // the other set) issued between the first half of them, and this sub-step's share of the step's
+    // global loads spread evenly between all of them.  A wavefront issues in order, and the two
+    // wavefronts of a SIMD run in lockstep between barriers, so anything not tucked between MFMAs
+    // would leave the matrix pipe idle in both at once; and a burst of loads would wait for the
+    // address unit, which all eight wavefronts feed at the same time.
+    constexpr int LOAD_EVERY = (KK * NM) / C::LOADS;   // one global load per this many MFMAs
+    static_assert(LOAD_EVERY >= 1 && LOAD_EVERY * C::LOADS == KK * NM, "loads must spread evenly over a step's MFMAs");
+    auto substep = [&](auto kk_, auto next_kk_, uint32_t next_base, int load_stage, int load_kb) {
+        constexpr int kk = decltype(kk_)::value, set = kk % 2;
+        lgkm_wait<0>();                                // the reads of this set were issued one sub-step ago
+        bf16x8 af[C::FM], bfv[C::FN];
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i) {
+            asm volatile("" : "+v"(fa[set][i][0]), "+v"(fa[set][i][1]));
+            af[i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(fa[set][i][0], fa[set][i][1], 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j) {
+            asm volatile("" : "+v"(fb[set][j][0]), "+v"(fb[set][j][1]));
+            bfv[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(fb[set][j][0], fb[set][j][1], 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+        static_for<0, NM>([&](auto m_) {
+            constexpr int m = decltype(m_)::value, i = m / C::FN, j = m % C::FN;
+            if (!(DROPIT_ABLATE & 8))
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
+            static_for<m * READS_PER_MFMA, (m + 1) * READS_PER_MFMA>([&](auto r_) {
+                if constexpr (decltype(r_)::value < SET_READS)
+                    issue_read(std::integral_constant<int, 1 - set>{}, next_kk_, r_, next_base);
+            });
+            constexpr int g = kk * NM + m;             // MFMA number within the step
+            if constexpr (g % LOAD_EVERY == LOAD_EVERY - 1)
+                issue_load(std::integral_constant<int, g / LOAD_EVERY>{}, load_stage, load_kb);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    // ---- pipeline --------------------------------------------------------------------
+    // Token block t of the split lives in stage t % STAGES; its loads are issued D = STAGES - 1
+    // steps ahead.  LDS reads run one sub-step ahead of the MFMAs; for that the fragments of
+    // (step s + 1, sub-step 0) are read during step s, i.e. a stage must be complete one step
+    // before it is multiplied.
+    // Iteration s: wait until this wavefront's loads of step s + 1 have landed (the D - 2 newer
+    // steps may stay in flight), barrier (now everybody's have, and everybody is done reading
+    // step s - 1), then the sub-steps, which between them also refill the stage step s - 1 used
+    // with step s + D.
+    // Loads past the last block are clamped to it instead of branched around, so the in-flight
+    // count is the same in every iteration; they land in stages that are read but never multiplied.
+#ifdef DROPIT_PHASE_CLOCK          // development only: where does a wavefront's step go (100 MHz ticks)
+    unsigned long long pc_t[5] = {0, 0, 0, 0, 0}, pc_sum[4] = {0, 0, 0, 0};
+    const unsigned long long pc_begin = wall_clock64();
+#define PHASE_CLOCK(i)                                                        \
+    do {                                                                      \
+        pc_t[i] = wall_clock64();                                             \
+        if ((i) > 0) pc_sum[(i) - 1] += pc_t[i] - pc_t[(i) - 1];              \
+    } while (0)
+#else
+#define PHASE_CLOCK(i) do { } while (0)
+#endif
+    if (steps > 0) {
+        constexpr int D = C::STAGES - 1;
+        static_assert(D >= 2, "a stage is read one step early: three stages at least");
+        const int kb_last = kb_end - 1;
+#pragma unroll
+        for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
+        wait_loads<(D - 1) * C::LOADS>();
+        workgroup_barrier();
+        static_for<0, SET_READS>([&](auto r_) {
+            issue_read(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, r_, lds_base);
+        });
+        int stage = 0, fill = D;                       // s % STAGES and (s + D) % STAGES
+        for (int s = 0; s < steps; ++s) {
+            const int next = stage + 1 == C::STAGES ? 0 : stage + 1;
+            PHASE_CLOCK(0);
+            wait_loads<(D - 2) * C::LOADS>();
+            PHASE_CLOCK(1);
+            workgroup_barrier();
+            PHASE_CLOCK(2);
+            const uint32_t cur_base = lds_base + stage * C::STAGE_BYTES;
+            const uint32_t next_base = lds_base + next * C::STAGE_BYTES;
+            const int load_kb = min(kb_begin + s + D, kb_last);
+            static_for<0, KK>([&](auto kk_) {
+                constexpr int kk = decltype(kk_)::value;
+                if constexpr (kk + 1 < KK)
+                    substep(kk_, std::integral_constant<int, kk + 1>{}, cur_base, fill, load_kb);
+                else
+                    substep(kk_, std::integral_constant<int, 0>{}, next_base, fill, load_kb);
+                if constexpr (kk == 0) PHASE_CLOCK(3);
+            });
+            PHASE_CLOCK(4);
+            stage = next;
+            fill = fill + 1 == C::STAGES ? 0 : fill + 1;
+        }
+        wait_loads<0>();                               // nothing may still be writing LDS
+        lgkm_wait<0>();                                // or registers when the wavefront goes on
+    }
+
+#ifdef DROPIT_PHASE_CLOCK
+    const unsigned long long pc_loop_end = wall_clock64();
+#endif
+    // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block.
+    if (splits == 1) {                                  // straight into dW, row-major
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm * C::WM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    const int n = n0 + wn * C::WN + j * 32 + (lane & 31);
+                    if (m < M && n < N) out[int64_t(m) * N + n] = acc[i][j][e];
+                }
+    } else {
+        // A K-slice's partial tile is written in the accumulator's own order instead: [i][j][e/4]
+        // [thread] x 4 floats, so every store is 16 bytes per lane and 1 KB contiguous per wavefront.
+        // The seven-fold partial traffic then moves in full lines, and the one pass that adds the
+        // slices (splitk_sum_kernel) does the transposition into row-major dW.
+        f32x4 *dst = reinterpret_cast<f32x4 *>(out) +
+                     (int64_t(split) * (nb_count * mb_count) + (mb * nb_count + nb)) * (BM * BN / 4) + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if ((DROPIT_ABLATE & 2) && acc[i][j][q * 4] != 123.456f) continue;
+                    const f32x4 v4 = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+                    dst[((i * C::FN + j) * 4 + q) * C::NTHREADS] = v4;
+                }
+    }
+#ifdef DROPIT_PHASE_CLOCK
+    if (v == total / 2 && lane == 0 && (wave == 0 || wave == C::NWAVES - 1)) {
+        float *o = out + int64_t(splits) * nb_count * mb_count * BM * BN + (wave == 0 ? 0 : 8);      // scratch past the partials (the probe over-allocates)
+        for (int i = 0; i < 4; ++i) o[i] = float(pc_sum[i]);
+        o[4] = float(steps);
+        o[5] = float(pc_t[0] ? pc_loop_end - pc_begin : 0);
+        o[6] = float(wall_clock64() - pc_loop_end);
+    }
+#endif
+}
+
+// Sums the split-K partials in ascending split order, dW = ((p0 + p1) + p2) + ..., and moves
+// them from the accumulator order the GEMM wrote (see its epilogue) to row-major dW.
+// One thread per 4 accumulator floats: rows m .. m+3 of one column.
+template <typename C>
+__global__ void __launch_bounds__(256)
+splitk_sum_kernel(const f32x4 *__restrict__ partial, int splits, int M, int N, int nb_count, int mb_count,
+                  float *__restrict__ dW)
+{
+    constexpr int TILE4 = C::BM * C::BN / 4;            // float4 groups per tile
+    const int64_t tiles = int64_t(nb_count) * mb_count;
+    const int64_t total = tiles * TILE4;
+    for (int64_t g = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; g < total; g += int64_t(gridDim.x) * blockDim.x) {
+        f32x4 s = partial[g];
+        for (int p = 1; p < splits; ++p) s += partial[p * total + g];
+        const int tile = int(g / TILE4), r = int(g % TILE4);
+        const int tid = r % C::NTHREADS, slot = r / C::NTHREADS;   // slot = (i * FN + j) * 4 + q
+        const int q = slot & 3, j = (slot >> 2) % C::FN, i = (slot >> 2) / C::FN;
+        const int lane = tid & 63, wave = tid >> 6;
+        const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+        const int mb = tile / nb_count, nb = tile % nb_count;
+        const int m = mb * C::BM + wm * C::WM + i * 32 + q * 8 + (lane >> 5) * 4;
+        const int n = nb * C::BN + wn * C::WN + j * 32 + (lane & 31);
+        if (n < N) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (m + e < M) dW[int64_t(m + e) * N + n] = s[e];
+        }
+    }
+}
+
+#ifndef DROPIT_GEMM_CFG
+#define DROPIT_GEMM_CFG 256, 256, 32, 4, 2, 4
+#endif
+using Cfg = GemmCfg<DROPIT_GEMM_CFG>;
+
+int tuned_splits(int tiles, int nkb)
+{
+    // one workgroup per compute unit: as many K-slices as fill the 256 compute units
+    // without starting a second round
+    int splits = 256 / tiles;
+#ifdef DROPIT_TUNING
+    if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
+#endif
+    if (splits > nkb) splits = nkb;
+    if (splits < 1) splits = 1;
+    if (splits > 64) splits = 64;
+    return splits;
+}
+
+}  // namespace
+
+bool fc_dense_supported(const FcProblem &p)
+{
+    // 16-byte dY vectors need c_out % 8 == 0; per-lane byte offsets inside a token block are 32-bit;
+    // a recover workgroup holds at least one padded row in LDS
+    const int64_t pitch = (p.cin + 7) / 8 * 8;
+    return p.cout % 8 == 0 && p.cout >= 8 && p.cin >= 1 && pitch <= RECOVER_ELEMS &&
+           p.cout * Cfg::BK * 2 < (int64_t(1) << 31);
+}
+
+FcDensePlan fc_dense_plan(const FcProblem &p)
+{
+    FcDensePlan plan;
+    plan.nkb = int((p.ntok + Cfg::BK - 1) / Cfg::BK);
+    plan.nb_count = int((p.cin + Cfg::BN - 1) / Cfg::BN);
+    plan.mb_count = int((p.cout + Cfg::BM - 1) / Cfg::BM);
+    plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
+    plan.pitch = int((p.cin + 7) / 8 * 8);
+    plan.rows_per_wg = std::max(1, RECOVER_ELEMS / plan.pitch);
+    plan.dense_bytes = round_up(size_t(plan.nkb) * Cfg::BK * plan.pitch * 2, 256);
+    // K-slice partials are whole tiles (ragged edge tiles included) in accumulator order
+    plan.partial_bytes = plan.splits > 1 ? size_t(plan.splits) * plan.nb_count * plan.mb_count * Cfg::BM * Cfg::BN * 4 : 0;
+    return plan;
+}
+
+dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
+                           const void *dY, float *dW, char *ws, hipStream_t stream)
+{
+    uint16_t *dense = reinterpret_cast<uint16_t *>(ws);
+    float *partial = reinterpret_cast<float *>(ws + plan.dense_bytes);
+    const int64_t ntok_pad = int64_t(plan.nkb) * Cfg::BK;
+
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, RECOVER_ELEMS * 2) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) != hipSuccess)
+            return DROPIT_EHIP;
+        attr_set = true;
+    }
+
+    trace_mark(stream);
+    const int recover_grid = int((ntok_pad + plan.rows_per_wg - 1) / plan.rows_per_wg);
+    const size_t recover_lds = size_t(plan.rows_per_wg) * plan.pitch * 2;
+    fc_recover_kernel<<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
+        static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
+        dense);
+
+    trace_mark(stream);
+    const int total = plan.nb_count * plan.mb_count * plan.splits;
+    const int grid = (total + 7) / 8 * 8;
+    float *out = plan.splits > 1 ? partial : dW;
+    fc_dense_kernel<Cfg><<<grid, Cfg::NTHREADS, Cfg::LDS_BYTES, stream>>>(
+        static_cast<const uint16_t *>(dY), dense, p.ntok, int(p.cout), int(p.cin), plan.pitch, plan.nb_count,
+        plan.mb_count, plan.nkb, plan.splits, out);
+
+    trace_mark(stream);
+    if (plan.splits > 1) {
+        const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (Cfg::BM * Cfg::BN / 4);
+        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 4096));
+        splitk_sum_kernel<Cfg><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
+                                                           int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
+    }
+    trace_mark(stream);
+    return launch_status();
+}
+
+}  // namespace dropit

@@ -11,17 +11,17 @@ struct FcProblem {
     int64_t ntok, cin, cout, k;
 };
 
-struct FcPlan {
-    int nkb, nb_count, mb_count, splits;
-    size_t packed_bytes, tileptr_bytes, partial_bytes;
-    size_t total() const { return packed_bytes + tileptr_bytes + partial_bytes; }
+struct FcDensePlan {
+    int nkb, nb_count, mb_count, splits, pitch, rows_per_wg;
+    size_t dense_bytes, partial_bytes;
+    size_t total() const { return dense_bytes + partial_bytes; }
 };
 
-// bf16 fully-connected weight gradient on the matrix cores (wgrad_fc_mfma.hip)
-bool fc_mfma_supported(const FcProblem &p);
-FcPlan fc_mfma_plan(const FcProblem &p);
-dropit_status fc_mfma_run(const FcProblem &p, const FcPlan &plan, const void *vals, const int32_t *idx,
-                          const void *dY, float *dW, char *ws, hipStream_t stream);
+// bf16 fully-connected weight gradient: recover R(a^) densely, then a direct-to-LDS GEMM (wgrad_fc_dense.hip)
+bool fc_dense_supported(const FcProblem &p);
+FcDensePlan fc_dense_plan(const FcProblem &p);
+dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
+                           const void *dY, float *dW, char *ws, hipStream_t stream);
 
 struct ConvProblem {
     int64_t N, C, H, W, J, k;

@@ -62,6 +62,38 @@ def test_fc_shapes(dtype, ntok, cin, cout, gamma):
     assert_close(got, ref, TOL[dtype])
 
 
+@pytest.mark.parametrize("ntok,cin,cout,gamma", [
+    (777, 257, 40, 0.9),      # c_in not a multiple of 8: padded row pitch of the recovered matrix
+    (5, 24, 16, 0.5),         # fewer tokens than one token block
+    (33, 520, 264, 0.9),      # ragged tiles in both output dimensions, ragged last token block
+    (4100, 8, 3080, 0.8),     # many row tiles, one narrow column tile
+    (2000, 3000, 8, 0.95),    # many column tiles, one narrow row tile
+    (9000, 512, 512, 0.9),    # several K-slices per tile
+    (640, 40000, 8, 0.9),     # c_in beyond what the recover kernel holds in LDS: generic path
+])
+def test_fc_bf16_tile_edges(ntok, cin, cout, gamma):
+    print("wgrad fc edges", ntok, cin, cout, gamma, flush=True)
+    x = activation((ntok, cin), "normal", 300 + ntok, "bf16")
+    dy = gradient((ntok, cout), 0.02, 400 + ntok, "bf16")
+    got, _, _ = gpu_dw(x, dy, gamma, cout)
+    ref = oracle.dw_fc(ref_xhat(x, gamma), oracle.widen(dy))
+    assert_close(got, ref, TOL["bf16"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("conv", [None, CONV3])
+def test_everything_dropped_gives_zero(dtype, conv):
+    print("wgrad all dropped", dtype, conv, flush=True)
+    shape = (2, 16, 8, 8) if conv else (96, 64)
+    dy_shape = (2, 24, 8, 8) if conv else (96, 24)
+    x = activation(shape, "normal", 7, dtype)
+    dy = gradient(dy_shape, 0.02, 8, dtype)
+    got, vals, idx = gpu_dw(x, dy, 1.0, 24, conv=conv)
+    assert vals.size == 0 and idx.size == 0
+    assert got.shape == ((24, 16, 3, 3) if conv else (24, 64))
+    assert not got.any()
+
+
 def test_fc_leading_dims_are_tokens():
     x = activation((4, 50, 96), "gelu", 3, "bf16")
     dy = gradient((4, 50, 40), 0.02, 4, "bf16")
