@@ -136,12 +136,22 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
                                  void *hip_stream);
 
 /*
- * dropit_compress runs, when it can, as a single cooperative kernel (one workgroup per
- * compute unit, grid barriers between its phases).  Cooperative launches cannot be
- * recorded into a HIP graph; a caller that captures the stream selects mode 1, which runs
- * the same select as separate ordinary kernels (no memset nodes).  Mode 0 (default) tries
- * the cooperative kernel first and falls back to mode 1 if that launch is refused.
- * The setting is per host thread.  Returns DROPIT_EINVAL for any other mode.
+ * How dropit_compress runs its select (per host thread):
+ *   0 (default)  one persistent kernel, one workgroup per compute unit, grid barriers between
+ *                its phases, launched as an ordinary kernel after checking that the grid fits
+ *                the device at once; falls back to mode 1 if it does not.  Its barriers wait a
+ *                bounded time; if the workgroups do not all become resident (a device shared
+ *                with other persistent kernels) the kernel redoes the selection serially in its
+ *                last workgroup, so the result is complete either way, only late.
+ *   1            the same select as separate ordinary kernels (no grid barriers, no memset
+ *                nodes): for callers that must not depend on co-residency at all.
+ *   2            mode 0's kernel through a cooperative launch: the runtime then guarantees
+ *                co-residency, at the price of tens of microseconds of queue switching per
+ *                call; cannot be recorded into a HIP graph (falls back to mode 0's launch).
+ *   3            test hook: mode 0 with zero patience at the grid barriers, which forces the
+ *                serial redo; every kernel still exits normally.
+ * Modes 0, 1 and 3 use only ordinary kernel launches and can be captured into a HIP graph.
+ * Returns DROPIT_EINVAL for any other mode.
  */
 dropit_status dropit_set_select_mode(int mode);
 

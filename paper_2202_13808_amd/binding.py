@@ -183,8 +183,9 @@ def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], d
 
 
 def set_select_mode(mode: int) -> None:
-    """dropit_set_select_mode: 0 = cooperative fused select when possible (default),
-    1 = separate ordinary kernels (the form that can be captured into a HIP graph)."""
+    """dropit_set_select_mode: 0 = one persistent kernel (default), 1 = separate ordinary
+    kernels, 2 = the persistent kernel through a cooperative launch, 3 = test hook that forces
+    the persistent kernel's serial redo path."""
     _check(lib().dropit_set_select_mode(int(mode)))
 
 

@@ -46,7 +46,8 @@ inline void trace_mark(hipStream_t stream)
     if (t.next < t.count) (void)hipEventRecord(t.events[t.next++], stream);
 }
 
-// 0 = cooperative fused select when possible, 1 = separate kernels (see dropit_set_select_mode)
+// how dropit_compress runs its select: 0 persistent kernel, 1 separate kernels, 2 cooperative launch,
+// 3 forced serial redo (see dropit_set_select_mode)
 int &select_mode();                              // per host thread; defined in compress.hip
 
 // ---- wave / block primitives (64-wide wavefronts) -----------------------

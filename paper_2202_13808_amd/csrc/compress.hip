@@ -22,6 +22,7 @@
 // Nothing here synchronises with the host; counts are integer, so the result
 // does not depend on the order in which workgroups run.
 #include "common.hpp"
+#include <cstdlib>
 #include <type_traits>
 
 namespace dropit {
@@ -40,8 +41,9 @@ struct SelState {
     uint32_t m;          // how many keys equal to t are kept (lowest flat index first)
     uint32_t ticket[4];  // arrival counters, one per pass
     uint32_t barrier;    // arrivals at the fused kernel's grid barriers (monotone within a call)
-    uint32_t error;      // set if a grid barrier ran out of patience (results are then invalid)
-    uint32_t pad[54];
+    uint32_t error;      // hint: some workgroup ran out of patience at a grid barrier (the others stop waiting)
+    uint32_t exited;     // fused kernel: low 16 bits = workgroups done, high 16 bits = how many of them gave up
+    uint32_t pad[53];
 };
 static_assert(sizeof(SelState) == 256, "state block is 256 bytes");
 
@@ -383,7 +385,7 @@ compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vp
 }
 
 // ---------------------------------------------------------------------------
-// Fused path: the whole select + compaction as ONE cooperative kernel with one
+// Fused path: the whole select + compaction as ONE persistent kernel with one
 // workgroup per compute unit.  Each workgroup parks the first FUSED_RES x 16 KB of its
 // chunk in LDS across all phases (the whole chunk for tensors up to ~25 MB; anything
 // beyond is re-read, mostly from the Infinity Cache), and the phases are separated by
@@ -391,12 +393,18 @@ compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vp
 // on purpose: unrolling them 8x made the kernel 48 KB of code and instruction-fetch bound.  Every workgroup resolves the digits itself
 // from the merged histogram, so the select state lives in registers.
 //
+// The kernel is an ordinary launch (a cooperative launch costs ~14 us of queue switching before and
+// after the kernel on this runtime): the host only checks that the grid fits the device all at once.
+// Should the workgroups nevertheless not all become resident (a device shared with other persistent
+// kernels), the bounded grid barriers give up, every workgroup leaves, and the last one to leave
+// redoes the whole selection on its own (select_serial): slow, but the result is always complete.
+//
 // Everything workgroups exchange (histogram, per-chunk table, barrier counter) is
 // accessed ONLY with device-scope atomics, which are coherent by themselves, so no
 // device-wide fence is needed: on this 8-XCD part such a fence writes back and
 // invalidates a whole L2 and was measured at 5-8 us per grid barrier.
 constexpr int FUSED_RES = 6;             // 16-byte vectors per thread parked in LDS
-constexpr uint32_t SPIN_LIMIT = 1u << 22;   // grid-barrier patience; every wave exits even if it runs out
+constexpr uint32_t SPIN_LIMIT = 1u << 22;   // grid-barrier patience in polls (~0.1 us each); every wave exits even if it runs out
 
 __device__ inline uint32_t dev_load(const uint32_t *p)
 {
@@ -407,23 +415,29 @@ __device__ inline void dev_store(uint32_t *p, uint32_t v)
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// All workgroups of the (cooperatively launched, hence co-resident) grid meet here.
+// All workgroups of the grid meet here.  The grid is sized so that every workgroup is resident at
+// once, but nothing enforces that the device is not shared, so the wait is bounded: returns false
+// (in every thread of the workgroup) if the others did not all arrive within `spin_limit` polls or
+// if some workgroup already gave up.  The caller then skips to the kernel's exit protocol.
 // __syncthreads() makes every wave wait for its own outstanding atomics first.
-__device__ inline void grid_barrier(SelState *st, uint32_t target)
+__device__ inline bool grid_barrier(SelState *st, uint32_t target, uint32_t spin_limit, uint32_t *ok_slot)
 {
     __syncthreads();
     if (threadIdx.x == 0) {
         __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        uint32_t spins = 0;
+        uint32_t spins = 0, ok = 1;
         while (dev_load(&st->barrier) < target) {
-            if (++spins > SPIN_LIMIT) {
+            if (++spins > spin_limit || ((spins & 31u) == 0 && dev_load(&st->error) != 0)) {
                 dev_store(&st->error, 1u);
+                ok = 0;
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
+        *ok_slot = ok;
     }
     __syncthreads();
+    return *ok_slot != 0;
 }
 
 // Finds the digit d with #{digit > d} < k_rem <= #{digit >= d} in the merged histogram
@@ -462,11 +476,12 @@ __device__ inline void resolve_digit_local(const uint32_t *hist, uint32_t &prefi
     __syncthreads();
 }
 
+// The parallel selection; false (in every thread) if a grid barrier gave up, in which case the
+// outputs are incomplete (whatever was written is correct, nothing is out of bounds).
 template <typename RAW>
-__global__ void __launch_bounds__(SEL_THREADS)
-select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k, SelState *st,
-                    uint32_t *hist0, uint32_t *hist1, uint32_t *table, RAW *__restrict__ vals,
-                    int32_t *__restrict__ idx)
+__device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k,
+                                         SelState *st, uint32_t *hist0, uint32_t *hist1, uint32_t *table,
+                                         RAW *__restrict__ vals, int32_t *__restrict__ idx, uint32_t spin_limit)
 {
     constexpr int VEC = KeyTraits<RAW>::VEC;
     constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
@@ -561,14 +576,17 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
             if (c) atomicAdd(&ghist[i], c);
         }
         STAMP();
-        grid_barrier(st, ++barriers * G);
+        if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return false;
         STAMP();
         resolve_digit_local<NB, BITS>(ghist, prefix, k_rem, wave_tot, bcast);
         STAMP();
+        return true;
     };
-    hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{}, std::true_type{}, hist0);
+    if (!hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{}, std::true_type{}, hist0))
+        return false;
     if constexpr (F32)
-        hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{}, std::false_type{}, hist1);
+        if (!hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{}, std::false_type{}, hist1))
+            return false;
 
     // ---- last digit and per-chunk counts -------------------------------------------
     for (int i = tid; i < LB + 1 + WAVE; i += SEL_THREADS) lh[i] = 0;
@@ -588,7 +606,7 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
     __syncthreads();
     if (tid <= LB) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
     STAMP();
-    grid_barrier(st, ++barriers * G);
+    if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return false;
     STAMP();
 
     for (int b = tid / WAVE; b < LB; b += NW) {      // totals per bin over all chunks
@@ -636,7 +654,7 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
     // The kept elements of a tile occupy consecutive output slots; they are gathered in
     // LDS first so that the global stores are contiguous.
     auto keep = [&](uint32_t pos, uint32_t raw, int64_t i) {
-        if (pos < k) {                     // always true unless a grid barrier gave up
+        if (pos < k) {                     // always true for consistent counts
             vals[pos] = static_cast<RAW>(raw);
             idx[pos] = static_cast<int32_t>(i);
         }
@@ -674,7 +692,7 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
         const uint32_t tile_kept = run_gt + min(run_eq, m) - tile_first;
         __syncthreads();
         for (uint32_t s = tid; s < tile_kept; s += SEL_THREADS)
-            if (tile_first + s < k) {      // always true unless a grid barrier gave up
+            if (tile_first + s < k) {      // always true for consistent counts
                 vals[tile_first + s] = stage_val[s];
                 idx[tile_first + s] = stage_idx[s];
             }
@@ -704,6 +722,132 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
         }
     }
 #undef STAMP
+    return true;
+}
+
+// The whole selection by ONE workgroup, phase after phase over the whole tensor: same digits,
+// same slot formula, histograms in LDS, nothing read from the workspace.  Only ever runs after
+// the parallel path gave up.  `lh` is LDS scratch of (1 << 13) + 2 * WAVE words.
+template <typename RAW>
+__device__ inline void select_serial(const RAW *__restrict__ x, int64_t numel, int64_t nvf, uint32_t k,
+                                     RAW *__restrict__ vals, int32_t *__restrict__ idx, uint32_t *lh,
+                                     uint32_t *wave_tot, uint32_t *bcast)
+{
+    constexpr int VEC = KeyTraits<RAW>::VEC;
+    constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
+    constexpr bool F32 = sizeof(RAW) == 4;
+    constexpr int LAST_BITS = F32 ? 5 : 4;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const u32x4 *xv = reinterpret_cast<const u32x4 *>(x);
+    auto for_all = [&](auto f) {
+        for (int64_t v = tid; v < nvf; v += SEL_THREADS)
+            for_each_raw(RAW(0), xv[v], [&](uint32_t raw, int) { f(raw); });
+        if (tid == 0)
+            for (int64_t i = nvf * VEC; i < numel; ++i) f(x[i]);
+    };
+    uint32_t prefix = 0, k_rem = k;
+    auto pass = [&](auto shift_c, auto bits_c, auto first_c) {
+        constexpr int SHIFT = decltype(shift_c)::value, BITS = decltype(bits_c)::value;
+        constexpr bool FIRST = decltype(first_c)::value;
+        constexpr int NB = 1 << BITS;
+        __syncthreads();
+        for (int i = tid; i < NB + 2 * WAVE; i += SEL_THREADS) lh[i] = 0;
+        __syncthreads();
+        const uint32_t zslot = NB + lane, dslot = NB + WAVE + lane;
+        for_all([&](uint32_t raw) {
+            const uint32_t key = raw & MASK;
+            const uint32_t d = (key >> SHIFT) & (NB - 1);
+            uint32_t a = d ? d : zslot;
+            if (!FIRST) a = ((key >> (SHIFT + BITS)) == prefix) ? a : dslot;
+            atomicAdd(&lh[a], 1u);
+        });
+        __syncthreads();
+        if (tid < WAVE) {
+            const uint32_t z = wave_sum(lh[NB + tid]);
+            if (tid == 0) lh[0] += z;
+        }
+        __syncthreads();
+        resolve_digit_local<NB, BITS>(lh, prefix, k_rem, wave_tot, bcast);
+    };
+    if constexpr (F32) {
+        pass(std::integral_constant<int, 18>{}, std::integral_constant<int, 13>{}, std::true_type{});
+        pass(std::integral_constant<int, 5>{}, std::integral_constant<int, 13>{}, std::false_type{});
+    } else {
+        pass(std::integral_constant<int, 4>{}, std::integral_constant<int, 11>{}, std::true_type{});
+    }
+    pass(std::integral_constant<int, 0>{}, std::integral_constant<int, LAST_BITS>{}, std::false_type{});
+    const uint32_t t = prefix, m = k_rem;   // all digits resolved: the threshold key and its tie budget
+
+    uint32_t run_gt = 0, run_eq = 0;
+    auto keep = [&](uint32_t pos, uint32_t raw, int64_t i) {
+        if (pos < k) {
+            vals[pos] = static_cast<RAW>(raw);
+            idx[pos] = static_cast<int32_t>(i);
+        }
+    };
+    for (int64_t vb = 0; vb < nvf; vb += SEL_THREADS) {
+        const int64_t v = vb + tid;
+        const bool live = v < nvf;
+        u32x4 q = u32x4{0, 0, 0, 0};
+        if (live) q = xv[v];
+        uint32_t cnt = 0;                  // low 16 bits: #gt, high 16 bits: #eq (tile <= 8192 elements)
+        for_each_raw(RAW(0), q, [&](uint32_t raw, int) {
+            const uint32_t key = raw & MASK;
+            cnt += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
+        });
+        if (!live) cnt = 0;
+        uint32_t total;
+        const uint32_t excl = block_exclusive_scan<SEL_THREADS>(cnt, wave_tot, total);
+        uint32_t my_gt = run_gt + (excl & 0xFFFFu);
+        uint32_t my_eq = run_eq + (excl >> 16);
+        if (cnt) {
+            for_each_raw(RAW(0), q, [&](uint32_t raw, int e) {
+                const uint32_t key = raw & MASK;
+                const bool gt = key > t, eq = key == t;
+                if (gt || (eq && my_eq < m)) keep(my_gt + min(my_eq, m), raw, v * VEC + e);
+                my_gt += gt ? 1u : 0u;
+                my_eq += eq ? 1u : 0u;
+            });
+        }
+        run_gt += total & 0xFFFFu;
+        run_eq += total >> 16;
+    }
+    if (tid == 0) {
+        for (int64_t i = nvf * VEC; i < numel; ++i) {
+            const RAW raw = x[i];
+            const uint32_t key = raw & MASK;
+            const bool gt = key > t, eq = key == t;
+            if (gt || (eq && run_eq < m)) keep(run_gt + min(run_eq, m), raw, i);
+            run_gt += gt ? 1u : 0u;
+            run_eq += eq ? 1u : 0u;
+        }
+    }
+}
+
+template <typename RAW>
+__global__ void __launch_bounds__(SEL_THREADS)
+select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k, SelState *st,
+                    uint32_t *hist0, uint32_t *hist1, uint32_t *table, RAW *__restrict__ vals,
+                    int32_t *__restrict__ idx, uint32_t spin_limit)
+{
+    const bool ok = select_fused_body<RAW>(x, numel, nvf, vpc, k, st, hist0, hist1, table, vals, idx, spin_limit);
+    // Exit protocol: one atomic per workgroup counts the leavers and, in the high half, those that
+    // gave up.  The last to leave sees whether anybody did.  Everything the others stored to the
+    // outputs before leaving is either final or missing, never wrong, and the serial pass below
+    // uses no workspace, so it needs no ordering against their remaining traffic.
+    extern __shared__ __attribute__((aligned(16))) u32x4 dyn_smem[];
+    __shared__ uint32_t s_redo;
+    __shared__ uint32_t s_wave_tot[SEL_THREADS / WAVE];
+    __shared__ uint32_t s_bcast[2];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t mine = ok ? 1u : 0x10001u;
+        const uint32_t seen = __hip_atomic_fetch_add(&st->exited, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+        s_redo = ((seen & 0xFFFFu) == gridDim.x && (seen >> 16) != 0) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (s_redo)
+        select_serial<RAW>(x, numel, nvf, k, vals, idx, reinterpret_cast<uint32_t *>(dyn_smem), s_wave_tot, s_bcast);
 }
 
 struct Geometry {
@@ -745,50 +889,58 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
     init_kernel<<<32, 256, 0, stream>>>(reinterpret_cast<uint32_t *>(ws),
                                         static_cast<uint32_t>(SelWorkspace::zero_bytes / 4),
                                         static_cast<uint32_t>(k));
-    // Preferred: one cooperative kernel, one workgroup per compute unit.
-    {
-        static int cus = 0;
-        if (cus == 0) {
+    // Preferred: one persistent kernel, one workgroup per compute unit.
+    const int mode = select_mode();
+    if (mode != 1) {
+        constexpr int VEC = KeyTraits<RAW>::VEC;
+        constexpr int TILE_WORDS = SEL_THREADS * VEC + SEL_THREADS * VEC * int(sizeof(RAW)) / 4;
+        constexpr int HIST_WORDS = (sizeof(RAW) == 4 ? (1 << 13) : (1 << 11)) + 2 * WAVE;
+        constexpr size_t smem_bytes = size_t(FUSED_RES) * SEL_THREADS * 16 +
+                                      4 * size_t(TILE_WORDS > HIST_WORDS ? TILE_WORDS : HIST_WORDS);
+        static_assert(size_t(FUSED_RES) * SEL_THREADS * 16 >= 4 * ((size_t(1) << 13) + 2 * WAVE),
+                      "the serial fallback keeps its histogram where the chunk head was parked");
+        // how many workgroups of this kernel the device holds at once (asked once per element type)
+        static int capacity = 0;
+        if (capacity == 0) {
+            capacity = -1;
             hipDeviceProp_t prop;
-            int dev = 0;
-            if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-                cus = prop.multiProcessorCount;
-            if (cus <= 0 || cus > SEL_MAX_CHUNKS) cus = cus > SEL_MAX_CHUNKS ? SEL_MAX_CHUNKS : -1;
+            int dev = 0, per_cu = 0;
+            if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+                hipFuncSetAttribute(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    static_cast<int>(smem_bytes)) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, select_fused_kernel<RAW>, SEL_THREADS,
+                                                             smem_bytes) == hipSuccess &&
+                per_cu > 0 && prop.multiProcessorCount > 0)
+                capacity = std::min(per_cu * prop.multiProcessorCount, SEL_MAX_CHUNKS);
+            (void)hipGetLastError();
         }
-        if (cus > 0 && select_mode() == 0) {
-            constexpr int VEC = KeyTraits<RAW>::VEC;
+        if (capacity > 0) {
+            // chunk geometry: at most one workgroup per resident slot, chunks start on 128-byte lines
             int64_t nvf = numel / VEC;
-            int64_t chunks = (nvf + SEL_THREADS - 1) / SEL_THREADS;
-            if (chunks > cus) chunks = cus;
-            if (chunks < 1) chunks = 1;
-            int64_t vpc = (nvf + chunks - 1) / chunks;
-            vpc = (vpc + 7) / 8 * 8;
-            if (vpc < 8) vpc = 8;
-            chunks = (nvf + vpc - 1) / vpc;
-            if (chunks < 1) chunks = 1;
+            int64_t chunks = std::min<int64_t>(std::max<int64_t>((nvf + SEL_THREADS - 1) / SEL_THREADS, 1), capacity);
+            int64_t vpc = std::max<int64_t>(((nvf + chunks - 1) / chunks + 7) / 8 * 8, 8);
+            chunks = std::max<int64_t>((nvf + vpc - 1) / vpc, 1);
             uint32_t k32 = static_cast<uint32_t>(k);
+            uint32_t spin_limit = mode == 3 ? 0u : SPIN_LIMIT;
             RAW *vals_t = static_cast<RAW *>(vals);
-            void *args[] = {(void *)&xr, (void *)&numel, (void *)&nvf, (void *)&vpc, (void *)&k32, (void *)&st,
-                            (void *)&hist0, (void *)&hist1, (void *)&table, (void *)&vals_t, (void *)&idx};
             trace_mark(stream);
-            constexpr int TILE_WORDS = SEL_THREADS * VEC + SEL_THREADS * VEC * int(sizeof(RAW)) / 4;
-            constexpr int HIST_WORDS = (sizeof(RAW) == 4 ? (1 << 13) : (1 << 11)) + 2 * WAVE;
-            constexpr size_t smem_bytes = size_t(FUSED_RES) * SEL_THREADS * 16 +
-                                          4 * size_t(TILE_WORDS > HIST_WORDS ? TILE_WORDS : HIST_WORDS);
-            static bool attr_set = false;
-            if (!attr_set) {
-                attr_set = hipFuncSetAttribute(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               static_cast<int>(smem_bytes)) == hipSuccess;
+            if (mode == 2) {               // the runtime guarantees co-residency, at the price of slow queue switches
+                void *args[] = {(void *)&xr, (void *)&numel, (void *)&nvf, (void *)&vpc, (void *)&k32, (void *)&st,
+                                (void *)&hist0, (void *)&hist1, (void *)&table, (void *)&vals_t, (void *)&idx,
+                                (void *)&spin_limit};
+                if (hipLaunchCooperativeKernel(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
+                                               dim3(static_cast<unsigned>(chunks)), dim3(SEL_THREADS), args,
+                                               smem_bytes, stream) == hipSuccess) {
+                    trace_mark(stream);
+                    return launch_status();
+                }
+                (void)hipGetLastError();   // cooperative launch unavailable (e.g. stream capture): ordinary launch
             }
-            if (attr_set &&
-                hipLaunchCooperativeKernel(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
-                                           dim3(static_cast<unsigned>(chunks)), dim3(SEL_THREADS), args,
-                                           smem_bytes, stream) == hipSuccess) {
-                trace_mark(stream);
-                return launch_status();
-            }
-            (void)hipGetLastError();       // cooperative launch unavailable (e.g. stream capture): separate kernels
+            select_fused_kernel<RAW><<<dim3(static_cast<unsigned>(chunks)), dim3(SEL_THREADS), smem_bytes, stream>>>(
+                xr, numel, nvf, vpc, k32, st, hist0, hist1, table, vals_t, idx, spin_limit);
+            trace_mark(stream);
+            return launch_status();
         }
     }
     const dim3 grid(g.chunks), block(SEL_THREADS);
@@ -830,7 +982,7 @@ using namespace dropit;
 
 extern "C" dropit_status dropit_set_select_mode(int mode)
 {
-    if (mode != 0 && mode != 1) return DROPIT_EINVAL;
+    if (mode < 0 || mode > 3) return DROPIT_EINVAL;
     select_mode() = mode;
     return DROPIT_OK;
 }

@@ -81,7 +81,9 @@ def test_select_mode_switch_validates():
     L = dropit.lib()
     assert L.dropit_set_select_mode(1) == binding.OK
     assert L.dropit_set_select_mode(0) == binding.OK
-    assert L.dropit_set_select_mode(2) == binding.EINVAL
+    assert L.dropit_set_select_mode(2) == binding.OK
+    assert L.dropit_set_select_mode(3) == binding.OK
+    assert L.dropit_set_select_mode(4) == binding.EINVAL
     assert L.dropit_set_select_mode(-1) == binding.EINVAL
 
 

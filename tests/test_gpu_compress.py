@@ -125,8 +125,28 @@ def test_separate_kernel_mode_matches_oracle(dtype):
         dropit.set_select_mode(0)
 
 
-def test_separate_kernel_mode_in_a_hip_graph():
-    """The ordinary-kernel form replays correctly from a captured graph (no memset nodes inside)."""
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode,label", [(3, "forced serial redo"), (2, "cooperative launch")])
+def test_other_select_modes_match_oracle(dtype, mode, label):
+    """Mode 3 gives the grid barriers zero patience, so (nearly) every workgroup gives up and the last
+    one to leave redoes the selection alone; mode 2 launches the same kernel cooperatively.  Both
+    must give the oracle's bytes, and every kernel exits normally."""
+    dropit.set_select_mode(mode)
+    try:
+        for numel in (3, 9, 4097, 300003, (1 << 20) + 5):
+            x = activation((numel,), "relu", 600 + numel % 89, dtype)
+            for gamma in (0.9, 0.3):
+                run_and_compare(x, gamma, label)
+        if dtype == "bf16":
+            w = WORKLOADS["vitb_fc1"]
+            run_and_compare(activation(w.x_shape, w.x_dist, w.x_seed, w.dtype), w.gamma, label + " vitb_fc1")
+    finally:
+        dropit.set_select_mode(0)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_select_in_a_hip_graph(mode):
+    """Both ordinary-launch forms replay correctly from a captured graph (no memset nodes inside)."""
     x = activation((123457,), "gelu", 77, "bf16")
     xd = to_device(x)
     k = dropit.keep_count(x.size, 0.9)
@@ -134,7 +154,7 @@ def test_separate_kernel_mode_in_a_hip_graph():
     idx = torch.zeros(k, dtype=torch.int32, device="cuda:0")
     ws = torch.empty(dropit.compress_workspace_bytes(x.size, xd.dtype), dtype=torch.uint8, device="cuda:0")
     want_v, want_i = oracle.compress(x, k)
-    dropit.set_select_mode(1)
+    dropit.set_select_mode(mode)
     try:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
