@@ -51,15 +51,33 @@ inline void trace_mark(hipStream_t stream)
 int &select_mode();                              // per host thread; defined in compress.hip
 
 // ---- wave / block primitives (64-wide wavefronts) -----------------------
+// The 32-bit scans and sums run on the VALU's data-parallel primitives (row shifts inside
+// 16-lane rows, then the two row broadcasts), not on LDS-routed shuffles: a kernel with 16
+// wavefronts per compute unit that scans in a loop is otherwise bound by LDS instruction issue.
 
-__device__ inline uint32_t wave_sum(uint32_t v)
+// inclusive prefix sum across the 64 lanes of a wavefront
+__device__ inline uint32_t wave_inclusive_scan(uint32_t v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    // lanes whose source lies outside the row (or whose row is masked off) add the `old` operand, 0
+#define DROPIT_DPP_ADD(ctrl, row_mask) \
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), ctrl, row_mask, 0xf, false))
+    DROPIT_DPP_ADD(0x111, 0xf);   // row_shr:1
+    DROPIT_DPP_ADD(0x112, 0xf);   // row_shr:2
+    DROPIT_DPP_ADD(0x114, 0xf);   // row_shr:4
+    DROPIT_DPP_ADD(0x118, 0xf);   // row_shr:8   -> inclusive inside each row of 16
+    DROPIT_DPP_ADD(0x142, 0xa);   // row_bcast:15 into rows 1 and 3
+    DROPIT_DPP_ADD(0x143, 0xc);   // row_bcast:31 into rows 2 and 3
+#undef DROPIT_DPP_ADD
     return v;
 }
 
-// inclusive prefix sum across the 64 lanes of a wavefront
+// sum over the 64 lanes, in every lane
+__device__ inline uint32_t wave_sum(uint32_t v)
+{
+    return uint32_t(__builtin_amdgcn_readlane(int(wave_inclusive_scan(v)), WAVE - 1));
+}
+
+// generic (slow) form for other types
 template <typename T>
 __device__ inline T wave_inclusive_scan(T v)
 {
@@ -72,29 +90,51 @@ __device__ inline T wave_inclusive_scan(T v)
     return v;
 }
 
-// Exclusive prefix sum over a block of THREADS threads (THREADS % 64 == 0).
+// Exclusive prefix sum over a block of THREADS threads (THREADS % 64 == 0, at most 64 wavefronts).
 // `wave_tot` is LDS scratch of THREADS/64 entries.  Returns the exclusive
 // prefix of `v`; `total` receives the block sum.  Contains two barriers, so
 // every thread of the block must call it.
-template <int THREADS, typename T>
-__device__ inline T block_exclusive_scan(T v, T *wave_tot, T &total)
+template <int THREADS>
+__device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t &total)
 {
     constexpr int NW = THREADS / WAVE;
+    static_assert(NW <= WAVE, "the wavefront totals are scanned by one wavefront's lanes");
     const int lane = threadIdx.x & (WAVE - 1);
-    const int w = threadIdx.x / WAVE;
-    T inc = wave_inclusive_scan(v);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const uint32_t inc = wave_inclusive_scan(v);
     __syncthreads();                      // protects wave_tot reuse across calls
     if (lane == WAVE - 1) wave_tot[w] = inc;
     __syncthreads();
-    T before = 0, all = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        T t = wave_tot[i];
-        if (i < w) before += t;
-        all += t;
-    }
-    total = all;
+    // every wavefront scans the totals itself: lane j holds wavefront j's
+    const uint32_t t = lane < NW ? wave_tot[lane] : 0u;
+    const uint32_t tinc = wave_inclusive_scan(t);
+    total = uint32_t(__builtin_amdgcn_readlane(int(tinc), WAVE - 1));
+    const uint32_t before = uint32_t(__builtin_amdgcn_readlane(int(tinc), w)) - uint32_t(__builtin_amdgcn_readlane(int(t), w));
     return before + inc - v;
+}
+
+// Two independent exclusive block scans sharing their barriers (a[2], b[2] of wave_tot2 rows).
+template <int THREADS>
+__device__ inline void block_exclusive_scan2(uint32_t va, uint32_t vb, uint32_t *wave_tot2 /*[2][THREADS/64]*/,
+                                             uint32_t &ea, uint32_t &eb, uint32_t &ta, uint32_t &tb)
+{
+    constexpr int NW = THREADS / WAVE;
+    static_assert(NW <= WAVE, "the wavefront totals are scanned by one wavefront's lanes");
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const uint32_t ia = wave_inclusive_scan(va), ib = wave_inclusive_scan(vb);
+    __syncthreads();
+    if (lane == WAVE - 1) {
+        wave_tot2[w] = ia;
+        wave_tot2[NW + w] = ib;
+    }
+    __syncthreads();
+    const uint32_t xa = lane < NW ? wave_tot2[lane] : 0u, xb = lane < NW ? wave_tot2[NW + lane] : 0u;
+    const uint32_t sa = wave_inclusive_scan(xa), sb = wave_inclusive_scan(xb);
+    ta = uint32_t(__builtin_amdgcn_readlane(int(sa), WAVE - 1));
+    tb = uint32_t(__builtin_amdgcn_readlane(int(sb), WAVE - 1));
+    ea = uint32_t(__builtin_amdgcn_readlane(int(sa), w)) - uint32_t(__builtin_amdgcn_readlane(int(xa), w)) + ia - va;
+    eb = uint32_t(__builtin_amdgcn_readlane(int(sb), w)) - uint32_t(__builtin_amdgcn_readlane(int(xb), w)) + ib - vb;
 }
 
 }  // namespace dropit

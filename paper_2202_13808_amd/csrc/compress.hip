@@ -216,7 +216,7 @@ count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc,
     constexpr int NW = SEL_THREADS / WAVE;
     __shared__ uint32_t lh[LB + 1 + WAVE];
     __shared__ uint32_t s_digit;
-    __shared__ unsigned long long wave_tot[NW];
+    __shared__ uint32_t wave_tot2[2 * NW];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int G = gridDim.x;
     for (int i = tid; i < LB + 1 + WAVE; i += SEL_THREADS) lh[i] = 0;
@@ -277,7 +277,7 @@ count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc,
     // exclusive scan over chunks of (#{key > t}, #{key == t}); consecutive chunks per thread
     constexpr int CPT = (SEL_MAX_CHUNKS + SEL_THREADS - 1) / SEL_THREADS;
     uint32_t gt[CPT], eq[CPT];
-    unsigned long long mine = 0;
+    uint32_t mine_gt = 0, mine_eq = 0;
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         const int c = tid * CPT + i;
@@ -292,18 +292,20 @@ count_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc,
             }
             gt[i] = g;
         }
-        mine += (static_cast<unsigned long long>(eq[i]) << 32) | gt[i];
+        mine_gt += gt[i];
+        mine_eq += eq[i];
     }
-    unsigned long long total;
-    unsigned long long run = block_exclusive_scan<SEL_THREADS>(mine, wave_tot, total);
+    uint32_t run_gt, run_eq, total_gt, total_eq;
+    block_exclusive_scan2<SEL_THREADS>(mine_gt, mine_eq, wave_tot2, run_gt, run_eq, total_gt, total_eq);
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         const int c = tid * CPT + i;
         if (c < G) {
-            off_gt[c] = static_cast<uint32_t>(run & 0xFFFFFFFFull);
-            off_eq[c] = static_cast<uint32_t>(run >> 32);
+            off_gt[c] = run_gt;
+            off_eq[c] = run_eq;
         }
-        run += (static_cast<unsigned long long>(eq[i]) << 32) | gt[i];
+        run_gt += gt[i];
+        run_eq += eq[i];
     }
 }
 
@@ -501,7 +503,7 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
     RAW *stage_val = reinterpret_cast<RAW *>(smem + TILE);
     __shared__ uint32_t bcast[4];
     __shared__ uint32_t wave_tot[NW];
-    __shared__ unsigned long long wave_tot64[NW];
+    __shared__ uint32_t wave_tot2[2 * NW];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int G = gridDim.x;
     const bool last_chunk = blockIdx.x == gridDim.x - 1;
@@ -589,16 +591,18 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
             return false;
 
     // ---- last digit and per-chunk counts -------------------------------------------
-    for (int i = tid; i < LB + 1 + WAVE; i += SEL_THREADS) lh[i] = 0;
+    for (int i = tid; i <= LB; i += SEL_THREADS) lh[i] = 0;
     __syncthreads();
     {
-        const uint32_t dslot = LB + 1 + lane;
+        // Few keys share the threshold's higher digits, so unlike the digit histograms this pass
+        // branches: a wavefront with no such key among its lanes skips the LDS atomic altogether
+        // (an LDS atomic costs its issue cycles whatever the number of active lanes).
         uint32_t above = 0;
         for_chunk([&](uint32_t raw) {
             const uint32_t key = raw & MASK;
             const uint32_t hi = key >> LAST_BITS;
             above += (hi > prefix) ? 1u : 0u;
-            atomicAdd(&lh[(hi == prefix) ? (key & (LB - 1)) : dslot], 1u);
+            if (hi == prefix) atomicAdd(&lh[key & (LB - 1)], 1u);
         });
         above = wave_sum(above);
         if (lane == 0 && above) atomicAdd(&lh[LB], above);
@@ -631,7 +635,7 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
     const uint32_t t = bcast[0], m = bcast[1];
     const int d = static_cast<int>(bcast[2]);
     // exclusive offsets of this chunk: sums over the chunks before it
-    unsigned long long mine = 0;
+    uint32_t mine_gt = 0, mine_eq = 0;
     for (int c = tid; c < static_cast<int>(blockIdx.x); c += SEL_THREADS) {
         uint32_t n[LB + 1];
 #pragma unroll
@@ -642,12 +646,14 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
             g += (b > d) ? n[b] : 0u;
             e = (b == d) ? n[b] : e;
         }
-        mine += (static_cast<unsigned long long>(e) << 32) | g;
+        mine_gt += g;
+        mine_eq += e;
     }
-    unsigned long long before;
-    (void)block_exclusive_scan<SEL_THREADS>(mine, wave_tot64, before);
-    uint32_t run_gt = static_cast<uint32_t>(before & 0xFFFFFFFFull);   // #{key > t} before this chunk
-    uint32_t run_eq = static_cast<uint32_t>(before >> 32);             // #{key == t} before this chunk
+    uint32_t run_gt, run_eq;               // #{key > t}, #{key == t} before this chunk: the block totals
+    {
+        uint32_t ex_gt, ex_eq;
+        block_exclusive_scan2<SEL_THREADS>(mine_gt, mine_eq, wave_tot2, ex_gt, ex_eq, run_gt, run_eq);
+    }
     STAMP();
 
     // ---- ordered compaction -------------------------------------------------------
@@ -660,32 +666,40 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
         }
     };
     auto emit_tile = [&](const u32x4 &q, int64_t v, bool live) {
-        uint32_t cnt = 0;
-        for_each_raw(RAW(0), q, [&](uint32_t raw, int) {
+        // bit e of gtm / eqm: element e of this thread's vector has key > t / key == t
+        uint32_t gtm = 0, eqm = 0;
+        for_each_raw(RAW(0), q, [&](uint32_t raw, int e) {
             const uint32_t key = raw & MASK;
-            cnt += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
+            gtm |= (key > t ? 1u : 0u) << e;
+            eqm |= (key == t ? 1u : 0u) << e;
         });
-        if (!live) cnt = 0;
+        if (!live) gtm = eqm = 0;
+        const uint32_t cnt = __builtin_popcount(gtm) | (__builtin_popcount(eqm) << 16);
         uint32_t total;
         const uint32_t excl = block_exclusive_scan<SEL_THREADS>(cnt, wave_tot, total);
         const uint32_t tile_first = run_gt + min(run_eq, m);           // output slot of the tile's first kept element
         uint32_t my_gt = run_gt + (excl & 0xFFFFu);
         uint32_t my_eq = run_eq + (excl >> 16);
         const int64_t base = v * VEC;
-        if (cnt) {
-            // a kept element (key > t, or one of the first m keys == t) goes to output slot
-            // #gt-before + min(#eq-before, m): one formula for both cases
-            for_each_raw(RAW(0), q, [&](uint32_t raw, int e) {
-                const uint32_t key = raw & MASK;
-                const bool gt = key > t, eq = key == t;
+        // A kept element (key > t, or one of the first m keys == t) goes to output slot
+        // #gt-before + min(#eq-before, m): one formula for both cases.  Only the candidate
+        // elements are visited (a tenth of them at gamma = 0.9): every LDS store a wavefront
+        // issues costs its slot on the LDS pipe however few lanes take part.
+        uint32_t todo = gtm | eqm;
+        while (todo) {
+            const int e = __builtin_ctz(todo);
+            todo &= todo - 1;
+            const bool gt = (gtm >> e) & 1u;
+            if (gt || my_eq < m) {
                 const uint32_t slot = my_gt + min(my_eq, m) - tile_first;
-                if (gt || (eq && my_eq < m)) {
-                    stage_val[slot] = static_cast<RAW>(raw);
-                    stage_idx[slot] = static_cast<int32_t>(base + e);
-                }
-                my_gt += gt ? 1u : 0u;
-                my_eq += eq ? 1u : 0u;
-            });
+                uint32_t raw;
+                if constexpr (F32) raw = q[e];
+                else raw = (q[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+                stage_val[slot] = static_cast<RAW>(raw);
+                stage_idx[slot] = static_cast<int32_t>(base + e);
+            }
+            my_gt += gt ? 1u : 0u;
+            my_eq += gt ? 0u : 1u;
         }
         run_gt += total & 0xFFFFu;
         run_eq += total >> 16;

@@ -41,8 +41,16 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define DROPIT_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define DROPIT_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-constexpr int RECOVER_THREADS = 1024;
-constexpr int RECOVER_ELEMS = 32768;      // dense elements (64 KB of LDS) one recover workgroup builds
+#ifndef DROPIT_RECOVER_CFG
+#define DROPIT_RECOVER_CFG 256, 16384
+#endif
+constexpr int recover_cfg[2] = {DROPIT_RECOVER_CFG};
+constexpr int RECOVER_THREADS = recover_cfg[0];
+// Dense elements one recover workgroup builds in LDS.  Small tiles keep many workgroups resident
+// per compute unit, which hides the latency of each one's search; rows wider than that get the
+// large tile (64 KB of LDS), rows wider than the large tile take the generic path.
+constexpr int RECOVER_ELEMS = recover_cfg[1];
+constexpr int RECOVER_ELEMS_MAX = 32768;
 
 // ---------------------------------------------------------------------------
 // Cooperative lower_bound over a sorted int32 array for two targets at once
@@ -519,7 +527,7 @@ bool fc_dense_supported(const FcProblem &p)
     // 16-byte dY vectors need c_out % 8 == 0; per-lane byte offsets inside a token block are 32-bit;
     // a recover workgroup holds at least one padded row in LDS
     const int64_t pitch = (p.cin + 7) / 8 * 8;
-    return p.cout % 8 == 0 && p.cout >= 8 && p.cin >= 1 && pitch <= RECOVER_ELEMS &&
+    return p.cout % 8 == 0 && p.cout >= 8 && p.cin >= 1 && pitch <= RECOVER_ELEMS_MAX &&
            p.cout * Cfg::BK * 2 < (int64_t(1) << 31);
 }
 
@@ -531,7 +539,7 @@ FcDensePlan fc_dense_plan(const FcProblem &p)
     plan.mb_count = int((p.cout + Cfg::BM - 1) / Cfg::BM);
     plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
     plan.pitch = int((p.cin + 7) / 8 * 8);
-    plan.rows_per_wg = std::max(1, RECOVER_ELEMS / plan.pitch);
+    plan.rows_per_wg = std::max(1, (plan.pitch <= RECOVER_ELEMS ? RECOVER_ELEMS : RECOVER_ELEMS_MAX) / plan.pitch);
     plan.dense_bytes = round_up(size_t(plan.nkb) * Cfg::BK * plan.pitch * 2, 256);
     // K-slice partials are whole tiles (ragged edge tiles included) in accumulator order
     plan.partial_bytes = plan.splits > 1 ? size_t(plan.splits) * plan.nb_count * plan.mb_count * Cfg::BM * Cfg::BN * 4 : 0;
@@ -548,7 +556,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, RECOVER_ELEMS * 2) != hipSuccess ||
+                                hipFuncAttributeMaxDynamicSharedMemorySize, RECOVER_ELEMS_MAX * 2) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) != hipSuccess)
             return DROPIT_EHIP;
