@@ -134,10 +134,17 @@ fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__
 // GEMM: one workgroup = one BM x BN tile of dW over a contiguous range of token
 // blocks (one of `splits` K-slices).  WAVES_M x WAVES_N wavefronts, each a
 // (BM/WAVES_M) x (BN/WAVES_N) sub-tile built from 32x32x16 bf16 MFMAs.
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int WPE_, int EARLY_>
 struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    // WPE: wavefronts per SIMD the register budget must allow (2 = one workgroup of 8 per compute unit, 4 = two).
+    // EARLY: the first fragments of a token block are read during the previous block, so the matrix pipe never
+    // waits for LDS after a barrier; costs one more stage of load latency cover.  Without it the reads follow
+    // the barrier, which a second resident workgroup can hide.
+    static constexpr int WPE = WPE_;
+    static constexpr bool EARLY = EARLY_ != 0;
     static constexpr int NWAVES = WAVES_M * WAVES_N;
+    static constexpr int WGS_PER_CU = WPE * 4 / NWAVES;
     static constexpr int NTHREADS = WAVE * NWAVES;
     static constexpr int ROW_A = BM * 2, ROW_B = BN * 2;            // bytes per LDS row (one token)
     static constexpr int A_BYTES = BK * ROW_A, B_BYTES = BK * ROW_B;
@@ -152,7 +159,7 @@ struct GemmCfg {
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tiles must divide over the wavefronts");
     static_assert(ROW_A % 256 == 0 && ROW_B % 256 == 0, "the swizzle permutes the four 64-byte units of a 256-byte group");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "MFMA 32x32x16 tiling");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+    static_assert(WGS_PER_CU >= 1 && LDS_BYTES * WGS_PER_CU <= 160 * 1024, "LDS of one compute unit");
 };
 
 template <int N>
@@ -195,7 +202,7 @@ __device__ inline void static_for(F &&f)
 }
 
 template <typename C>
-__global__ void __launch_bounds__(C::NTHREADS)
+__global__ void __launch_bounds__(C::NTHREADS) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
 fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd, int64_t ntok, int M, int N,
                 int pitch, int nb_count, int mb_count, int nkb, int splits,
                 float *__restrict__ out /* dW or partials [splits][M][N] */)
@@ -336,10 +343,10 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     // wavefronts of a SIMD run in lockstep between barriers, so anything not tucked between MFMAs
     // would leave the matrix pipe idle in both at once; and a burst of loads would wait for the
     // address unit, which all eight wavefronts feed at the same time.
-    constexpr int LOAD_EVERY = (KK * NM) / C::LOADS;   // one global load per this many MFMAs
-    static_assert(LOAD_EVERY >= 1 && LOAD_EVERY * C::LOADS == KK * NM, "loads must spread evenly over a step's MFMAs");
-    auto substep = [&](auto kk_, auto next_kk_, uint32_t next_base, int load_stage, int load_kb) {
+    static_assert(C::LOADS <= KK * NM, "at most one global load rides behind each MFMA");
+    auto substep = [&](auto kk_, auto next_kk_, auto read_next_, uint32_t next_base, int load_stage, int load_kb) {
         constexpr int kk = decltype(kk_)::value, set = kk % 2;
+        constexpr bool read_next = decltype(read_next_)::value;
         lgkm_wait<0>();                                // the reads of this set were issued one sub-step ago
         bf16x8 af[C::FM], bfv[C::FN];
 #pragma unroll
@@ -357,27 +364,30 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             if (!(DROPIT_ABLATE & 8))
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
             static_for<m * READS_PER_MFMA, (m + 1) * READS_PER_MFMA>([&](auto r_) {
-                if constexpr (decltype(r_)::value < SET_READS)
+                if constexpr (read_next && decltype(r_)::value < SET_READS)
                     issue_read(std::integral_constant<int, 1 - set>{}, next_kk_, r_, next_base);
             });
             constexpr int g = kk * NM + m;             // MFMA number within the step
-            if constexpr (g % LOAD_EVERY == LOAD_EVERY - 1)
-                issue_load(std::integral_constant<int, g / LOAD_EVERY>{}, load_stage, load_kb);
+            static_for<0, C::LOADS>([&](auto q_) {     // load q rides behind MFMA (q + 1) * MFMAs / LOADS - 1
+                constexpr int q = decltype(q_)::value;
+                if constexpr (g == (q + 1) * KK * NM / C::LOADS - 1) issue_load(q_, load_stage, load_kb);
+            });
             __builtin_amdgcn_sched_barrier(0);
         });
     };
 
     // ---- pipeline --------------------------------------------------------------------
     // Token block t of the split lives in stage t % STAGES; its loads are issued D = STAGES - 1
-    // steps ahead.  LDS reads run one sub-step ahead of the MFMAs; for that the fragments of
-    // (step s + 1, sub-step 0) are read during step s, i.e. a stage must be complete one step
-    // before it is multiplied.
-    // Iteration s: wait until this wavefront's loads of step s + 1 have landed (the D - 2 newer
-    // steps may stay in flight), barrier (now everybody's have, and everybody is done reading
-    // step s - 1), then the sub-steps, which between them also refill the stage step s - 1 used
-    // with step s + D.
+    // steps ahead.  LDS reads run one sub-step ahead of the MFMAs.
+    // EARLY: the fragments of (step s + 1, sub-step 0) are read during step s, so a stage must be
+    // complete one step before it is multiplied.  Iteration s: wait until this wavefront's loads
+    // of step s + 1 have landed (the D - 2 newer steps may stay in flight), barrier (now
+    // everybody's have, and everybody is done reading step s - 1), then the sub-steps, which
+    // between them also refill the stage step s - 1 used with step s + D.
+    // Otherwise: wait for step s itself (D - 1 newer steps in flight), barrier, read sub-step 0,
+    // then the sub-steps; the exposed read is for a second resident workgroup to hide.
     // Loads past the last block are clamped to it instead of branched around, so the in-flight
-    // count is the same in every iteration; they land in stages that are read but never multiplied.
+    // count is the same in every iteration; they land in stages that are never multiplied.
 #ifdef DROPIT_PHASE_CLOCK          // development only: where does a wavefront's step go (100 MHz ticks)
     unsigned long long pc_t[5] = {0, 0, 0, 0, 0}, pc_sum[4] = {0, 0, 0, 0};
     const unsigned long long pc_begin = wall_clock64();
@@ -391,32 +401,40 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
 #endif
     if (steps > 0) {
         constexpr int D = C::STAGES - 1;
-        static_assert(D >= 2, "a stage is read one step early: three stages at least");
+        constexpr int AHEAD = C::EARLY ? 1 : 0;        // how many steps before its own a stage must be complete
+        static_assert(D >= 1 + AHEAD, "stages: one being multiplied, one per step of load latency, one more if read early");
         const int kb_last = kb_end - 1;
 #pragma unroll
         for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
-        wait_loads<(D - 1) * C::LOADS>();
-        workgroup_barrier();
-        static_for<0, SET_READS>([&](auto r_) {
-            issue_read(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, r_, lds_base);
-        });
+        if constexpr (C::EARLY) {
+            wait_loads<(D - 1) * C::LOADS>();
+            workgroup_barrier();
+            static_for<0, SET_READS>([&](auto r_) {
+                issue_read(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, r_, lds_base);
+            });
+        }
         int stage = 0, fill = D;                       // s % STAGES and (s + D) % STAGES
         for (int s = 0; s < steps; ++s) {
             const int next = stage + 1 == C::STAGES ? 0 : stage + 1;
             PHASE_CLOCK(0);
-            wait_loads<(D - 2) * C::LOADS>();
+            wait_loads<(D - 1 - AHEAD) * C::LOADS>();
             PHASE_CLOCK(1);
             workgroup_barrier();
             PHASE_CLOCK(2);
             const uint32_t cur_base = lds_base + stage * C::STAGE_BYTES;
             const uint32_t next_base = lds_base + next * C::STAGE_BYTES;
             const int load_kb = min(kb_begin + s + D, kb_last);
+            if constexpr (!C::EARLY)
+                static_for<0, SET_READS>([&](auto r_) {
+                    issue_read(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, r_, cur_base);
+                });
             static_for<0, KK>([&](auto kk_) {
                 constexpr int kk = decltype(kk_)::value;
                 if constexpr (kk + 1 < KK)
-                    substep(kk_, std::integral_constant<int, kk + 1>{}, cur_base, fill, load_kb);
+                    substep(kk_, std::integral_constant<int, kk + 1>{}, std::true_type{}, cur_base, fill, load_kb);
                 else
-                    substep(kk_, std::integral_constant<int, 0>{}, next_base, fill, load_kb);
+                    substep(kk_, std::integral_constant<int, 0>{}, std::integral_constant<bool, C::EARLY>{}, next_base,
+                            fill, load_kb);
                 if constexpr (kk == 0) PHASE_CLOCK(3);
             });
             PHASE_CLOCK(4);
@@ -502,15 +520,15 @@ splitk_sum_kernel(const f32x4 *__restrict__ partial, int splits, int M, int N, i
 }
 
 #ifndef DROPIT_GEMM_CFG
-#define DROPIT_GEMM_CFG 256, 256, 32, 4, 2, 4
+#define DROPIT_GEMM_CFG 256, 256, 32, 4, 2, 4, 2, 1
 #endif
 using Cfg = GemmCfg<DROPIT_GEMM_CFG>;
 
 int tuned_splits(int tiles, int nkb)
 {
-    // one workgroup per compute unit: as many K-slices as fill the 256 compute units
+    // as many K-slices as fill the 256 compute units (one or two resident workgroups each)
     // without starting a second round
-    int splits = 256 / tiles;
+    int splits = 256 * Cfg::WGS_PER_CU / tiles;
 #ifdef DROPIT_TUNING
     if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
 #endif
