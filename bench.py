@@ -44,8 +44,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--cold", action="store_true",
-                    help="rotate over several input copies so that x / dY never sit in the Infinity Cache")
+    ap.add_argument("--warm", action="store_true",
+                    help="time with ONE input copy (x / dY then stay in the 256 MB Infinity Cache) instead of "
+                         "rotating over > 600 MB of copies; the rotating (cold) figure is the default")
     return ap.parse_args()
 
 
@@ -119,7 +120,7 @@ def main():
         return torch.from_numpy(a).to(dev)
 
     copies = 1
-    if args.cold:
+    if not args.warm:
         per = xh.nbytes + dyh.nbytes
         copies = max(2, int(np.ceil(600e6 / per)))
     xs = [dev_tensor(xh) for _ in range(copies)]
@@ -148,6 +149,17 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
+    # beside it, outside the timed region that `value` comes from: the same steps on one input copy
+    warm_ms_per_step = ms_per_step
+    if copies > 1:
+        for i in range(min(args.warmup, 5)):
+            step(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(0)
+        torch.cuda.synchronize()
+        warm_ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
 
     if args.copy_calibration:
         src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
@@ -229,7 +241,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: x %s %s gamma=%.2f, dY %s, dW %s fp32%s" % (
             w.name, w.dtype, list(w.x_shape), w.gamma, list(w.dy_shape), list(w.dw_shape),
-            " (cold: %d rotating input copies)" % copies if args.cold else " (inputs warm in Infinity Cache)")},
+            " (cold: %d rotating input copies, %.0f MB)" % (copies, copies * (xh.nbytes + dyh.nbytes) / 1e6)
+            if copies > 1 else " (inputs warm in Infinity Cache)")},
+        "warm": {"ms_per_step": warm_ms_per_step, "value": flops / (warm_ms_per_step * 1e-3) * 1e-12,
+                 "note": "same steps on one input copy (x and dY stay in the 256 MB Infinity Cache)"},
         "event_overhead_ms": event_overhead_ms,
         "halves": {
             "compress_GBps": compress_bytes / (compress_ms * 1e-3) * 1e-9,

@@ -713,13 +713,76 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
         // the next tile's scan starts with a barrier, which also protects the staging buffers
     };
     __syncthreads();                       // histogram storage becomes staging storage
-    for (int64_t vb = v0, i = 0; vb < v1; vb += SEL_THREADS, ++i) {
-        const int64_t v = vb + tid;
-        const bool live = v < v1;
-        u32x4 q = u32x4{0, 0, 0, 0};
-        if (i < nres) q = res[i * SEL_THREADS + tid];
-        else if (live) q = xv[v];
-        emit_tile(q, v, live);
+    // The parked part of the chunk is compacted in one go when what it keeps fits the staging
+    // buffers (always, unless most of the tensor is kept).  For that each thread takes `nres`
+    // CONSECUTIVE parked vectors (the other phases take every 1024th), so flat-index order is
+    // thread order and one block scan serves the whole part: two barriers + a gather + a
+    // write-out instead of that per 1024-vector tile.  Bit (i * VEC + e) of the masks stands for
+    // element e of the thread's i-th vector.
+    int64_t first_tile = 0;
+    {
+        const int64_t parked = min<int64_t>(max<int64_t>(v1 - v0, 0), int64_t(nres) * SEL_THREADS);   // vectors
+        const int64_t mine0 = int64_t(tid) * nres;                     // first parked vector of this thread
+        unsigned long long gtm = 0, eqm = 0;
+#pragma nounroll
+        for (int i = 0; i < nres; ++i) {
+            if (mine0 + i < parked) {
+                uint32_t g = 0, q = 0;
+                for_each_raw(RAW(0), res[mine0 + i], [&](uint32_t raw, int e) {
+                    const uint32_t key = raw & MASK;
+                    g |= (key > t ? 1u : 0u) << e;
+                    q |= (key == t ? 1u : 0u) << e;
+                });
+                gtm |= static_cast<unsigned long long>(g) << (i * VEC);
+                eqm |= static_cast<unsigned long long>(q) << (i * VEC);
+            }
+        }
+        uint32_t ex_gt, ex_eq, tot_gt, tot_eq;
+        block_exclusive_scan2<SEL_THREADS>(__builtin_popcountll(gtm), __builtin_popcountll(eqm), wave_tot2, ex_gt, ex_eq,
+                                           tot_gt, tot_eq);
+        const uint32_t part_first = run_gt + min(run_eq, m);
+        const uint32_t part_kept = (run_gt + tot_gt) + min(run_eq + tot_eq, m) - part_first;
+        if (part_kept <= uint32_t(TILE)) {                             // uniform over the workgroup
+            uint32_t my_gt = run_gt + ex_gt, my_eq = run_eq + ex_eq;
+            const RAW *res_raw = reinterpret_cast<const RAW *>(res);
+            unsigned long long todo = gtm | eqm;
+            while (todo) {
+                const int b = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const bool gt = (gtm >> b) & 1ull;
+                if (gt || my_eq < m) {
+                    const uint32_t slot = my_gt + min(my_eq, m) - part_first;
+                    stage_val[slot] = res_raw[mine0 * VEC + b];
+                    stage_idx[slot] = static_cast<int32_t>((v0 + mine0) * VEC + b);
+                }
+                my_gt += gt ? 1u : 0u;
+                my_eq += gt ? 0u : 1u;
+            }
+            run_gt += tot_gt;
+            run_eq += tot_eq;
+            __syncthreads();
+            for (uint32_t q = tid; q < part_kept; q += SEL_THREADS)
+                if (part_first + q < k) {          // always true for consistent counts
+                    vals[part_first + q] = stage_val[q];
+                    idx[part_first + q] = stage_idx[q];
+                }
+            first_tile = nres;                     // a tile's scan starts with a barrier: the staging buffers are free again
+        }
+    }
+    // The rest of the chunk (everything, if the parked part kept too much) goes tile by tile, one
+    // vector per thread; vectors that are not parked are fetched one tile ahead.
+    {
+        int64_t vb = v0 + first_tile * SEL_THREADS;
+        u32x4 ahead = u32x4{0, 0, 0, 0};
+        if (first_tile >= nres && vb + tid < v1) ahead = xv[vb + tid];
+        for (int64_t i = first_tile; vb < v1; vb += SEL_THREADS, ++i) {
+            const int64_t v = vb + tid;
+            const bool live = v < v1;
+            u32x4 q = ahead;
+            if (i < nres) q = res[i * SEL_THREADS + tid];
+            if (i + 1 >= nres && v + SEL_THREADS < v1) ahead = xv[v + SEL_THREADS];
+            emit_tile(q, v, live);
+        }
     }
     STAMP();
     if (last_chunk && tid == 0) {
