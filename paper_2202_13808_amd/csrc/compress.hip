@@ -713,20 +713,31 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
         // the next tile's scan starts with a barrier, which also protects the staging buffers
     };
     __syncthreads();                       // histogram storage becomes staging storage
-    // The parked part of the chunk is compacted in one go when what it keeps fits the staging
-    // buffers (always, unless most of the tensor is kept).  For that each thread takes `nres`
-    // CONSECUTIVE parked vectors (the other phases take every 1024th), so flat-index order is
-    // thread order and one block scan serves the whole part: two barriers + a gather + a
-    // write-out instead of that per 1024-vector tile.  Bit (i * VEC + e) of the masks stands for
-    // element e of the thread's i-th vector.
-    int64_t first_tile = 0;
-    {
-        const int64_t parked = min<int64_t>(max<int64_t>(v1 - v0, 0), int64_t(nres) * SEL_THREADS);   // vectors
-        const int64_t mine0 = int64_t(tid) * nres;                     // first parked vector of this thread
+    // The chunk is compacted in super-tiles of FUSED_RES x 1024 vectors that sit in the parking
+    // area: the first one is the parked head itself, the following ones are fetched (coalesced,
+    // one super-tile ahead, through registers) into the same area.  Inside a super-tile each thread
+    // takes `rows` CONSECUTIVE vectors (the other phases take every 1024th), so flat-index order is
+    // thread order and one block scan serves the whole super-tile: two barriers + a gather + a
+    // write-out per 49152 elements.  Bit (i * VEC + e) of the masks stands for element e of the
+    // thread's i-th vector.  A super-tile that keeps more than the staging buffers hold (only when
+    // most of the tensor is kept) falls back to one scan per 1024-vector row.
+    constexpr int64_t SUPER = int64_t(FUSED_RES) * SEL_THREADS;
+    auto fetch = [&](u32x4 (&pre)[FUSED_RES], int64_t sb) {       // vectors [sb, sb + SUPER) n [.., v1), clamped loads
+#pragma unroll
+        for (int i = 0; i < FUSED_RES; ++i)
+            pre[i] = (sb < v1) ? xv[min(sb + int64_t(i) * SEL_THREADS + tid, v1 - 1)] : u32x4{0, 0, 0, 0};
+    };
+    u32x4 pre[FUSED_RES];
+    for (int64_t sb = v0; sb < v1; sb += SUPER) {
+        const int64_t count = min<int64_t>(v1 - sb, SUPER);          // vectors of this super-tile, all in `res`
+        const int rows = static_cast<int>((count + SEL_THREADS - 1) / SEL_THREADS);
+        const bool more = sb + SUPER < v1;
+        if (more) fetch(pre, sb + SUPER);
+        const int64_t mine0 = int64_t(tid) * rows;                    // first vector of this thread
         unsigned long long gtm = 0, eqm = 0;
 #pragma nounroll
-        for (int i = 0; i < nres; ++i) {
-            if (mine0 + i < parked) {
+        for (int i = 0; i < rows; ++i) {
+            if (mine0 + i < count) {
                 uint32_t g = 0, q = 0;
                 for_each_raw(RAW(0), res[mine0 + i], [&](uint32_t raw, int e) {
                     const uint32_t key = raw & MASK;
@@ -753,7 +764,7 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
                 if (gt || my_eq < m) {
                     const uint32_t slot = my_gt + min(my_eq, m) - part_first;
                     stage_val[slot] = res_raw[mine0 * VEC + b];
-                    stage_idx[slot] = static_cast<int32_t>((v0 + mine0) * VEC + b);
+                    stage_idx[slot] = static_cast<int32_t>((sb + mine0) * VEC + b);
                 }
                 my_gt += gt ? 1u : 0u;
                 my_eq += gt ? 0u : 1u;
@@ -766,22 +777,17 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
                     vals[part_first + q] = stage_val[q];
                     idx[part_first + q] = stage_idx[q];
                 }
-            first_tile = nres;                     // a tile's scan starts with a barrier: the staging buffers are free again
+        } else {
+            for (int i = 0; i < rows; ++i) {       // row by row; a row's scan starts with a barrier, which frees the staging buffers
+                const int64_t v = sb + int64_t(i) * SEL_THREADS + tid;
+                emit_tile(res[i * SEL_THREADS + tid], v, v < v1);
+            }
         }
-    }
-    // The rest of the chunk (everything, if the parked part kept too much) goes tile by tile, one
-    // vector per thread; vectors that are not parked are fetched one tile ahead.
-    {
-        int64_t vb = v0 + first_tile * SEL_THREADS;
-        u32x4 ahead = u32x4{0, 0, 0, 0};
-        if (first_tile >= nres && vb + tid < v1) ahead = xv[vb + tid];
-        for (int64_t i = first_tile; vb < v1; vb += SEL_THREADS, ++i) {
-            const int64_t v = vb + tid;
-            const bool live = v < v1;
-            u32x4 q = ahead;
-            if (i < nres) q = res[i * SEL_THREADS + tid];
-            if (i + 1 >= nres && v + SEL_THREADS < v1) ahead = xv[v + SEL_THREADS];
-            emit_tile(q, v, live);
+        if (more) {
+            __syncthreads();                       // everybody is done with this super-tile's vectors and staging
+#pragma unroll
+            for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = pre[i];
+            __syncthreads();
         }
     }
     STAMP();
