@@ -213,7 +213,7 @@ def main():
     c_names = (["init", "select_fused"] if fused_select else
                ["init", "hist", "count", "compact"] if bf16 else ["init", "hist0", "hist1", "count", "compact"])
     g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
-               ["bucket_prep", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
+               ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
     grad_ms = float(g_med.sum())
 

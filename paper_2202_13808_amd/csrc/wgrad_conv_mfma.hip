@@ -9,12 +9,13 @@
 //             operand layout of v_mfma_f32_32x32x16_bf16, so fragments are loaded
 //             straight from global memory (16 bytes per lane), one per K step,
 //             shared by all 9 taps.
-//   B (a^)  : a prep kernel re-buckets the sorted (value, index) pairs by
-//             (image, input row, channel block).  The GEMM workgroup owns one image
-//             and a band of output rows, zero-fills LDS rows [channel][8 | W | 8]
-//             (zero pads left and right = the horizontal padding; rows outside the
-//             image stay zero = the vertical padding) and scatters its pairs with one
-//             16-bit store each.  A fragment for tap (u, v) is row oy+u-1 read at
+//   B (a^)  : the index-sorted (value, index) pairs of an NCHW tensor already are a CSR
+//             matrix over its (image, channel, row) rows; a prep kernel only marks where
+//             each row starts.  The GEMM workgroup owns one image and a band of output
+//             rows, zero-fills LDS rows [channel][8 | W | 8] (zero pads left and right =
+//             the horizontal padding; rows outside the image stay zero = the vertical
+//             padding) and scatters the pairs of its 64 channels (one contiguous run of
+//             the arrays per channel) with one 16-bit store each.  A fragment for tap (u, v) is row oy+u-1 read at
 //             ox+v-1: one aligned 16-byte read plus its two neighbouring dwords,
 //             funnel-shifted by one element in registers for v = 0 and v = 2.
 // One K step = 8 consecutive ox of TWO adjacent output rows (the two K-halves of the
@@ -34,90 +35,28 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int CT = 256;            // threads per GEMM workgroup (4 wavefronts: 2 j-halves x 2 c-halves)
 constexpr int BJ = 64, BC = 64;    // output-channel / input-channel block of a workgroup
-constexpr int PREP_T = 1024;
 
-__device__ inline int64_t block_lower_bound_1024(const int32_t *__restrict__ idx, int64_t n, int64_t target)
+// Prep: row_ptr[r] = number of pairs whose flat index lies before row r, for every row
+// r = (n * C + c) * H + h of W elements (row_ptr[R] = k).  One pass over idx: thread j looks at
+// pairs j - 1 and j and fills the row starts that fall between them.
+__global__ void __launch_bounds__(256)
+conv_rowptr_kernel(const int32_t *__restrict__ idx, int64_t k, int W, int64_t R, uint32_t *__restrict__ row_ptr)
 {
-    int64_t lo = 0, hi = n;
-    while (hi > lo) {
-        const int64_t span = hi - lo;
-        const int64_t step = (span + PREP_T - 1) / PREP_T;
-        const int64_t pos = lo + int64_t(threadIdx.x) * step;
-        const int pred = (pos < hi) && (int64_t(idx[pos]) < target);
-        const int c = __syncthreads_count(pred);
-        if (c == 0) {
-            hi = lo;
-        } else {
-            const int64_t nlo = lo + int64_t(c - 1) * step + 1;
-            const int64_t nhi = min(lo + int64_t(c) * step, hi);
-            lo = nlo;
-            hi = nhi;
-        }
-    }
-    return lo;
-}
-
-// Prep: one workgroup per image.  Buckets the image's pairs by (input row h, channel
-// block) and packs each as  value << 16 | local channel << 7 | w.  Order inside a bucket
-// is arbitrary (each pair has its own LDS slot), so it cannot affect dW.
-__global__ void __launch_bounds__(PREP_T)
-conv_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int C, int H,
-                   int W, int cb_count, uint32_t *__restrict__ packed, uint32_t *__restrict__ row_ptr)
-{
-    extern __shared__ uint32_t s_cnt[];                 // [2 * nbuckets + 1]
-    __shared__ uint32_t s_wave[PREP_T / WAVE];
-    const int tid = threadIdx.x;
-    const int n = blockIdx.x;
-    const int nbuckets = H * cb_count;
-    uint32_t *s_fill = s_cnt + nbuckets + 1;
-    const int64_t plane = int64_t(H) * W;
-    const int64_t img_first = int64_t(n) * C * plane;
-    const int64_t img_elems = int64_t(C) * plane;
-    const int64_t lo = block_lower_bound_1024(idx, k, img_first);
-    const int64_t hi = block_lower_bound_1024(idx, k, img_first + img_elems);
-    for (int i = tid; i < 2 * nbuckets + 1; i += PREP_T) s_cnt[i] = 0;
-    __syncthreads();
-    for (int64_t j = lo + tid; j < hi; j += PREP_T) {
-        const int64_t r = int64_t(idx[j]) - img_first;
-        if (r >= 0 && r < img_elems) {
-            const uint32_t c = uint32_t(r) / uint32_t(plane);
-            const uint32_t h = (uint32_t(r) - c * uint32_t(plane)) / uint32_t(W);
-            atomicAdd(&s_cnt[h * cb_count + c / BC], 1u);
-        }
-    }
-    __syncthreads();
-    uint32_t carry = 0;
-    for (int base = 0; base < nbuckets; base += PREP_T) {
-        const int b = base + tid;
-        const uint32_t c = (b < nbuckets) ? s_cnt[b] : 0u;
-        uint32_t total;
-        const uint32_t ex = block_exclusive_scan<PREP_T>(c, s_wave, total);
-        if (b < nbuckets) s_cnt[b] = carry + ex;
-        carry += total;
-        __syncthreads();
-    }
-    if (tid == 0) s_cnt[nbuckets] = carry;
-    __syncthreads();
-    uint32_t *rp = row_ptr + int64_t(n) * (nbuckets + 1);
-    for (int b = tid; b <= nbuckets; b += PREP_T) rp[b] = uint32_t(lo) + s_cnt[b];
-    for (int64_t j = lo + tid; j < hi; j += PREP_T) {
-        const int64_t r = int64_t(idx[j]) - img_first;
-        if (r >= 0 && r < img_elems) {
-            const uint32_t c = uint32_t(r) / uint32_t(plane);
-            const uint32_t rem = uint32_t(r) - c * uint32_t(plane);
-            const uint32_t h = rem / uint32_t(W);
-            const uint32_t w = rem - h * uint32_t(W);
-            const uint32_t b = h * cb_count + c / BC;
-            const uint32_t slot = atomicAdd(&s_fill[b], 1u);
-            packed[lo + s_cnt[b] + slot] = (uint32_t(vals[j]) << 16) | ((c % BC) << 7) | w;
-        }
+    for (int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; j <= k; j += int64_t(gridDim.x) * blockDim.x) {
+        const int64_t before = (j == 0) ? -1 : min<int64_t>(int64_t(idx[j - 1]) / W, R);
+        const int64_t here = (j == k) ? R : min<int64_t>(int64_t(idx[j]) / W, R);
+        for (int64_t r = max<int64_t>(before, -1) + 1; r <= here; ++r) row_ptr[r] = uint32_t(j);
     }
 }
 
 // GEMM: workgroup = (image n, band of RB output rows, 64 x 64 block of (j, c)).
+// AG = column groups (of 8) multiplied per step; the host picks the instantiation that wastes the
+// fewest padded groups for the row width at hand.
+template <int AG>
 __global__ void __launch_bounds__(CT)
-conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict__ packed,
-                    const uint32_t *__restrict__ row_ptr, int C, int H, int W, int J, int RB, int bands,
+conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ vals,
+                    const int32_t *__restrict__ idx, int64_t k, const uint32_t *__restrict__ row_ptr, int C, int H,
+                    int W, int J, int RB, int bands,
                     int cb_count, int jb_count, int pitch_c /*bytes per (row, channel)*/,
                     float *__restrict__ partial /*[N*bands][9][J][C]*/)
 {
@@ -134,25 +73,83 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict_
     const int slots = rows + 2;                        // input rows r0-1 .. r0+rows
     const int slot_bytes = BC * pitch_c;
 
+#ifdef DROPIT_PHASE_CLOCK
+    unsigned long long pc[5];
+    pc[0] = wall_clock64();
+#endif
     // ---- recover R(a^) for this band into LDS: zero fill, then scatter ------------
+    // Pairs of this band: for each of the 64 channels one contiguous run [first, last) of the arrays
+    // (input rows ih_lo .. ih_hi of that channel).  The runs are laid end to end (prefix sums of
+    // their lengths in LDS) and the threads stride over that flat range, so every thread has
+    // work and the loads of a run are coalesced.  The run bounds are fetched before the zero fill,
+    // which hides their latency.
+    __shared__ uint32_t s_first[BC], s_last[BC];
+    const int ih_lo = max(r0 - 1, 0), ih_hi = min(r0 + rows, H - 1);
+    uint32_t first = 0, last = 0;
+    if (tid < BC && cb * BC + tid < C) {
+        const int64_t row0 = (int64_t(n) * C + cb * BC + tid) * H;
+        first = row_ptr[row0 + ih_lo];
+        last = row_ptr[row0 + ih_hi + 1];
+    }
     {
         const int n16 = slots * slot_bytes / 16;
         for (int i = tid; i < n16; i += CT) reinterpret_cast<u32x4 *>(lds)[i] = u32x4{0, 0, 0, 0};
     }
+    if (tid < BC) {
+        first = min<uint32_t>(first, uint32_t(k));      // clamped: a malformed index array may
+        last = min<uint32_t>(last, uint32_t(k));        // leave row starts unwritten
+        s_first[tid] = first;
+        s_last[tid] = max(last, first);
+    }
     __syncthreads();
-    const uint32_t *rp = row_ptr + int64_t(n) * (H * cb_count + 1);
-    for (int s = 0; s < slots; ++s) {
-        const int ih = r0 - 1 + s;
-        if (ih < 0 || ih >= H) continue;               // vertical zero padding
-        const uint32_t lo = rp[ih * cb_count + cb], hi = rp[ih * cb_count + cb + 1];
-        char *row = lds + s * slot_bytes + 16;
-        for (uint32_t j = lo + tid; j < hi; j += CT) {
-            const uint32_t p = packed[j];
-            *reinterpret_cast<uint16_t *>(row + ((p >> 7) & 0x3Fu) * pitch_c + (p & 0x7Fu) * 2) = uint16_t(p >> 16);
+#ifdef DROPIT_PHASE_CLOCK
+    pc[1] = wall_clock64();
+#endif
+    // Each wavefront takes 16 of the 64 channels, SC at a time: the runs of SC channels are walked
+    // together so that SC x 2 loads per lane are in flight, and everything per channel (run bounds,
+    // plane offset, LDS row base) is wave-uniform scalar work.  Row and column of a pair come from
+    // its offset in the channel plane by a multiply-high with ceil(2^32 / W), exact here because
+    // the offset is far below 2^32 / W, and checked anyway.
+    constexpr int SC = 8;
+    const uint32_t w_magic = uint32_t(((1ull << 32) + uint32_t(W) - 1) / uint32_t(W));
+    const uint32_t plane = uint32_t(H) * uint32_t(W);
+    for (int c0 = wave * (BC / 4); c0 < (wave + 1) * (BC / 4); c0 += SC) {
+        uint32_t lo[SC], hi[SC], longest = 0;
+#pragma unroll
+        for (int q = 0; q < SC; ++q) {
+            lo[q] = __builtin_amdgcn_readfirstlane(s_first[c0 + q]);
+            hi[q] = __builtin_amdgcn_readfirstlane(s_last[c0 + q]);
+            longest = max(longest, hi[q] - lo[q]);
+        }
+        for (uint32_t off = lane; off < longest; off += WAVE) {
+            int flat[SC];
+            uint16_t val[SC];
+#pragma unroll
+            for (int q = 0; q < SC; ++q) {
+                const uint32_t at = min(lo[q] + off, uint32_t(k) - 1);   // unconditional, clamped (k > 0)
+                flat[q] = idx[at];
+                val[q] = vals[at];
+            }
+#pragma unroll
+            for (int q = 0; q < SC; ++q) {
+                if (lo[q] + off >= hi[q]) continue;
+                const int64_t base = (int64_t(n) * C + cb * BC + c0 + q) * int64_t(plane);   // scalar
+                const int64_t rel64 = int64_t(flat[q]) - base;                              // offset inside the channel plane
+                if (rel64 < 0 || rel64 >= int64_t(plane)) continue;   // never for a sorted, in-range index array
+                const uint32_t rel = uint32_t(rel64);
+                uint32_t ih = __umulhi(rel, w_magic);
+                if (ih * uint32_t(W) > rel) --ih;
+                const uint32_t w = rel - ih * uint32_t(W);
+                if (int(ih) >= ih_lo && int(ih) <= ih_hi && w < uint32_t(W))
+                    *reinterpret_cast<uint16_t *>(lds + (int(ih) - (r0 - 1)) * slot_bytes + 16 + (c0 + q) * pitch_c + w * 2) = val[q];
+            }
         }
     }
     __syncthreads();
 
+#ifdef DROPIT_PHASE_CLOCK
+    pc[2] = wall_clock64();
+#endif
     // ---- multiply ---------------------------------------------------------------
     f32x16 acc[9];
 #pragma unroll
@@ -162,20 +159,40 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict_
 
     const int kg = lane >> 5;                          // K-half: which row of the pair
     const int j = jb * BJ + wj * 32 + (lane & 31);
-    const int cl = wc * 32 + (lane & 31);
+    const int cl_b = wc * 32 + (lane & 31);            // this lane's input channel inside the block
     const int groups = W / 8;
     const int jc = min(j, J - 1);
-    for (int pr = 0; pr < rows; pr += 2) {
+    // The dY fragments come straight from global memory; they are fetched one chunk (a row pair x
+    // AG groups of 8 columns) ahead of the chunk being multiplied, all loads of a chunk in flight
+    // at once, so their latency hides behind a chunk's worth of MFMAs.  A chunk's body is
+    // branch-free (groups past the row get a zero dY fragment and a clamped LDS address), so
+    // the compiler can run its LDS reads ahead of the MFMAs across the whole chunk.
+    const int chunks = (groups + AG - 1) / AG;          // per row pair
+    const int n_steps = ((rows + 1) / 2) * chunks;
+    auto fetch = [&](u32x4 (&a)[AG], int step) {
+        const int pr = (step / chunks) * 2, t0 = (step % chunks) * AG;
         const int oy_l = pr + kg;                      // row inside the band
         const bool a_ok = (j < J) && (oy_l < rows);
         const int oy = r0 + min(oy_l, rows - 1);
         const uint16_t *arow = dY + ((int64_t(n) * J + jc) * H + oy) * W;
+#pragma unroll
+        for (int g = 0; g < AG; ++g) {
+            const u32x4 v4 = *reinterpret_cast<const u32x4 *>(arow + min(t0 + g, groups - 1) * 8);   // clamped, unconditional
+            a[g] = (a_ok && t0 + g < groups) ? v4 : u32x4{0, 0, 0, 0};
+        }
+    };
+    u32x4 cur[AG], nxt[AG];
+    fetch(cur, 0);
+    for (int step = 0; step < n_steps; ++step) {
+        fetch(nxt, min(step + 1, n_steps - 1));
+        const int pr = (step / chunks) * 2, t0 = (step % chunks) * AG;
+        const int oy_l = pr + kg;
         // slot of input row oy-1 (tap u = 0); a K-half past the band reads valid rows and multiplies by zero
-        const char *brow = lds + min(oy_l, rows - 1) * slot_bytes + cl * pitch_c + 16;
-        for (int t = 0; t < groups; ++t) {
-            u32x4 a4 = *reinterpret_cast<const u32x4 *>(arow + t * 8);
-            if (!a_ok) a4 = u32x4{0, 0, 0, 0};
-            const bf16x8 a = __builtin_bit_cast(bf16x8, a4);
+        const char *brow = lds + min(oy_l, rows - 1) * slot_bytes + cl_b * pitch_c + 16;
+#pragma unroll
+        for (int g = 0; g < AG; ++g) {
+            const int t = min(t0 + g, groups - 1);     // past the row: any valid address, the dY fragment is zero
+            const bf16x8 a = __builtin_bit_cast(bf16x8, cur[g]);
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const char *p = brow + u * slot_bytes + t * 16;
@@ -195,8 +212,13 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict_
                 acc[u * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b2, acc[u * 3 + 2], 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int g = 0; g < AG; ++g) cur[g] = nxt[g];
     }
 
+#ifdef DROPIT_PHASE_CLOCK
+    pc[3] = wall_clock64();
+#endif
     // ---- partial sums: [workgroup][tap][j][c] ------------------------------------
     float *dst = partial + (int64_t(n) * bands + band) * 9 * int64_t(J) * C;
 #pragma unroll
@@ -207,19 +229,41 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint32_t *__restrict_
             const int cc = cb * BC + wc * 32 + (lane & 31);
             if (jj < J && cc < C) dst[(int64_t(s) * J + jj) * C + cc] = acc[s][e];
         }
+#ifdef DROPIT_PHASE_CLOCK
+    pc[4] = wall_clock64();
+    if (blockIdx.x == gridDim.x / 2 && tid == 0) {
+        float *o = partial + int64_t(gridDim.x / (cb_count * jb_count)) * 9 * J * C;   // past the partials (the probe over-allocates)
+        for (int i = 0; i < 4; ++i) o[i] = float(pc[i + 1] - pc[i]);
+    }
+#endif
 }
 
-// dW[j][c][tap] = sum over workgroups (ascending) of partial[p][tap][j][c]
-__global__ void __launch_bounds__(256)
+// dW[j][c][tap] = sum over the GEMM workgroups' partials partial[p][tap][j][c], in a fixed order:
+// a workgroup takes 64 consecutive (tap, j, c) outputs; each of its 4 wavefronts adds a quarter
+// of the parts in ascending order, then the first wavefront adds the 4 sums in ascending order.
+constexpr int RED_GROUPS = 4;
+__global__ void __launch_bounds__(64 * RED_GROUPS)
 conv_reduce_kernel(const float *__restrict__ partial, int parts, int J, int C, float *__restrict__ dW)
 {
+    __shared__ float s_sum[RED_GROUPS][64];
     const int64_t jc = int64_t(J) * C;
     const int64_t total = jc * 9;
-    for (int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; i < total; i += int64_t(gridDim.x) * blockDim.x) {
-        float s = 0.f;
-        for (int p = 0; p < parts; ++p) s += partial[int64_t(p) * total + i];
-        const int64_t tap = i / jc, rem = i - tap * jc;             // i = (tap, j, c)
-        dW[rem * 9 + tap] = s;
+    const int o = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int64_t i = int64_t(blockIdx.x) * 64 + o;
+    float s = 0.f;
+    if (i < total) {
+        const int per = (parts + RED_GROUPS - 1) / RED_GROUPS;
+        const int p0 = grp * per, p1 = min(p0 + per, parts);
+        for (int p = p0; p < p1; ++p) s += partial[int64_t(p) * total + i];
+    }
+    s_sum[grp][o] = s;
+    __syncthreads();
+    if (grp == 0 && i < total) {
+        float t = s_sum[0][o];
+#pragma unroll
+        for (int g = 1; g < RED_GROUPS; ++g) t += s_sum[g][o];
+        const int64_t tap = i / jc, rem = i - tap * jc;                 // i = (tap, j, c)
+        dW[rem * 9 + tap] = t;
     }
 }
 
@@ -229,7 +273,7 @@ bool conv_mfma_supported(const ConvProblem &p)
 {
     if (p.W % 8 != 0 || p.W > 120 || p.H < 1) return false;
     const ConvPlan plan = conv_mfma_plan(p);
-    return plan.lds_bytes <= 160 * 1024 && int64_t(p.H) * plan.cb_count <= 8192 &&
+    return plan.lds_bytes <= 150 * 1024 && p.N * p.C * p.H < INT32_MAX &&
            int64_t(p.N) * plan.bands * plan.cb_count * plan.jb_count <= INT32_MAX;
 }
 
@@ -253,8 +297,8 @@ ConvPlan conv_mfma_plan(const ConvProblem &p)
     plan.rb = rb;
     plan.bands = int((p.H + rb - 1) / rb);
     plan.lds_bytes = size_t(rb + 2) * BC * plan.pitch_c;
-    plan.packed_bytes = round_up(size_t(p.k > 0 ? p.k : 1) * 4, 256);
-    plan.rowptr_bytes = round_up(size_t(p.N) * (p.H * plan.cb_count + 1) * 4, 256);
+    plan.packed_bytes = 0;
+    plan.rowptr_bytes = round_up(size_t(p.N * p.C * p.H + 1) * 4, 256);
     plan.partial_bytes = round_up(size_t(p.N) * plan.bands * 9 * p.J * p.C * 4, 256);
     return plan;
 }
@@ -262,32 +306,45 @@ ConvPlan conv_mfma_plan(const ConvProblem &p)
 dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const void *vals, const int32_t *idx,
                             const void *dY, float *dW, char *ws, hipStream_t stream)
 {
-    uint32_t *packed = reinterpret_cast<uint32_t *>(ws);
-    uint32_t *row_ptr = reinterpret_cast<uint32_t *>(ws + plan.packed_bytes);
-    float *partial = reinterpret_cast<float *>(ws + plan.packed_bytes + plan.rowptr_bytes);
+    uint32_t *row_ptr = reinterpret_cast<uint32_t *>(ws);
+    float *partial = reinterpret_cast<float *>(ws + plan.rowptr_bytes);
 
     trace_mark(stream);
-    const size_t bucket_lds = size_t(2 * p.H * plan.cb_count + 1) * 4;
-    conv_bucket_kernel<<<int(p.N), PREP_T, bucket_lds, stream>>>(static_cast<const uint16_t *>(vals), idx, p.k,
-                                                                 int(p.C), int(p.H), int(p.W), plan.cb_count, packed,
-                                                                 row_ptr);
+    const int64_t R = p.N * p.C * p.H;
+    const int prep_blocks = int(std::min<int64_t>((p.k + 1 + 255) / 256, 4096));
+    conv_rowptr_kernel<<<prep_blocks, 256, 0, stream>>>(idx, p.k, int(p.W), R, row_ptr);
     trace_mark(stream);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_mfma_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return DROPIT_EHIP;
-        attr_set = true;
+    // groups of 8 columns per row: take the chunk width (8, 7, 6 or 5) that pads the row least
+    const int groups = int(p.W / 8);
+    int ag = 8, padded = (groups + 7) / 8 * 8;
+    for (int cand = 7; cand >= 5; --cand) {
+        const int pc = (groups + cand - 1) / cand * cand;
+        if (pc < padded) {
+            ag = cand;
+            padded = pc;
+        }
     }
     const int grid = int(p.N) * plan.bands * plan.jb_count * plan.cb_count;
-    conv3x3_mfma_kernel<<<grid, CT, plan.lds_bytes, stream>>>(static_cast<const uint16_t *>(dY), packed, row_ptr,
-                                                              int(p.C), int(p.H), int(p.W), int(p.J), plan.rb,
-                                                              plan.bands, plan.cb_count, plan.jb_count, plan.pitch_c,
-                                                              partial);
+    auto launch = [&](auto kernel) -> dropit_status {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                150 * 1024) != hipSuccess)
+            return DROPIT_EHIP;
+        kernel<<<grid, CT, plan.lds_bytes, stream>>>(static_cast<const uint16_t *>(dY), static_cast<const uint16_t *>(vals),
+                                                     idx, p.k, row_ptr, int(p.C), int(p.H), int(p.W), int(p.J), plan.rb,
+                                                     plan.bands, plan.cb_count, plan.jb_count, plan.pitch_c, partial);
+        return DROPIT_OK;
+    };
+    dropit_status st = DROPIT_OK;
+    switch (ag) {
+    case 5: st = launch(conv3x3_mfma_kernel<5>); break;
+    case 6: st = launch(conv3x3_mfma_kernel<6>); break;
+    case 7: st = launch(conv3x3_mfma_kernel<7>); break;
+    default: st = launch(conv3x3_mfma_kernel<8>); break;
+    }
+    if (st != DROPIT_OK) return st;
     trace_mark(stream);
     const int64_t total = p.J * p.C * 9;
-    const int blocks = int(std::min<int64_t>((total + 255) / 256, 2048));
-    conv_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, int(p.N) * plan.bands, int(p.J), int(p.C), dW);
+    conv_reduce_kernel<<<int((total + 63) / 64), 64 * RED_GROUPS, 0, stream>>>(partial, int(p.N) * plan.bands, int(p.J), int(p.C), dW);
     trace_mark(stream);
     return launch_status();
 }
