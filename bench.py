@@ -199,9 +199,8 @@ def main():
         dropit.trace_events(None)
     torch.cuda.synchronize()
     bf16 = w.dtype == "bf16"
-    # marks actually recorded per call: compress bf16 = init,hist,count,compact,end (5); fp32 has two hist passes (6)
-    fused_select = True                      # init + one cooperative select kernel (falls back to 4-5 kernels)
-    n_c = 3 if fused_select else (5 if bf16 else 6)
+    # marks recorded per compress call: before and after the one persistent select kernel
+    n_c = 2
     fc_mfma = bf16 and w.conv is None and w.c_out % 8 == 0
     conv_mfma = bf16 and w.conv is not None and w.x_shape[3] % 8 == 0
     mfma = fc_mfma or conv_mfma
@@ -210,8 +209,7 @@ def main():
     g_ms = np.array([event_ms(e[:n_g]) for e in ge])
     c_med = np.median(c_ms, axis=0)
     g_med = np.median(g_ms, axis=0)
-    c_names = (["init", "select_fused"] if fused_select else
-               ["init", "hist", "count", "compact"] if bf16 else ["init", "hist0", "hist1", "count", "compact"])
+    c_names = ["select_fused"]
     g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
                ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
@@ -223,7 +221,7 @@ def main():
     main_idx = 1
     main_ms = float(np.mean(g_ms[:, main_idx]))
     dw_tflops_kernel = flops / (main_ms * 1e-3) * 1e-12
-    hist_ms = float(np.mean(c_ms[:, 1]))
+    hist_ms = float(np.mean(c_ms[:, 0]))
     hist_gbps = compress_bytes / (hist_ms * 1e-3) * 1e-9
 
     out = {

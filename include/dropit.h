@@ -137,9 +137,10 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
 
 /*
  * How dropit_compress runs its select (per host thread):
- *   0 (default)  one persistent kernel, one workgroup per compute unit, grid barriers between
- *                its phases, launched as an ordinary kernel after checking that the grid fits
- *                the device at once; falls back to mode 1 if it does not.  Its barriers wait a
+ *   0 (default)  one persistent kernel (it also clears its own exchange area), one workgroup per
+ *                compute unit, grid barriers between its phases, launched as an ordinary kernel
+ *                after checking that the grid fits the device at once; falls back to mode 1 if
+ *                it does not.  Its barriers wait a
  *                bounded time; if the workgroups do not all become resident (a device shared
  *                with other persistent kernels) the kernel redoes the selection serially in its
  *                last workgroup, so the result is complete either way, only late.

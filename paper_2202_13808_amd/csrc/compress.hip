@@ -22,7 +22,9 @@
 // Nothing here synchronises with the host; counts are integer, so the result
 // does not depend on the order in which workgroups run.
 #include "common.hpp"
+#include <atomic>
 #include <cstdlib>
+#include <random>
 #include <type_traits>
 
 namespace dropit {
@@ -43,7 +45,9 @@ struct SelState {
     uint32_t barrier;    // arrivals at the fused kernel's grid barriers (monotone within a call)
     uint32_t error;      // hint: some workgroup ran out of patience at a grid barrier (the others stop waiting)
     uint32_t exited;     // fused kernel: low 16 bits = workgroups done, high 16 bits = how many of them gave up
-    uint32_t pad[53];
+    uint32_t pad0;
+    unsigned long long ready;    // == the call's generation number once workgroup 0 has cleared the words above and the histograms
+    uint32_t pad[50];
 };
 static_assert(sizeof(SelState) == 256, "state block is 256 bytes");
 
@@ -416,6 +420,14 @@ __device__ inline void dev_store(uint32_t *p, uint32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline unsigned long long dev_load64(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void dev_store64(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // All workgroups of the grid meet here.  The grid is sized so that every workgroup is resident at
 // once, but nothing enforces that the device is not shared, so the wait is bounded: returns false
@@ -478,12 +490,16 @@ __device__ inline void resolve_digit_local(const uint32_t *hist, uint32_t &prefi
     __syncthreads();
 }
 
-// The parallel selection; false (in every thread) if a grid barrier gave up, in which case the
-// outputs are incomplete (whatever was written is correct, nothing is out of bounds).
+// The parallel selection.  Returns (the same in every thread) SEL_DONE, or SEL_GAVE_UP if a grid
+// barrier ran out of patience, or SEL_NEVER_READY if the exchange area was never published; in the
+// last two cases the outputs are incomplete (whatever was written is correct, nothing is out of bounds).
+enum SelOutcome { SEL_DONE = 0, SEL_GAVE_UP = 1, SEL_NEVER_READY = 2 };
+
 template <typename RAW>
-__device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k,
+__device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k,
                                          SelState *st, uint32_t *hist0, uint32_t *hist1, uint32_t *table,
-                                         RAW *__restrict__ vals, int32_t *__restrict__ idx, uint32_t spin_limit)
+                                         RAW *__restrict__ vals, int32_t *__restrict__ idx, uint32_t spin_limit,
+                                         unsigned long long gen)
 {
     constexpr int VEC = KeyTraits<RAW>::VEC;
     constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
@@ -513,13 +529,32 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
 
     // ---- park the head of the chunk in LDS (each thread only ever reads its own slots) --
     const int nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
-    if (nvf > 0) {
+    {
         u32x4 q[FUSED_RES];
+        if (nvf > 0) {
 #pragma unroll
-        for (int i = 0; i < FUSED_RES; ++i)     // unconditional, clamped: all loads in flight at once
-            q[i] = xv[min(v0 + int64_t(i) * SEL_THREADS + tid, nvf - 1)];
+            for (int i = 0; i < FUSED_RES; ++i)     // unconditional, clamped: all loads in flight at once
+                q[i] = xv[min(v0 + int64_t(i) * SEL_THREADS + tid, nvf - 1)];
+        }
+        // Workgroup 0 clears what the workgroups exchange through (histograms, barrier counter) while its
+        // loads are in flight, then publishes this call's generation number; the others look for it before
+        // their first global atomic.  No separate clearing kernel, and a workspace with arbitrary contents
+        // is fine: a stale word equals the generation (a per-process random number plus a call count)
+        // with probability 2^-64.  Device-scope atomic stores, like everything else that is exchanged.
+        if (blockIdx.x == 0) {
+            for (int i = tid; i < 2 * (1 << MAX_HIST_BITS); i += SEL_THREADS) dev_store(hist0 + i, 0u);   // hist1 follows hist0
+            if (tid == 0) {
+                dev_store(&st->barrier, 0u);
+                dev_store(&st->error, 0u);
+                dev_store(&st->exited, 0u);
+            }
+            __syncthreads();                    // every wave has waited for its stores
+            if (tid == 0) dev_store64(&st->ready, gen);
+        }
+        if (nvf > 0) {
 #pragma unroll
-        for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
+            for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
+        }
     }
     const int64_t v_stream = v0 + int64_t(nres) * SEL_THREADS;        // first vector that is not parked
     // visits every element of the chunk: f(raw bits)
@@ -573,22 +608,39 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
             if (tid == 0) lh[0] += z;
         }
         __syncthreads();
+        if (FIRST) {                            // the exchange area must have been cleared for this call
+            if (tid == 0) {
+                uint32_t spins = 0, ok = 1;
+                while (dev_load64(&st->ready) != gen) {
+                    if (++spins > SPIN_LIMIT) {  // workgroup 0 never ran: not this workgroup's patience setting
+                        ok = 0;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                bcast[3] = ok;
+            }
+            __syncthreads();
+            if (bcast[3] == 0) return SEL_NEVER_READY;
+        }
         for (int i = tid; i < NB; i += SEL_THREADS) {
             const uint32_t c = lh[i];
             if (c) atomicAdd(&ghist[i], c);
         }
         STAMP();
-        if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return false;
+        if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return SEL_GAVE_UP;
         STAMP();
         resolve_digit_local<NB, BITS>(ghist, prefix, k_rem, wave_tot, bcast);
         STAMP();
-        return true;
+        return SEL_DONE;
     };
-    if (!hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{}, std::true_type{}, hist0))
-        return false;
+    if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{},
+                                       std::true_type{}, hist0))
+        return o;
     if constexpr (F32)
-        if (!hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{}, std::false_type{}, hist1))
-            return false;
+        if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{},
+                                           std::false_type{}, hist1))
+            return o;
 
     // ---- last digit and per-chunk counts -------------------------------------------
     for (int i = tid; i <= LB; i += SEL_THREADS) lh[i] = 0;
@@ -610,7 +662,7 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
     __syncthreads();
     if (tid <= LB) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
     STAMP();
-    if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return false;
+    if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return SEL_GAVE_UP;
     STAMP();
 
     for (int b = tid / WAVE; b < LB; b += NW) {      // totals per bin over all chunks
@@ -805,7 +857,7 @@ __device__ inline bool select_fused_body(const RAW *__restrict__ x, int64_t nume
         }
     }
 #undef STAMP
-    return true;
+    return SEL_DONE;
 }
 
 // The whole selection by ONE workgroup, phase after phase over the whole tensor: same digits,
@@ -911,22 +963,30 @@ template <typename RAW>
 __global__ void __launch_bounds__(SEL_THREADS)
 select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k, SelState *st,
                     uint32_t *hist0, uint32_t *hist1, uint32_t *table, RAW *__restrict__ vals,
-                    int32_t *__restrict__ idx, uint32_t spin_limit)
+                    int32_t *__restrict__ idx, uint32_t spin_limit, unsigned long long gen)
 {
-    const bool ok = select_fused_body<RAW>(x, numel, nvf, vpc, k, st, hist0, hist1, table, vals, idx, spin_limit);
+    const SelOutcome outcome =
+        select_fused_body<RAW>(x, numel, nvf, vpc, k, st, hist0, hist1, table, vals, idx, spin_limit, gen);
     // Exit protocol: one atomic per workgroup counts the leavers and, in the high half, those that
-    // gave up.  The last to leave sees whether anybody did.  Everything the others stored to the
-    // outputs before leaving is either final or missing, never wrong, and the serial pass below
+    // gave up at a barrier.  The last to leave sees whether anybody did.  Everything the others stored
+    // to the outputs before leaving is either final or missing, never wrong, and the serial pass below
     // uses no workspace, so it needs no ordering against their remaining traffic.
+    // A workgroup that never saw the exchange area published (workgroup 0, although dispatched first,
+    // did not get through its first few microseconds within the waiting time: not expected to happen)
+    // cannot rely on the counter either and simply redoes the selection itself; several doing so
+    // write identical bytes.
     extern __shared__ __attribute__((aligned(16))) u32x4 dyn_smem[];
     __shared__ uint32_t s_redo;
     __shared__ uint32_t s_wave_tot[SEL_THREADS / WAVE];
     __shared__ uint32_t s_bcast[2];
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t mine = ok ? 1u : 0x10001u;
-        const uint32_t seen = __hip_atomic_fetch_add(&st->exited, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
-        s_redo = ((seen & 0xFFFFu) == gridDim.x && (seen >> 16) != 0) ? 1u : 0u;
+        s_redo = 1u;
+        if (outcome != SEL_NEVER_READY) {
+            const uint32_t mine = outcome == SEL_DONE ? 1u : 0x10001u;
+            const uint32_t seen = __hip_atomic_fetch_add(&st->exited, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+            s_redo = ((seen & 0xFFFFu) == gridDim.x && (seen >> 16) != 0) ? 1u : 0u;
+        }
     }
     __syncthreads();
     if (s_redo)
@@ -955,6 +1015,17 @@ Geometry geometry(int64_t numel)
     return g;
 }
 
+// A number no earlier call of this process has used (a random start, then a count), never 0.
+unsigned long long next_generation()
+{
+    static std::atomic<unsigned long long> counter{[] {
+        std::random_device rd;
+        return (static_cast<unsigned long long>(rd()) << 32) ^ rd();
+    }()};
+    unsigned long long g = counter.fetch_add(1) + 1;
+    return g ? g : counter.fetch_add(1) + 1;
+}
+
 template <typename RAW>
 dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, int32_t *idx,
                            char *ws, hipStream_t stream)
@@ -968,10 +1039,12 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
     uint32_t *off_eq = reinterpret_cast<uint32_t *>(ws + SelWorkspace::offeq_off);
     const RAW *xr = static_cast<const RAW *>(x);
 
-    trace_mark(stream);
-    init_kernel<<<32, 256, 0, stream>>>(reinterpret_cast<uint32_t *>(ws),
-                                        static_cast<uint32_t>(SelWorkspace::zero_bytes / 4),
-                                        static_cast<uint32_t>(k));
+    auto clear_state = [&]() {                 // the separate kernels' clearing pass
+        trace_mark(stream);
+        init_kernel<<<32, 256, 0, stream>>>(reinterpret_cast<uint32_t *>(ws),
+                                            static_cast<uint32_t>(SelWorkspace::zero_bytes / 4),
+                                            static_cast<uint32_t>(k));
+    };
     // Preferred: one persistent kernel, one workgroup per compute unit.
     const int mode = select_mode();
     if (mode != 1) {
@@ -1007,11 +1080,12 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
             uint32_t k32 = static_cast<uint32_t>(k);
             uint32_t spin_limit = mode == 3 ? 0u : SPIN_LIMIT;
             RAW *vals_t = static_cast<RAW *>(vals);
+            unsigned long long gen = next_generation();
             trace_mark(stream);
             if (mode == 2) {               // the runtime guarantees co-residency, at the price of slow queue switches
                 void *args[] = {(void *)&xr, (void *)&numel, (void *)&nvf, (void *)&vpc, (void *)&k32, (void *)&st,
                                 (void *)&hist0, (void *)&hist1, (void *)&table, (void *)&vals_t, (void *)&idx,
-                                (void *)&spin_limit};
+                                (void *)&spin_limit, (void *)&gen};
                 if (hipLaunchCooperativeKernel(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
                                                dim3(static_cast<unsigned>(chunks)), dim3(SEL_THREADS), args,
                                                smem_bytes, stream) == hipSuccess) {
@@ -1021,11 +1095,12 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
                 (void)hipGetLastError();   // cooperative launch unavailable (e.g. stream capture): ordinary launch
             }
             select_fused_kernel<RAW><<<dim3(static_cast<unsigned>(chunks)), dim3(SEL_THREADS), smem_bytes, stream>>>(
-                xr, numel, nvf, vpc, k32, st, hist0, hist1, table, vals_t, idx, spin_limit);
+                xr, numel, nvf, vpc, k32, st, hist0, hist1, table, vals_t, idx, spin_limit, gen);
             trace_mark(stream);
             return launch_status();
         }
     }
+    clear_state();
     const dim3 grid(g.chunks), block(SEL_THREADS);
     trace_mark(stream);
     if constexpr (sizeof(RAW) == 2) {
