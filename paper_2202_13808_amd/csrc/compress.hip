@@ -59,7 +59,8 @@ struct SelWorkspace {
     static constexpr size_t table_off = hist1_off + sizeof(uint32_t) * (1u << MAX_HIST_BITS);
     static constexpr size_t offgt_off = table_off + sizeof(uint32_t) * (MAX_LAST_BINS + 1) * SEL_MAX_CHUNKS;
     static constexpr size_t offeq_off = offgt_off + sizeof(uint32_t) * SEL_MAX_CHUNKS;
-    static constexpr size_t bytes = offeq_off + sizeof(uint32_t) * SEL_MAX_CHUNKS;
+    static constexpr size_t xbar_off = offeq_off + sizeof(uint32_t) * SEL_MAX_CHUNKS;   // 8 arrival counters, 256 B apart
+    static constexpr size_t bytes = xbar_off + 8 * 256;
     static constexpr size_t zero_bytes = table_off;   // state + both histograms are cleared per call
 };
 
@@ -429,18 +430,26 @@ __device__ inline void dev_store64(unsigned long long *p, unsigned long long v)
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// All workgroups of the grid meet here.  The grid is sized so that every workgroup is resident at
-// once, but nothing enforces that the device is not shared, so the wait is bounded: returns false
-// (in every thread of the workgroup) if the others did not all arrive within `spin_limit` polls or
-// if some workgroup already gave up.  The caller then skips to the kernel's exit protocol.
+// All workgroups of the grid meet here (`round` = 1, 2, ... counts the barriers of the call).
+// Arrival is two-level: a workgroup bumps the counter of its group (launch order modulo 8, counters
+// 256 bytes apart), the last of a group bumps the top counter, everybody polls the top counter;
+// 256 atomics on ONE word take ~10 ns each, one after the other.
+// The grid is sized so that every workgroup is resident at once, but nothing enforces that the
+// device is not shared, so the wait is bounded: returns false (in every thread of the workgroup)
+// if the others did not all arrive within `spin_limit` polls or if some workgroup already gave
+// up.  The caller then skips to the kernel's exit protocol.
 // __syncthreads() makes every wave wait for its own outstanding atomics first.
-__device__ inline bool grid_barrier(SelState *st, uint32_t target, uint32_t spin_limit, uint32_t *ok_slot)
+__device__ inline bool grid_barrier(SelState *st, uint32_t *xbar, uint32_t round, uint32_t spin_limit, uint32_t *ok_slot)
 {
     __syncthreads();
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t G = gridDim.x, group = blockIdx.x & 7u;
+        const uint32_t groups = G < 8u ? G : 8u, members = (G - group + 7u) / 8u;
+        const uint32_t before = __hip_atomic_fetch_add(&xbar[group * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (before + 1 == round * members)
+            __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         uint32_t spins = 0, ok = 1;
-        while (dev_load(&st->barrier) < target) {
+        while (dev_load(&st->barrier) < round * groups) {
             if (++spins > spin_limit || ((spins & 31u) == 0 && dev_load(&st->error) != 0)) {
                 dev_store(&st->error, 1u);
                 ok = 0;
@@ -548,6 +557,8 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                 dev_store(&st->error, 0u);
                 dev_store(&st->exited, 0u);
             }
+            if (tid < 8)
+                dev_store(reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(st) + SelWorkspace::xbar_off) + tid * 64, 0u);
             __syncthreads();                    // every wave has waited for its stores
             if (tid == 0) dev_store64(&st->ready, gen);
         }
@@ -579,6 +590,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
 
     uint32_t prefix = 0, k_rem = k;
     uint32_t barriers = 0;
+    uint32_t *xbar = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(st) + SelWorkspace::xbar_off);
 #ifdef DROPIT_TUNING
     int stamp_i = 0;
 #define STAMP() do { if (tid == 0 && blockIdx.x == gridDim.x / 2) reinterpret_cast<unsigned long long *>(st->pad + 6)[stamp_i] = wall_clock64(); ++stamp_i; } while (0)
@@ -628,7 +640,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             if (c) atomicAdd(&ghist[i], c);
         }
         STAMP();
-        if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return SEL_GAVE_UP;
+        if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
         STAMP();
         resolve_digit_local<NB, BITS>(ghist, prefix, k_rem, wave_tot, bcast);
         STAMP();
@@ -662,7 +674,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     __syncthreads();
     if (tid <= LB) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
     STAMP();
-    if (!grid_barrier(st, ++barriers * G, spin_limit, &bcast[3])) return SEL_GAVE_UP;
+    if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
     STAMP();
 
     for (int b = tid / WAVE; b < LB; b += NW) {      // totals per bin over all chunks
