@@ -455,7 +455,7 @@ __device__ inline bool grid_barrier(SelState *st, uint32_t *xbar, uint32_t round
                 ok = 0;
                 break;
             }
-            __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_s_sleep(8);        // ~0.2 us between polls: 256 pollers on one word compete with the arrivals
         }
         *ok_slot = ok;
     }
@@ -551,7 +551,9 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         // is fine: a stale word equals the generation (a per-process random number plus a call count)
         // with probability 2^-64.  Device-scope atomic stores, like everything else that is exchanged.
         if (blockIdx.x == 0) {
-            for (int i = tid; i < 2 * (1 << MAX_HIST_BITS); i += SEL_THREADS) dev_store(hist0 + i, 0u);   // hist1 follows hist0
+            // only the bins this element type uses: bf16 one 2048-bin pass, fp32 two 8192-bin passes (hist1 follows hist0)
+            constexpr int CLEAR_WORDS = F32 ? 2 * (1 << MAX_HIST_BITS) : (1 << BITS1);
+            for (int i = tid; i < CLEAR_WORDS; i += SEL_THREADS) dev_store(hist0 + i, 0u);
             if (tid == 0) {
                 dev_store(&st->barrier, 0u);
                 dev_store(&st->error, 0u);
