@@ -192,3 +192,63 @@ def test_full_size_conv_sampled_filters():
     ref = np.stack([oracle.dw_conv(xh, dyw, 3, 3, (1, 1), (1, 1), j0=j, j1=j + 1)[0] for j in js])
     assert_close(got[js], ref, TOL["bf16"], np.abs(ref).max())
     assert np.isfinite(got).all()
+
+
+@pytest.mark.parametrize("conv", [None, CONV3])
+def test_weight_grad_is_bit_reproducible_and_ignores_workspace_contents(conv):
+    """Fixed summation order: the same inputs give the same dW bytes, whatever the workspace held before."""
+    print("wgrad determinism", conv, flush=True)
+    if conv is None:
+        x = activation((3000, 520), "normal", 21, "bf16")
+        dy = gradient((3000, 264), 0.02, 22, "bf16")
+        c_out = 264
+    else:
+        x = activation((3, 64, 28, 24), "relu", 23, "bf16")
+        dy = gradient((3, 40, 28, 24), 0.02, 24, "bf16")
+        c_out = 40
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, 0.85)
+    nbytes = dropit.weight_grad_workspace_bytes(x.shape, xd.dtype, vals.numel(), c_out, conv)
+    outs = []
+    for fill in (0, 255, 0x5A):
+        ws = torch.full((max(nbytes, 1),), fill, dtype=torch.uint8, device="cuda:0")
+        outs.append(to_host(dropit.weight_grad(vals, idx, x.shape, dyd, c_out, conv=conv, workspace=ws)).copy())
+    torch.cuda.synchronize()
+    assert outs[0].tobytes() == outs[1].tobytes() == outs[2].tobytes()
+
+
+@pytest.mark.parametrize("conv", [None, CONV3])
+def test_weight_grad_in_a_hip_graph(conv):
+    """dropit_weight_grad is ordinary kernel launches only: a captured graph replays it correctly."""
+    print("wgrad graph", conv, flush=True)
+    if conv is None:
+        x = activation((1500, 256), "gelu", 31, "bf16")
+        dy = gradient((1500, 136), 0.02, 32, "bf16")
+        c_out = 136
+    else:
+        x = activation((2, 32, 16, 16), "relu", 33, "bf16")
+        dy = gradient((2, 24, 16, 16), 0.02, 34, "bf16")
+        c_out = 24
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, 0.9)
+    ws = torch.empty(max(1, dropit.weight_grad_workspace_bytes(x.shape, xd.dtype, vals.numel(), c_out, conv)),
+                     dtype=torch.uint8, device="cuda:0")
+    dW = dropit.weight_grad(vals, idx, x.shape, dyd, c_out, conv=conv, workspace=ws)     # warm-up outside capture
+    torch.cuda.synchronize()
+    want = to_host(dW).copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dropit.weight_grad(vals, idx, x.shape, dyd, c_out, conv=conv, dW=dW, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        dropit.weight_grad(vals, idx, x.shape, dyd, c_out, conv=conv, dW=dW, workspace=ws)
+    for replay in range(3):
+        dW.zero_()
+        ws.fill_(replay * 41)                                             # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert to_host(dW).tobytes() == want.tobytes(), replay
