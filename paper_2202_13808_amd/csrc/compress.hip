@@ -4,23 +4,27 @@
 // The magnitude key of an element is its bit pattern with the sign cleared
 // (15 bits for bf16, 31 for fp32); unsigned key order == |x| order.
 //
-//   init      : clear histograms / tickets, seed the select state with k
+// The steps, whichever way they are launched:
 //   hist pass : MSB-first digit histogram of the keys that match the digits
 //               resolved so far (LDS histogram per workgroup, merged with
-//               global atomics; the last workgroup to arrive resolves the digit)
+//               global atomics), then the digit holding the k-th key is resolved
 //   count pass: resolves the last (4/5-bit) digit; every workgroup owns one
 //               contiguous chunk of x and records, per chunk, how many keys
 //               are above the resolved prefix and a small histogram of the
-//               matching ones.  The last workgroup derives the threshold key
-//               t, the tie budget m = k - #{key > t}, and the exclusive
-//               per-chunk offsets of {key > t} and {key == t}.
-//   compact   : each workgroup re-reads its chunk and writes (value, index)
-//               pairs in ascending index order; of the keys equal to t only
-//               the first m by flat index are kept.
-//
+//               matching ones.  From these follow the threshold key t, the tie
+//               budget m = k - #{key > t}, and the exclusive per-chunk offsets
+//               of {key > t} and {key == t}.
+//   compact   : each workgroup writes the (value, index) pairs of its chunk in
+//               ascending index order; of the keys equal to t only the first m
+//               by flat index are kept.
 // bf16: 11 + 4 bits (one hist pass); fp32: 13 + 13 + 5 bits (two hist passes).
-// Nothing here synchronises with the host; counts are integer, so the result
-// does not depend on the order in which workgroups run.
+//
+// Default: ONE persistent kernel (select_fused_kernel) does all of it with grid
+// barriers between the steps, the chunk parked in LDS, and a serial redo path
+// should the barriers ever give up.  Alternative: the steps as separate kernels
+// (init, hist, count, compact) with a last-workgroup-to-arrive ticket instead of
+// barriers.  Nothing here synchronises with the host; counts are integer, so the
+// result does not depend on the order in which workgroups run.
 #include "common.hpp"
 #include <atomic>
 #include <cstdlib>
