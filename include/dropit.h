@@ -45,7 +45,7 @@ typedef enum {
     DROPIT_OK = 0,
     DROPIT_EINVAL = 1,        /* null / misaligned pointer, bad shape, gamma outside [0,1], numel > 2^31-1 */
     DROPIT_EWORKSPACE = 2,    /* workspace smaller than the matching *_workspace_bytes query */
-    DROPIT_EUNSUPPORTED = 3,  /* a convolution geometry that is not implemented */
+    DROPIT_EUNSUPPORTED = 3,  /* reserved: a geometry that is not implemented (none at present) */
     DROPIT_EHIP = 4           /* a HIP launch failed */
 } dropit_status;
 
@@ -116,8 +116,10 @@ size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, drop
  *     OH = (H + 2*pad_h - dil_h*(kh-1) - 1)/stride_h + 1 (OW alike), type dt
  *     dW  [c_out, C, kh, kw] fp32:
  *     dW[j][c][u][v] = sum_{n,oy,ox} dY[n][j][oy][ox] * R(a^)[n][c][oy*sh-ph+u*dh][ox*sw-pw+v*dw]
- *     Only kh = kw = 3, stride 1, pad 1, dilation 1 is implemented; any other
- *     geometry returns DROPIT_EUNSUPPORTED.
+ *     bf16 with kh = kw = 3, stride 1, pad 1, dilation 1 (and W a multiple of 8, W <= 120)
+ *     runs on the matrix cores; every other geometry (kernel extents up to 1024,
+ *     stride / pad / dilation up to 65535) takes an exact but slow fp32 kernel.
+ *     DROPIT_EINVAL if the window does not fit the padded input.
  *
  *   vals, idx [in]  device, the k pairs written by dropit_compress for a tensor
  *                   of x_shape (idx strictly ascending, in range; not checked)

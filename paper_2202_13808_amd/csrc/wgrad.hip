@@ -124,10 +124,62 @@ conv3x3_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int
     if (tid < 9) dW[(int64_t(j) * C + c) * 9 + tid] = red[0][tid];
 }
 
+// ---- any other convolution geometry: one workgroup per (j, c), taps in chunks of 16 ----
+// Each thread walks the output positions (n, oy, ox) with a fixed stride and keeps 16 tap sums;
+// the workgroup adds them up in a fixed tree, so the result is reproducible.  Slow (the data is
+// walked once per 16 taps) but exact, for the geometries the matrix-core kernel does not take.
+constexpr int TAP_CHUNK = 16;
+template <typename RAW>
+__global__ void __launch_bounds__(256)
+conv_general_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int N, int C, int H, int W, int cout,
+                        int OH, int OW, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw,
+                        float *__restrict__ dW)
+{
+    __shared__ float red[256][TAP_CHUNK + 1];
+    const int j = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+    const int taps = kh * kw;
+    const int64_t oplane = int64_t(OH) * OW, iplane = int64_t(H) * W;
+    const int64_t positions = int64_t(N) * oplane;
+    for (int t0 = 0; t0 < taps; t0 += TAP_CHUNK) {
+        float acc[TAP_CHUNK];
+#pragma unroll
+        for (int q = 0; q < TAP_CHUNK; ++q) acc[q] = 0.f;
+        for (int64_t p = tid; p < positions; p += 256) {
+            const int n = int(p / oplane);
+            const int r = int(p - int64_t(n) * oplane);
+            const int oy = r / OW, ox = r - oy * OW;
+            const float g = to_f32(dY[(int64_t(n) * cout + j) * oplane + r]);
+            const RAW *xp = xhat + (int64_t(n) * C + c) * iplane;
+#pragma unroll
+            for (int q = 0; q < TAP_CHUNK; ++q) {
+                const int tap = t0 + q;                         // uniform
+                if (tap < taps) {
+                    const int u = tap / kw, v = tap - u * kw;
+                    const int64_t iy = int64_t(oy) * sh - ph + int64_t(u) * dh, ix = int64_t(ox) * sw - pw + int64_t(v) * dw;
+                    if (iy >= 0 && iy < H && ix >= 0 && ix < W) acc[q] = __builtin_fmaf(g, to_f32(xp[iy * W + ix]), acc[q]);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < TAP_CHUNK; ++q) red[tid][q] = acc[q];
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if (tid < s)
+#pragma unroll
+                for (int q = 0; q < TAP_CHUNK; ++q) red[tid][q] += red[tid + s][q];
+            __syncthreads();
+        }
+        if (tid < TAP_CHUNK && t0 + tid < taps) dW[(int64_t(j) * C + c) * taps + t0 + tid] = red[0][tid];
+        __syncthreads();
+    }
+}
+
 struct Problem {
     bool conv;
     int64_t numel, ntok, cin, cout;
-    int64_t N, C, H, W;
+    int64_t N, C, H, W, OH, OW;
+    dropit_conv2d g;
+    bool is_3x3_s1_p1;
 };
 
 // Validates shape arguments; returns DROPIT_OK and fills `p`.
@@ -139,6 +191,9 @@ dropit_status describe(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_
     if (p.numel < 1 || c_out < 1 || c_out > INT32_MAX) return DROPIT_EINVAL;
     p.cout = c_out;
     p.conv = conv != nullptr;
+    p.is_3x3_s1_p1 = false;
+    p.g = dropit_conv2d{};
+    p.N = p.C = p.H = p.W = p.OH = p.OW = 0;
     if (!p.conv) {
         p.cin = x_shape[ndim - 1];
         p.ntok = p.numel / p.cin;
@@ -149,11 +204,21 @@ dropit_status describe(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_
     if (conv->kh < 1 || conv->kw < 1 || conv->stride_h < 1 || conv->stride_w < 1 || conv->pad_h < 0 ||
         conv->pad_w < 0 || conv->dil_h < 1 || conv->dil_w < 1)
         return DROPIT_EINVAL;
-    if (conv->kh != 3 || conv->kw != 3 || conv->stride_h != 1 || conv->stride_w != 1 || conv->pad_h != 1 ||
-        conv->pad_w != 1 || conv->dil_h != 1 || conv->dil_w != 1)
-        return DROPIT_EUNSUPPORTED;
+    p.g = *conv;
+    p.is_3x3_s1_p1 = conv->kh == 3 && conv->kw == 3 && conv->stride_h == 1 && conv->stride_w == 1 && conv->pad_h == 1 &&
+                     conv->pad_w == 1 && conv->dil_h == 1 && conv->dil_w == 1;
     p.N = x_shape[0]; p.C = x_shape[1]; p.H = x_shape[2]; p.W = x_shape[3];
-    if (p.N * c_out * p.H * p.W > INT32_MAX * int64_t(16)) return DROPIT_EINVAL;
+    constexpr int64_t GEOM_MAX = 65535;              // keeps every index expression far inside 64 bits
+    if (conv->kh > 1024 || conv->kw > 1024 || conv->pad_h > GEOM_MAX || conv->pad_w > GEOM_MAX ||
+        conv->stride_h > GEOM_MAX || conv->stride_w > GEOM_MAX || conv->dil_h > GEOM_MAX || conv->dil_w > GEOM_MAX)
+        return DROPIT_EINVAL;
+    const int64_t eh = p.H + 2 * conv->pad_h - conv->dil_h * (conv->kh - 1) - 1;   // output extent: floor(e / stride) + 1
+    const int64_t ew = p.W + 2 * conv->pad_w - conv->dil_w * (conv->kw - 1) - 1;
+    if (eh < 0 || ew < 0) return DROPIT_EINVAL;                                    // the window does not fit the padded input
+    p.OH = eh / conv->stride_h + 1;
+    p.OW = ew / conv->stride_w + 1;
+    if (p.N * c_out * p.OH * p.OW > INT32_MAX * int64_t(16)) return DROPIT_EINVAL;
+    if (c_out * p.C * conv->kh * conv->kw > INT32_MAX) return DROPIT_EINVAL;
     return DROPIT_OK;
 }
 
@@ -180,8 +245,14 @@ dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx
                                                       int(p.cout), dW);
     } else {
         const dim3 grid(p.C, p.cout);
-        conv3x3_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), int(p.N), int(p.C),
-                                                           int(p.H), int(p.W), int(p.cout), dW);
+        if (p.is_3x3_s1_p1)
+            conv3x3_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), int(p.N), int(p.C),
+                                                               int(p.H), int(p.W), int(p.cout), dW);
+        else
+            conv_general_fma_kernel<RAW><<<grid, 256, 0, stream>>>(
+                dense, static_cast<const RAW *>(dY), int(p.N), int(p.C), int(p.H), int(p.W), int(p.cout), int(p.OH),
+                int(p.OW), int(p.g.kh), int(p.g.kw), int(p.g.stride_h), int(p.g.stride_w), int(p.g.pad_h),
+                int(p.g.pad_w), int(p.g.dil_h), int(p.g.dil_w), dW);
     }
     trace_mark(stream);
     return launch_status();
@@ -201,7 +272,7 @@ static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
         if (use_fc_dense(fp)) return fc_dense_plan(fp).total();
     }
-    if (p.conv && dt == DROPIT_BF16) {
+    if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
         if (conv_mfma_supported(cp)) return conv_mfma_plan(cp).total();
     }
@@ -235,7 +306,7 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
     if (k == 0) {                                  // everything was dropped: R(a^) = 0, so dW = 0
-        const int64_t n = p.conv ? p.cout * p.C * 9 : p.cout * p.cin;
+        const int64_t n = p.conv ? p.cout * p.C * p.g.kh * p.g.kw : p.cout * p.cin;
         zero_f32_kernel<<<int(std::min<int64_t>((n + 255) / 256, 2048)), 256, 0, stream>>>(dW, n);
         return launch_status();
     }
@@ -243,7 +314,7 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
         if (use_fc_dense(fp)) return fc_dense_run(fp, fc_dense_plan(fp), vals, idx, dY, dW, ws, stream);
     }
-    if (p.conv && dt == DROPIT_BF16 && k > 0) {
+    if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16 && k > 0) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
         if (conv_mfma_supported(cp)) return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
     }

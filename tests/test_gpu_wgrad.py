@@ -147,14 +147,37 @@ def test_conv3x3_integer_values_are_exact():
     assert np.array_equal(got, ref)
 
 
-def test_unsupported_conv_geometry_is_reported():
-    x = activation((1, 2, 8, 8), "relu", 1, "bf16")
-    dy = gradient((1, 2, 4, 4), 0.02, 2, "bf16")
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,C,H,W,J,geom", [
+    (2, 6, 9, 11, 5, (1, 1, 1, 1, 0, 0, 1, 1)),        # 1x1
+    (2, 3, 20, 22, 8, (7, 7, 2, 2, 3, 3, 1, 1)),       # 7x7 / stride 2 / pad 3 (first ResNet layer's geometry)
+    (3, 8, 15, 14, 4, (3, 3, 2, 2, 1, 1, 1, 1)),       # 3x3 / stride 2
+    (2, 3, 32, 48, 6, (16, 16, 16, 16, 0, 0, 1, 1)),   # 16x16 / stride 16 (ViT patch embedding)
+    (1, 4, 13, 17, 3, (3, 2, 1, 2, 2, 0, 2, 3)),       # asymmetric kernel, stride, pad, dilation
+    (2, 5, 12, 10, 7, (3, 3, 1, 1, 1, 1, 2, 2)),       # dilated 3x3: not the matrix-core geometry
+])
+def test_conv_general_geometries(dtype, N, C, H, W, J, geom):
+    """Every geometry other than 3x3/s1/p1 takes the exact fp32 kernel; same oracle (it is general)."""
+    kh, kw, sh, sw, ph, pw, dh, dw = geom
+    OH = (H + 2 * ph - dh * (kh - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (kw - 1) - 1) // sw + 1
+    print("wgrad conv general", dtype, N, C, H, W, J, geom, flush=True)
+    x = activation((N, C, H, W), "relu", 900 + H + kh, dtype)
+    dy = gradient((N, J, OH, OW), 0.02, 950 + W + kw, dtype)
+    got, _, _ = gpu_dw(x, dy, 0.6, J, conv=geom)
+    ref = oracle.dw_conv(ref_xhat(x, 0.6), oracle.widen(dy), kh, kw, (sh, sw), (ph, pw), (dh, dw))
+    assert got.shape == (J, C, kh, kw)
+    assert_close(got, ref, TOL[dtype])
+
+
+def test_conv_window_larger_than_input_is_rejected():
+    x = activation((1, 2, 4, 4), "relu", 1, "bf16")
+    dy = gradient((1, 2, 1, 1), 0.02, 2, "bf16")
     xd, dyd = to_device(x), to_device(dy)
     vals, idx = dropit.compress(xd, 0.5)
     with pytest.raises(dropit.DropitError) as e:
-        dropit.weight_grad(vals, idx, x.shape, dyd, 2, conv=(3, 3, 2, 2, 1, 1, 1, 1))
-    assert e.value.status == 3
+        dropit.weight_grad(vals, idx, x.shape, dyd, 2, conv=(7, 7, 1, 1, 0, 0, 1, 1))
+    assert e.value.status == 1
 
 
 @pytest.mark.parametrize("name", ["vitb_fc1", "vitb_fc2", "vitdet_fc1", "vitdet_fc2"])
