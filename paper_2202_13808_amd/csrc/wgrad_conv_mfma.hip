@@ -33,7 +33,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int CT = 256;            // threads per GEMM workgroup (4 wavefronts: 2 j-halves x 2 c-halves)
+constexpr int CT = 512;            // threads per GEMM workgroup: 2 K-groups x (2 j-halves x 2 c-halves) wavefronts
 constexpr int BJ = 64, BC = 64;    // output-channel / input-channel block of a workgroup
 
 // Prep: row_ptr[r] = number of pairs whose flat index lies before row r, for every row
@@ -62,7 +62,8 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wj = wave >> 1, wc = wave & 1;
+    const int wk = wave >> 2;                          // K-group: takes every other step of the band
+    const int wj = (wave >> 1) & 1, wc = wave & 1;
     int v = blockIdx.x;
     const int cb = v % cb_count; v /= cb_count;
     const int jb = v % jb_count; v /= jb_count;
@@ -105,7 +106,7 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
 #ifdef DROPIT_PHASE_CLOCK
     pc[1] = wall_clock64();
 #endif
-    // Each wavefront takes 16 of the 64 channels, SC at a time: the runs of SC channels are walked
+    // Each wavefront takes 8 of the 64 channels, SC at a time: the runs of SC channels are walked
     // together so that SC x 2 loads per lane are in flight, and everything per channel (run bounds,
     // plane offset, LDS row base) is wave-uniform scalar work.  Row and column of a pair come from
     // its offset in the channel plane by a multiply-high with ceil(2^32 / W), exact here because
@@ -113,7 +114,7 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     constexpr int SC = 8;
     const uint32_t w_magic = uint32_t(((1ull << 32) + uint32_t(W) - 1) / uint32_t(W));
     const uint32_t plane = uint32_t(H) * uint32_t(W);
-    for (int c0 = wave * (BC / 4); c0 < (wave + 1) * (BC / 4); c0 += SC) {
+    for (int c0 = wave * (BC / 8); c0 < (wave + 1) * (BC / 8); c0 += SC) {
         uint32_t lo[SC], hi[SC], longest = 0;
 #pragma unroll
         for (int q = 0; q < SC; ++q) {
@@ -181,10 +182,11 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
             a[g] = (a_ok && t0 + g < groups) ? v4 : u32x4{0, 0, 0, 0};
         }
     };
+    // the two K-groups of wavefronts take alternate steps; their sums meet in LDS at the end
     u32x4 cur[AG], nxt[AG];
-    fetch(cur, 0);
-    for (int step = 0; step < n_steps; ++step) {
-        fetch(nxt, min(step + 1, n_steps - 1));
+    fetch(cur, min(wk, n_steps - 1));
+    for (int step = wk; step < n_steps; step += 2) {
+        fetch(nxt, min(step + 2, n_steps - 1));
         const int pr = (step / chunks) * 2, t0 = (step % chunks) * AG;
         const int oy_l = pr + kg;
         // slot of input row oy-1 (tap u = 0); a K-half past the band reads valid rows and multiplies by zero
@@ -219,16 +221,29 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
 #ifdef DROPIT_PHASE_CLOCK
     pc[3] = wall_clock64();
 #endif
-    // ---- partial sums: [workgroup][tap][j][c] ------------------------------------
-    float *dst = partial + (int64_t(n) * bands + band) * 9 * int64_t(J) * C;
+    // ---- the two K-groups meet: group 1 parks its sums in LDS (the rows are no longer needed: 4 wavefronts x
+    // 9 tiles x 4 KB = exactly the 144 KB the accumulators take), group 0 adds them and writes -----------
+    __syncthreads();                                   // every wavefront is done reading the rows
+    float *park = reinterpret_cast<float *>(lds) + (wave & 3) * (9 * 16 * WAVE);
+    if (wk == 1) {
 #pragma unroll
-    for (int s = 0; s < 9; ++s)
+        for (int s = 0; s < 9; ++s)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int jj = jb * BJ + wj * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-            const int cc = cb * BC + wc * 32 + (lane & 31);
-            if (jj < J && cc < C) dst[(int64_t(s) * J + jj) * C + cc] = acc[s][e];
-        }
+            for (int e = 0; e < 16; ++e) park[(s * 16 + e) * WAVE + lane] = acc[s][e];
+    }
+    __syncthreads();
+    if (wk == 0) {
+        // partial sums: [workgroup][tap][j][c]
+        float *dst = partial + (int64_t(n) * bands + band) * 9 * int64_t(J) * C;
+#pragma unroll
+        for (int s = 0; s < 9; ++s)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int jj = jb * BJ + wj * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                const int cc = cb * BC + wc * 32 + (lane & 31);
+                if (jj < J && cc < C) dst[(int64_t(s) * J + jj) * C + cc] = acc[s][e] + park[(s * 16 + e) * WAVE + lane];
+            }
+    }
 #ifdef DROPIT_PHASE_CLOCK
     pc[4] = wall_clock64();
     if (blockIdx.x == gridDim.x / 2 && tid == 0) {
@@ -296,7 +311,8 @@ ConvPlan conv_mfma_plan(const ConvProblem &p)
     if (rb < 2) rb = 2;
     plan.rb = rb;
     plan.bands = int((p.H + rb - 1) / rb);
-    plan.lds_bytes = size_t(rb + 2) * BC * plan.pitch_c;
+    // the rows of a band, and afterwards the parked accumulators of one K-group (4 x 9 x 16 x 64 floats)
+    plan.lds_bytes = std::max(size_t(rb + 2) * BC * plan.pitch_c, size_t(4) * 9 * 16 * WAVE * 4);
     plan.packed_bytes = 0;
     plan.rowptr_bytes = round_up(size_t(p.N * p.C * p.H + 1) * 4, 256);
     plan.partial_bytes = round_up(size_t(p.N) * plan.bands * 9 * p.J * p.C * 4, 256);
