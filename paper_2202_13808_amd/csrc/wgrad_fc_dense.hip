@@ -391,6 +391,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
 #ifdef DROPIT_PHASE_CLOCK          // development only: where does a wavefront's step go (100 MHz ticks)
     unsigned long long pc_t[5] = {0, 0, 0, 0, 0}, pc_sum[4] = {0, 0, 0, 0};
     const unsigned long long pc_begin = wall_clock64();
+    const unsigned long long pc_cyc_begin = __builtin_readcyclecounter();
 #define PHASE_CLOCK(i)                                                        \
     do {                                                                      \
         pc_t[i] = wall_clock64();                                             \
@@ -447,6 +448,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
 
 #ifdef DROPIT_PHASE_CLOCK
     const unsigned long long pc_loop_end = wall_clock64();
+    const unsigned long long pc_cyc_end = __builtin_readcyclecounter();
 #endif
     // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block.
     if (splits == 1) {                                  // straight into dW, row-major
@@ -485,6 +487,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         o[4] = float(steps);
         o[5] = float(pc_t[0] ? pc_loop_end - pc_begin : 0);
         o[6] = float(wall_clock64() - pc_loop_end);
+        o[7] = float(pc_cyc_end - pc_cyc_begin);                             // shader clocks over the same span as o[5]
     }
 #endif
 }
