@@ -85,6 +85,60 @@ def test_full_size_configs(name):
     check_selection_invariants(x, i.size, v, i)
 
 
+def _keys(t: torch.Tensor) -> torch.Tensor:
+    """Magnitude keys (bit pattern with the sign cleared) of a device tensor, as int32."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).to(torch.int32) & 0x7FFF
+    return t.view(torch.int32) & 0x7FFFFFFF
+
+
+@pytest.mark.parametrize("dtype,mode", [("bf16", 0), ("f32", 0), ("bf16", 1)])
+def test_maximum_size_properties(dtype, mode):
+    """numel = 2^31 - 1, the largest tensor the int32 index allows (Sec. 3.2: the cache holds values and indices).
+    The oracle's full sort is out of reach at this size, so the result is checked through the properties that
+    define it, each evaluated with plain torch reductions over the input in pieces: exactly k pairs, strictly
+    ascending in-range indices, vals == x[idx], every key above the threshold kept, and the ties kept being the
+    first m in index order."""
+    numel, gamma, piece = (1 << 31) - 1, 0.99, 1 << 28
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cuda:0").manual_seed(77)
+    x = torch.empty(numel, dtype=tdt, device="cuda:0")
+    for s in range(0, numel, piece):
+        n = min(piece, numel - s)
+        x[s:s + n] = torch.randn(n, device="cuda:0", dtype=torch.float32, generator=gen).to(tdt)
+    x[numel - 1] = 1000.0                       # the very last element is among the largest and must be kept
+    k = dropit.keep_count(numel, gamma)
+    dropit.set_select_mode(mode)
+    try:
+        vals, idx = dropit.compress(x, gamma)
+        torch.cuda.synchronize()
+    finally:
+        dropit.set_select_mode(0)
+    assert vals.numel() == k and idx.numel() == k
+    assert int(idx[0]) >= 0 and int(idx[-1]) == numel - 1
+    assert bool((idx[1:] > idx[:-1]).all())
+    ibits = torch.int16 if dtype == "bf16" else torch.int32
+    assert bool((x[idx.long()].view(ibits) == vals.view(ibits)).all())
+    kept = _keys(vals)
+    t = int(kept.min())
+    n_gt = n_eq = 0
+    for s in range(0, numel, piece):
+        kk = _keys(x[s:s + min(piece, numel - s)])
+        n_gt += int((kk > t).sum())
+        n_eq += int((kk == t).sum())
+    m = k - n_gt
+    assert 1 <= m <= n_eq
+    assert int((kept > t).sum()) == n_gt and int((kept == t).sum()) == m
+    seen, want_last = 0, -1
+    for s in range(0, numel, piece):
+        pos = torch.nonzero(_keys(x[s:s + min(piece, numel - s)]) == t).flatten()
+        if seen + pos.numel() >= m:
+            want_last = int(pos[m - seen - 1]) + s
+            break
+        seen += pos.numel()
+    assert int(idx[kept == t][-1]) == want_last
+
+
 def test_deterministic_and_workspace_contents_irrelevant():
     x = activation((3001, 257), "gelu", 5, "bf16")
     xd = to_device(x)
