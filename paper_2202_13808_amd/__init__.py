@@ -6,6 +6,7 @@ argument marshalling from torch tensors (device memory + streams) to raw
 pointers.  There is no CPU fallback: without the built library, or without a
 GPU, the calls raise.
 """
+from . import nn  # noqa: F401  (autograd wrappers: nn.Linear, nn.Conv2d, nn.apply_dropit)
 from .binding import (  # noqa: F401
     DropitError,
     compress,

@@ -1,0 +1,231 @@
+"""torch.autograd integration of the DropIT hot path.
+
+The paper's implementation note (Sec. 4, "Implementation") describes the layer-level mechanism: in
+the forward pass the layer's input is converted to (value, index) form and the dense input is left
+to be released; in the backward pass the sparse form is recovered for the weight gradient only
+(Sec. 3.2, 3.3).  The forward output and the gradient with respect to the input never touch the
+cache (Sec. 3.5: dropping happens only where the gradient flows to the parameters), so they are
+computed here by the ordinary torch operators; the two steps the method adds -- the min-k
+compression and the weight gradient from the sparse cache -- are the library's HIP kernels behind
+``dropit_compress`` / ``dropit_weight_grad``.  There is no CPU path: training-mode calls need
+device tensors and the built library.
+
+Layer policy (Sec. 3.5 and the appendix on first and final layers): fully-connected and
+convolutional layers are applicable, normalisation and activation layers are not, and the first
+and the last applicable layer of a network are left alone because dropping there cannot lower the
+peak.  Inference is unchanged.
+"""
+from __future__ import annotations
+
+import contextlib
+import threading
+from typing import Iterator, List, Optional, Sequence, Tuple, Union
+
+import torch
+import torch.nn.functional as F
+
+from . import binding
+
+_Int2 = Union[int, Sequence[int]]
+
+
+def _pair(v: _Int2) -> Tuple[int, int]:
+    if isinstance(v, int):
+        return (v, v)
+    a, b = v
+    return (int(a), int(b))
+
+
+# ---------------------------------------------------------------------------------------------
+# cache accounting (Sec. 5, table of cached-tensor memory: value bytes fall by exactly gamma;
+# the indices are the method's own extra cost)
+# ---------------------------------------------------------------------------------------------
+class CacheMeter:
+    """Bytes the DropIT layers cached during the forward passes run under ``cache_meter()``."""
+
+    def __init__(self) -> None:
+        self.dense_bytes = 0     # what the same layers would have kept without dropping
+        self.value_bytes = 0     # retained values
+        self.index_bytes = 0     # their int32 flat indices
+        self.layers = 0
+
+    def _add(self, x: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor) -> None:
+        self.dense_bytes += x.numel() * x.element_size()
+        self.value_bytes += vals.numel() * vals.element_size()
+        self.index_bytes += idx.numel() * idx.element_size()
+        self.layers += 1
+
+
+_meters = threading.local()
+
+
+@contextlib.contextmanager
+def cache_meter() -> Iterator[CacheMeter]:
+    meter = CacheMeter()
+    stack = getattr(_meters, "stack", None)
+    if stack is None:
+        stack = _meters.stack = []
+    stack.append(meter)
+    try:
+        yield meter
+    finally:
+        stack.pop()
+
+
+def _account(x: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor) -> None:
+    for meter in getattr(_meters, "stack", ()):
+        meter._add(x, vals, idx)
+
+
+def _compress_input(x: torch.Tensor, gamma: float) -> Tuple[torch.Tensor, torch.Tensor]:
+    if not x.is_cuda:
+        raise RuntimeError("DropIT layers train on device tensors only: there is no CPU path")
+    xc = x.detach()
+    if not xc.is_contiguous():
+        xc = xc.contiguous()
+    vals, idx = binding.compress(xc, gamma)
+    _account(xc, vals, idx)
+    return vals, idx
+
+
+def _match_dtype(dy: torch.Tensor, vals: torch.Tensor) -> torch.Tensor:
+    dy = dy if dy.dtype == vals.dtype else dy.to(vals.dtype)
+    return dy if dy.is_contiguous() else dy.contiguous()
+
+
+# ---------------------------------------------------------------------------------------------
+# fully-connected layer (Sec. 3.3, weight gradient of a fully-connected layer from the retained elements)
+# ---------------------------------------------------------------------------------------------
+class _LinearFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, gamma):
+        y = F.linear(x, weight, bias)
+        vals, idx = _compress_input(x, gamma)
+        ctx.save_for_backward(vals, idx, weight)
+        ctx.x_shape = tuple(x.shape)
+        ctx.has_bias = bias is not None
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        vals, idx, weight = ctx.saved_tensors
+        c_out, c_in = weight.shape
+        dx = dw = db = None
+        dy2 = dy.reshape(-1, c_out)
+        if ctx.needs_input_grad[0]:
+            dx = (dy2 @ weight.to(dy.dtype)).reshape(ctx.x_shape)
+        if ctx.needs_input_grad[1]:
+            dw = binding.weight_grad(vals, idx, ctx.x_shape, _match_dtype(dy2, vals), c_out).to(weight.dtype)
+        if ctx.has_bias and ctx.needs_input_grad[2]:
+            db = dy2.sum(0)
+        return dx, dw, db, None
+
+
+def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
+           gamma: float = 0.9) -> torch.Tensor:
+    """``F.linear`` whose backward computes the weight gradient from the min-k cache of ``x``."""
+    return _LinearFn.apply(x, weight, bias, float(gamma))
+
+
+# ---------------------------------------------------------------------------------------------
+# convolution (Sec. 3.3, weight gradient of a convolutional layer from the retained elements)
+# ---------------------------------------------------------------------------------------------
+class _Conv2dFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma):
+        y = F.conv2d(x, weight, bias, stride, padding, dilation, 1)
+        vals, idx = _compress_input(x, gamma)
+        ctx.save_for_backward(vals, idx, weight)
+        ctx.x_shape = tuple(x.shape)
+        ctx.geometry = (stride, padding, dilation)
+        ctx.has_bias = bias is not None
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        vals, idx, weight = ctx.saved_tensors
+        stride, padding, dilation = ctx.geometry
+        c_out, _, kh, kw = weight.shape
+        dx = dw = db = None
+        if ctx.needs_input_grad[0]:
+            dx = torch.nn.grad.conv2d_input(ctx.x_shape, weight.to(dy.dtype), dy, stride, padding, dilation, 1)
+        if ctx.needs_input_grad[1]:
+            conv = (kh, kw, stride[0], stride[1], padding[0], padding[1], dilation[0], dilation[1])
+            dw = binding.weight_grad(vals, idx, ctx.x_shape, _match_dtype(dy, vals), c_out, conv=conv).to(weight.dtype)
+        if ctx.has_bias and ctx.needs_input_grad[2]:
+            db = dy.sum((0, 2, 3))
+        return dx, dw, db, None, None, None, None
+
+
+def conv2d(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
+           stride: _Int2 = 1, padding: _Int2 = 0, dilation: _Int2 = 1, gamma: float = 0.9) -> torch.Tensor:
+    """``F.conv2d`` (groups = 1, zero padding, NCHW) whose backward computes the weight gradient
+    from the min-k cache of ``x``."""
+    return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma))
+
+
+# ---------------------------------------------------------------------------------------------
+# modules and the layer policy
+# ---------------------------------------------------------------------------------------------
+def _dropping(module: torch.nn.Module) -> bool:
+    """Inference, no-grad regions, frozen weights and gamma = 0 (the baseline column) run the plain operator."""
+    return (module.training and torch.is_grad_enabled() and module.gamma > 0.0
+            and module.weight.requires_grad)
+
+
+class Linear(torch.nn.Linear):
+    def __init__(self, in_features: int, out_features: int, bias: bool = True, gamma: float = 0.9,
+                 device=None, dtype=None) -> None:
+        super().__init__(in_features, out_features, bias, device=device, dtype=dtype)
+        self.gamma = float(gamma)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        if not _dropping(self):
+            return F.linear(x, self.weight, self.bias)
+        return linear(x, self.weight, self.bias, self.gamma)
+
+    def extra_repr(self) -> str:
+        return super().extra_repr() + ", gamma=%g" % self.gamma
+
+
+def _conv_applicable(m: torch.nn.Conv2d) -> bool:
+    return m.groups == 1 and m.padding_mode == "zeros" and not isinstance(m.padding, str)
+
+
+class Conv2d(torch.nn.Conv2d):
+    def __init__(self, *args, gamma: float = 0.9, **kwargs) -> None:
+        super().__init__(*args, **kwargs)
+        if not _conv_applicable(self):
+            raise ValueError("DropIT Conv2d supports groups=1, zero padding given as integers")
+        self.gamma = float(gamma)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        if not _dropping(self):
+            return self._conv_forward(x, self.weight, self.bias)
+        return conv2d(x, self.weight, self.bias, self.stride, self.padding, self.dilation, self.gamma)
+
+    def extra_repr(self) -> str:
+        return super().extra_repr() + ", gamma=%g" % self.gamma
+
+
+def apply_dropit(model: torch.nn.Module, gamma: float, skip_first: bool = True,
+                 skip_last: bool = True) -> List[str]:
+    """Switch the applicable layers of ``model`` to DropIT in place and return their names.
+
+    Applicable: ``nn.Linear`` and ``nn.Conv2d`` (groups = 1, zero padding); the modules keep their
+    parameters, buffers, hooks and state-dict keys (only their class changes).  The first and the
+    last applicable layer, in module registration order, are left as they are unless asked
+    otherwise: their inputs stay alive (or are created last) whatever the layer caches, so
+    dropping there adds the sparse copy to the peak instead of lowering it."""
+    found: List[Tuple[str, torch.nn.Module]] = []
+    for name, m in model.named_modules():
+        if type(m) is torch.nn.Linear or (type(m) is torch.nn.Conv2d and _conv_applicable(m)):
+            found.append((name, m))
+    if skip_first and found:
+        found = found[1:]
+    if skip_last and found:
+        found = found[:-1]
+    for _, m in found:
+        m.__class__ = Linear if isinstance(m, torch.nn.Linear) else Conv2d
+        m.gamma = float(gamma)
+    return [name for name, _ in found]
