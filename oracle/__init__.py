@@ -49,6 +49,12 @@ def _load():
         lib.oracle_keep_count.argtypes = [i64, dbl]
         lib.oracle_compress.restype = i32
         lib.oracle_compress.argtypes = [vp, i64, i32, i64, vp, vp]
+        lib.oracle_philox4x32_10.restype = None
+        lib.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        lib.oracle_random_key.restype = ctypes.c_uint32
+        lib.oracle_random_key.argtypes = [i64, ctypes.c_uint64]
+        lib.oracle_compress_random.restype = i32
+        lib.oracle_compress_random.argtypes = [vp, i64, i32, i64, ctypes.c_uint64, vp, vp]
         lib.oracle_widen.restype = None
         lib.oracle_widen.argtypes = [vp, i64, i32, vp]
         lib.oracle_densify.restype = i32
@@ -97,6 +103,32 @@ def compress(x: np.ndarray, k: int):
     rc = _load().oracle_compress(_ptr(x), x.size, code, int(k), _ptr(vals), _ptr(idx))
     if rc != 0:
         raise ValueError("oracle_compress rejected its arguments")
+    return vals, idx
+
+
+def philox4x32_10(ctr, key):
+    """One block of Philox4x32-10 (Salmon et al., SC'11): 4 counter words, 2 key words -> 4 words."""
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _load().oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def random_key(i: int, seed: int) -> int:
+    """31-bit selection key of flat index i under `seed`  [Sec. 3.3 Random Elements; reading in the C header]."""
+    return int(_load().oracle_random_key(int(i), int(seed)))
+
+
+def compress_random(x: np.ndarray, k: int, seed: int):
+    """D(a) with a uniformly random retained set of k elements  [Sec. 3.3 Random Elements]."""
+    x = np.ascontiguousarray(x).reshape(-1)
+    code = _dtype_code(x)
+    vals = np.empty(k, dtype=x.dtype)
+    idx = np.empty(k, dtype=np.int32)
+    rc = _load().oracle_compress_random(_ptr(x), x.size, code, int(k), int(seed), _ptr(vals), _ptr(idx))
+    if rc != 0:
+        raise ValueError("oracle_compress_random rejected its arguments")
     return vals, idx
 
 

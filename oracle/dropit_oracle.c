@@ -12,6 +12,7 @@
  *   - min-k dropping    D(a) = {a_Xr, Xr}: keep the k elements of largest
  *                       absolute magnitude, with their indices
  *                                                         [Sec. 3.2; Sec. 3.3 Min-K; Sec. 4.1]
+ *   - random dropping   D(a) with X_r a uniformly random k-subset            [Sec. 3.3 Random Elements]
  *   - recover           R(a^): dense tensor, dropped positions zero
  *                                                         [Sec. 3.2; Fig. 1 caption]
  *   - FC weight grad    g[j][c] = sum_n dz[n][j] * a^[n][c]
@@ -25,7 +26,12 @@
  *   bit cleared (so -0 == +0, denormals ordered exactly, NaN above inf);
  *   int32 0-based row-major flat indices [App. A.7]; conv is a
  *   cross-correlation with 0-based y' = y*stride - pad + u*dil and zero
- *   padding.
+ *   padding.  Random dropping keeps exactly k elements (the same k as min-k):
+ *   element i draws the 32-bit word (i mod 4) of Philox4x32-10 (Salmon et al.,
+ *   "Parallel random numbers: as easy as 1, 2, 3", SC'11) at counter
+ *   (floor(i/4), 0, 0, 0) under key (seed mod 2^32, seed div 2^32); the k
+ *   elements with the largest draw, shifted right by one bit, are kept, equal
+ *   draws going to the lowest index.
  *
  * All floating-point accumulation is fp64, in the summation order the
  * formulas are written in.  No blocking, fusion or reordering.
@@ -96,6 +102,65 @@ int oracle_compress(const void *x, int64_t numel, int dtype, int64_t k,
     if (!p) return -1;
     for (int64_t i = 0; i < numel; ++i) {
         p[i].key = key_of(x, i, dtype);
+        p[i].idx = (int32_t)i;
+    }
+    qsort(p, (size_t)numel, sizeof(pair_t), cmp_key_desc_idx_asc);
+    for (int64_t j = 0; j < k; ++j) idx[j] = p[j].idx;
+    free(p);
+    qsort(idx, (size_t)k, sizeof(int32_t), cmp_i32_asc);
+    size_t es = (dtype == ORACLE_F32) ? 4 : 2;
+    for (int64_t j = 0; j < k; ++j)
+        memcpy((char *)vals + es * (size_t)j, (const char *)x + es * (size_t)idx[j], es);
+    return 0;
+}
+
+/* ---- random dropping -------------------------------------------------- */
+/* Philox4x32 with 10 rounds as published (Salmon, Moraes, Dror, Shaw, SC'11):
+ * each round multiplies counter words 0 and 2 by two fixed odd constants, and
+ * the new counter is (hi(p1)^c1^k0, lo(p1), hi(p0)^c3^k1, lo(p0)); the key
+ * advances by the two Weyl constants before every round but the first. */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 31-bit selection key of element i under `seed`. */
+uint32_t oracle_random_key(int64_t i, uint64_t seed)
+{
+    uint32_t ctr[4] = { (uint32_t)(i >> 2), 0u, 0u, 0u };
+    uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return out[i & 3] >> 1;
+}
+
+/* D(a) with random X_r: the same full sort as oracle_compress, on the drawn
+ * keys instead of the magnitudes.  Returns 0, or -1 on bad arguments. */
+int oracle_compress_random(const void *x, int64_t numel, int dtype, int64_t k, uint64_t seed,
+                           void *vals, int32_t *idx)
+{
+    if (numel < 0 || numel > 2147483647LL || k < 0 || k > numel) return -1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return -1;
+    if (k == 0) return 0;
+    pair_t *p = (pair_t *)malloc((size_t)numel * sizeof(pair_t));
+    if (!p) return -1;
+    for (int64_t i = 0; i < numel; ++i) {
+        p[i].key = oracle_random_key(i, seed);
         p[i].idx = (int32_t)i;
     }
     qsort(p, (size_t)numel, sizeof(pair_t), cmp_key_desc_idx_asc);
