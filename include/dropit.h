@@ -90,6 +90,31 @@ dropit_status dropit_compress(const void *x, const int64_t *shape, int ndim, dro
                               double gamma, void *vals, int32_t *idx,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Bytes of device workspace dropit_compress_random needs (0 on invalid arguments). */
+size_t dropit_compress_random_workspace_bytes(int64_t numel, dropit_dtype dt);
+
+/*
+ * Random dropping D(a) (Sec. 3.3 "Random Elements": a gamma fraction of the
+ * elements of the mini-batch tensor is dropped at random; the paper's baseline
+ * strategy beside min-k).
+ *
+ * Keeps exactly k = dropit_keep_count(numel, gamma) elements, a uniformly random
+ * k-subset fixed by `seed` alone (not by the values of x): element i draws the
+ * 32-bit word (i mod 4) of Philox4x32-10 (Salmon et al., SC'11) at counter
+ * (floor(i/4), 0, 0, 0) under key (seed mod 2^32, seed div 2^32); the k elements
+ * with the largest draw, shifted right by one bit, are kept, equal draws going to
+ * the lowest flat index.  Callers that want a fresh subset per iteration pass a
+ * fresh seed.
+ *
+ * Arguments, outputs (ascending idx, vals[j] = x[idx[j]] bit for bit), alignment
+ * and error behaviour as for dropit_compress; the workspace must hold
+ * dropit_compress_random_workspace_bytes (it keeps one 32-bit draw per element).
+ * The pairs feed dropit_weight_grad unchanged.
+ */
+dropit_status dropit_compress_random(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                                     double gamma, uint64_t seed, void *vals, int32_t *idx,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Convolution geometry for dropit_weight_grad (cross-correlation, zero padding,
  * 0-based: input row = out_row*stride_h - pad_h + u*dil_h). */
 typedef struct {

@@ -10,6 +10,8 @@ from . import nn  # noqa: F401  (autograd wrappers: nn.Linear, nn.Conv2d, nn.app
 from .binding import (  # noqa: F401
     DropitError,
     compress,
+    compress_random,
+    compress_random_workspace_bytes,
     compress_workspace_bytes,
     keep_count,
     lib,

@@ -57,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.dropit_compress_workspace_bytes.argtypes = [i64, i32]
         L.dropit_compress.restype = i32
         L.dropit_compress.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp, sz, vp]
+        L.dropit_compress_random_workspace_bytes.restype = sz
+        L.dropit_compress_random_workspace_bytes.argtypes = [i64, i32]
+        L.dropit_compress_random.restype = i32
+        L.dropit_compress_random.argtypes = [vp, p64, i32, i32, dbl, ctypes.c_uint64, vp, vp, vp, sz, vp]
         L.dropit_weight_grad_workspace_bytes.restype = sz
         L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
         L.dropit_set_select_mode.restype = i32
@@ -140,6 +144,36 @@ def compress(x: torch.Tensor, gamma: float, vals: Optional[torch.Tensor] = None,
         _check(lib().dropit_compress(x.data_ptr(), shape, x.dim(), code, float(gamma),
                                      vals.data_ptr() if k else None, idx.data_ptr() if k else None,
                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return vals[:k], idx[:k]
+
+
+def compress_random_workspace_bytes(numel: int, dtype: torch.dtype) -> int:
+    return int(lib().dropit_compress_random_workspace_bytes(int(numel), _dtype_code(dtype)))
+
+
+def compress_random(x: torch.Tensor, gamma: float, seed: int, vals: Optional[torch.Tensor] = None,
+                    idx: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                    stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """dropit_compress_random: like ``compress`` with a uniformly random retained set fixed by ``seed``."""
+    _require_device(x, vals, idx, workspace)
+    code = _dtype_code(x.dtype)
+    k = keep_count(x.numel(), gamma)
+    if k < 0 or not 0 <= int(seed) < (1 << 64):
+        _check(EINVAL)
+    if vals is None:
+        vals = torch.empty(k, dtype=x.dtype, device=x.device)
+    if idx is None:
+        idx = torch.empty(k, dtype=torch.int32, device=x.device)
+    if vals.numel() < k or idx.numel() < k or vals.dtype != x.dtype or idx.dtype != torch.int32:
+        raise ValueError("vals/idx must hold k=%d elements of %s / int32" % (k, x.dtype))
+    if workspace is None:
+        workspace = torch.empty(max(compress_random_workspace_bytes(x.numel(), x.dtype), 1),
+                                dtype=torch.uint8, device=x.device)
+    shape = _shape_array(x.shape)
+    with torch.cuda.device(x.device):
+        _check(lib().dropit_compress_random(x.data_ptr(), shape, x.dim(), code, float(gamma), int(seed),
+                                            vals.data_ptr() if k else None, idx.data_ptr() if k else None,
+                                            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return vals[:k], idx[:k]
 
 

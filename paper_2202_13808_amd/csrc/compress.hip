@@ -1011,6 +1011,65 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
         select_serial<RAW>(x, numel, nvf, k, vals, idx, reinterpret_cast<uint32_t *>(dyn_smem), s_wave_tot, s_bcast);
 }
 
+// ---- random dropping (Sec. 3.3, Random Elements) ------------------------------------------------
+// Philox4x32 with 10 rounds (Salmon et al., SC'11): per round, counter words 0 and 2 are multiplied by two
+// odd constants and the halves of the products are crossed with the other two words and the key; the key
+// advances by two Weyl constants between rounds.
+__device__ inline void philox_round(uint32_t (&c)[4], uint32_t k0, uint32_t k1)
+{
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c[0]), lo0 = 0xD2511F53u * c[0];
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c[2]), lo1 = 0xCD9E8D57u * c[2];
+    c[0] = hi1 ^ c[1] ^ k0;
+    c[1] = lo1;
+    c[2] = hi0 ^ c[3] ^ k1;
+    c[3] = lo0;
+}
+
+// keys[4b .. 4b+3] = the four words of block b, each shifted right by one (31-bit keys, so that the
+// select's sign-cleared order of fp32 bit patterns is their integer order).  `blocks` 16-byte stores.
+__global__ void __launch_bounds__(256) random_keys_kernel(uint4 *keys, int64_t blocks, uint32_t seed_lo,
+                                                          uint32_t seed_hi)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t b = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; b < blocks; b += stride) {
+        uint32_t c[4] = {static_cast<uint32_t>(b), 0u, 0u, 0u};
+        uint32_t k0 = seed_lo, k1 = seed_hi;
+#pragma unroll
+        for (int round = 0; round < 10; ++round) {
+            if (round > 0) {
+                k0 += 0x9E3779B9u;
+                k1 += 0xBB67AE85u;
+            }
+            philox_round(c, k0, k1);
+        }
+        keys[b] = make_uint4(c[0] >> 1, c[1] >> 1, c[2] >> 1, c[3] >> 1);
+    }
+}
+
+template <typename RAW>
+__global__ void __launch_bounds__(256) gather_kernel(const RAW *__restrict__ x, const int32_t *__restrict__ idx,
+                                                     int64_t k, RAW *__restrict__ vals)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t j = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; j < k; j += stride)
+        vals[j] = x[idx[j]];
+}
+
+inline size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Workspace of the random strategy: the select's own area, one key per element (padded to whole Philox
+// blocks), and the keys the select writes out beside the indices (unused afterwards).
+struct RandomWorkspace {
+    size_t keys_off, keyvals_off, bytes;
+    explicit RandomWorkspace(int64_t numel)
+    {
+        const size_t key_bytes = round_up_256((static_cast<size_t>(numel) + 3) / 4 * 16);
+        keys_off = round_up_256(SelWorkspace::bytes);
+        keyvals_off = keys_off + key_bytes;
+        bytes = keyvals_off + key_bytes;
+    }
+};
+
 struct Geometry {
     int64_t nvf, vpc;      // full 16-byte vectors, vectors per chunk
     int chunks;
@@ -1220,4 +1279,49 @@ extern "C" dropit_status dropit_compress(const void *x, const int64_t *shape, in
     char *ws = static_cast<char *>(workspace);
     if (dt == DROPIT_BF16) return run_compress<uint16_t>(x, numel, k, vals, idx, ws, stream);
     return run_compress<uint32_t>(x, numel, k, vals, idx, ws, stream);
+}
+
+extern "C" size_t dropit_compress_random_workspace_bytes(int64_t numel, dropit_dtype dt)
+{
+    if (numel < 1 || numel > INT32_MAX) return 0;
+    if (dt != DROPIT_F32 && dt != DROPIT_BF16) return 0;
+    return RandomWorkspace(numel).bytes;
+}
+
+extern "C" dropit_status dropit_compress_random(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                                                double gamma, uint64_t seed, void *vals, int32_t *idx,
+                                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (dt != DROPIT_F32 && dt != DROPIT_BF16) return DROPIT_EINVAL;
+    const int64_t numel = checked_numel(shape, ndim);
+    if (numel < 1) return DROPIT_EINVAL;
+    const int64_t k = dropit_keep_count(numel, gamma);
+    if (k < 0) return DROPIT_EINVAL;
+    if (x == nullptr || !aligned(x, 16)) return DROPIT_EINVAL;
+    if (k == 0) return DROPIT_OK;
+    if (vals == nullptr || idx == nullptr) return DROPIT_EINVAL;
+    if (!aligned(vals, dt == DROPIT_F32 ? 4 : 2) || !aligned(idx, 4)) return DROPIT_EINVAL;
+    if (workspace == nullptr || !aligned(workspace, 256)) return DROPIT_EINVAL;
+    const RandomWorkspace rw(numel);
+    if (workspace_bytes < rw.bytes) return DROPIT_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    uint4 *keys = reinterpret_cast<uint4 *>(ws + rw.keys_off);
+    const int64_t blocks = (numel + 3) / 4;
+    const unsigned grid = static_cast<unsigned>(std::min<int64_t>((blocks + 255) / 256, 256 * 16));
+    trace_mark(stream);
+    random_keys_kernel<<<grid, 256, 0, stream>>>(keys, blocks, static_cast<uint32_t>(seed & 0xFFFFFFFFu),
+                                                 static_cast<uint32_t>(seed >> 32));
+    // the drawn keys are 31-bit patterns: the fp32 select ranks them as integers
+    dropit_status st = run_compress<uint32_t>(keys, numel, k, ws + rw.keyvals_off, idx, ws, stream);
+    if (st != DROPIT_OK) return st;
+    const unsigned ggrid = static_cast<unsigned>(std::min<int64_t>((k + 255) / 256, 256 * 16));
+    if (dt == DROPIT_BF16)
+        gather_kernel<uint16_t><<<ggrid, 256, 0, stream>>>(static_cast<const uint16_t *>(x), idx, k,
+                                                           static_cast<uint16_t *>(vals));
+    else
+        gather_kernel<uint32_t><<<ggrid, 256, 0, stream>>>(static_cast<const uint32_t *>(x), idx, k,
+                                                           static_cast<uint32_t *>(vals));
+    trace_mark(stream);
+    return launch_status();
 }

@@ -77,13 +77,17 @@ def _account(x: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor) -> None:
         meter._add(x, vals, idx)
 
 
-def _compress_input(x: torch.Tensor, gamma: float) -> Tuple[torch.Tensor, torch.Tensor]:
+def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int]) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Min-k dropping, or (seed given) the random strategy of Sec. 3.3 with that seed."""
     if not x.is_cuda:
         raise RuntimeError("DropIT layers train on device tensors only: there is no CPU path")
     xc = x.detach()
     if not xc.is_contiguous():
         xc = xc.contiguous()
-    vals, idx = binding.compress(xc, gamma)
+    if seed is None:
+        vals, idx = binding.compress(xc, gamma)
+    else:
+        vals, idx = binding.compress_random(xc, gamma, seed)
     _account(xc, vals, idx)
     return vals, idx
 
@@ -98,9 +102,9 @@ def _match_dtype(dy: torch.Tensor, vals: torch.Tensor) -> torch.Tensor:
 # ---------------------------------------------------------------------------------------------
 class _LinearFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, gamma):
+    def forward(ctx, x, weight, bias, gamma, seed):
         y = F.linear(x, weight, bias)
-        vals, idx = _compress_input(x, gamma)
+        vals, idx = _compress_input(x, gamma, seed)
         ctx.save_for_backward(vals, idx, weight)
         ctx.x_shape = tuple(x.shape)
         ctx.has_bias = bias is not None
@@ -118,13 +122,14 @@ class _LinearFn(torch.autograd.Function):
             dw = binding.weight_grad(vals, idx, ctx.x_shape, _match_dtype(dy2, vals), c_out).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy2.sum(0)
-        return dx, dw, db, None
+        return dx, dw, db, None, None
 
 
 def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
-           gamma: float = 0.9) -> torch.Tensor:
-    """``F.linear`` whose backward computes the weight gradient from the min-k cache of ``x``."""
-    return _LinearFn.apply(x, weight, bias, float(gamma))
+           gamma: float = 0.9, seed: Optional[int] = None) -> torch.Tensor:
+    """``F.linear`` whose backward computes the weight gradient from the min-k cache of ``x``
+    (from a random cache drawn with ``seed`` when one is given)."""
+    return _LinearFn.apply(x, weight, bias, float(gamma), seed)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -132,9 +137,9 @@ def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] =
 # ---------------------------------------------------------------------------------------------
 class _Conv2dFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma):
+    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma, seed):
         y = F.conv2d(x, weight, bias, stride, padding, dilation, 1)
-        vals, idx = _compress_input(x, gamma)
+        vals, idx = _compress_input(x, gamma, seed)
         ctx.save_for_backward(vals, idx, weight)
         ctx.x_shape = tuple(x.shape)
         ctx.geometry = (stride, padding, dilation)
@@ -154,19 +159,39 @@ class _Conv2dFn(torch.autograd.Function):
             dw = binding.weight_grad(vals, idx, ctx.x_shape, _match_dtype(dy, vals), c_out, conv=conv).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy.sum((0, 2, 3))
-        return dx, dw, db, None, None, None, None
+        return dx, dw, db, None, None, None, None, None
 
 
 def conv2d(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
-           stride: _Int2 = 1, padding: _Int2 = 0, dilation: _Int2 = 1, gamma: float = 0.9) -> torch.Tensor:
+           stride: _Int2 = 1, padding: _Int2 = 0, dilation: _Int2 = 1, gamma: float = 0.9,
+           seed: Optional[int] = None) -> torch.Tensor:
     """``F.conv2d`` (groups = 1, zero padding, NCHW) whose backward computes the weight gradient
-    from the min-k cache of ``x``."""
-    return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma))
+    from the min-k cache of ``x`` (from a random cache drawn with ``seed`` when one is given)."""
+    return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma), seed)
 
 
 # ---------------------------------------------------------------------------------------------
 # modules and the layer policy
 # ---------------------------------------------------------------------------------------------
+_SEED_STRIDE = 0x9E3779B97F4A7C15      # odd: successive calls of a layer walk through all 2^64 seeds
+
+
+def _next_seed(module: torch.nn.Module) -> Optional[int]:
+    """None for min-k; for the random strategy a fresh seed per forward call, so that every
+    iteration drops a different subset (Sec. 3.3: dropped at random within each mini-batch)."""
+    if getattr(module, "strategy", "mink") != "random":
+        return None
+    calls = getattr(module, "_dropit_calls", 0)
+    module._dropit_calls = calls + 1
+    return (int(getattr(module, "seed", 0)) + calls * _SEED_STRIDE) & 0xFFFFFFFFFFFFFFFF
+
+
+def _check_strategy(strategy: str) -> str:
+    if strategy not in ("mink", "random"):
+        raise ValueError("strategy must be 'mink' or 'random'")
+    return strategy
+
+
 def _dropping(module: torch.nn.Module) -> bool:
     """Inference, no-grad regions, frozen weights and gamma = 0 (the baseline column) run the plain operator."""
     return (module.training and torch.is_grad_enabled() and module.gamma > 0.0
@@ -175,14 +200,16 @@ def _dropping(module: torch.nn.Module) -> bool:
 
 class Linear(torch.nn.Linear):
     def __init__(self, in_features: int, out_features: int, bias: bool = True, gamma: float = 0.9,
-                 device=None, dtype=None) -> None:
+                 strategy: str = "mink", seed: int = 0, device=None, dtype=None) -> None:
         super().__init__(in_features, out_features, bias, device=device, dtype=dtype)
         self.gamma = float(gamma)
+        self.strategy = _check_strategy(strategy)
+        self.seed = int(seed)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         if not _dropping(self):
             return F.linear(x, self.weight, self.bias)
-        return linear(x, self.weight, self.bias, self.gamma)
+        return linear(x, self.weight, self.bias, self.gamma, _next_seed(self))
 
     def extra_repr(self) -> str:
         return super().extra_repr() + ", gamma=%g" % self.gamma
@@ -193,30 +220,35 @@ def _conv_applicable(m: torch.nn.Conv2d) -> bool:
 
 
 class Conv2d(torch.nn.Conv2d):
-    def __init__(self, *args, gamma: float = 0.9, **kwargs) -> None:
+    def __init__(self, *args, gamma: float = 0.9, strategy: str = "mink", seed: int = 0, **kwargs) -> None:
         super().__init__(*args, **kwargs)
         if not _conv_applicable(self):
             raise ValueError("DropIT Conv2d supports groups=1, zero padding given as integers")
         self.gamma = float(gamma)
+        self.strategy = _check_strategy(strategy)
+        self.seed = int(seed)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         if not _dropping(self):
             return self._conv_forward(x, self.weight, self.bias)
-        return conv2d(x, self.weight, self.bias, self.stride, self.padding, self.dilation, self.gamma)
+        return conv2d(x, self.weight, self.bias, self.stride, self.padding, self.dilation, self.gamma,
+                      _next_seed(self))
 
     def extra_repr(self) -> str:
         return super().extra_repr() + ", gamma=%g" % self.gamma
 
 
 def apply_dropit(model: torch.nn.Module, gamma: float, skip_first: bool = True,
-                 skip_last: bool = True) -> List[str]:
+                 skip_last: bool = True, strategy: str = "mink", seed: int = 0) -> List[str]:
     """Switch the applicable layers of ``model`` to DropIT in place and return their names.
 
     Applicable: ``nn.Linear`` and ``nn.Conv2d`` (groups = 1, zero padding); the modules keep their
     parameters, buffers, hooks and state-dict keys (only their class changes).  The first and the
     last applicable layer, in module registration order, are left as they are unless asked
     otherwise: their inputs stay alive (or are created last) whatever the layer caches, so
-    dropping there adds the sparse copy to the peak instead of lowering it."""
+    dropping there adds the sparse copy to the peak instead of lowering it.  ``strategy`` is
+    "mink" (Sec. 3.3 Min-K Elements) or "random" (Sec. 3.3 Random Elements, seeded per layer
+    and per call from ``seed``)."""
     found: List[Tuple[str, torch.nn.Module]] = []
     for name, m in model.named_modules():
         if type(m) is torch.nn.Linear or (type(m) is torch.nn.Conv2d and _conv_applicable(m)):
@@ -225,7 +257,10 @@ def apply_dropit(model: torch.nn.Module, gamma: float, skip_first: bool = True,
         found = found[1:]
     if skip_last and found:
         found = found[:-1]
-    for _, m in found:
+    _check_strategy(strategy)
+    for number, (_, m) in enumerate(found):
         m.__class__ = Linear if isinstance(m, torch.nn.Linear) else Conv2d
         m.gamma = float(gamma)
+        m.strategy = strategy
+        m.seed = (int(seed) + (number << 48)) & 0xFFFFFFFFFFFFFFFF     # layers draw from disjoint seed ranges
     return [name for name, _ in found]

@@ -21,7 +21,8 @@ def declared_symbols():
 def test_header_declares_the_expected_entry_points():
     assert declared_symbols() == sorted([
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
-        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode"])
+        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode",
+        "dropit_compress_random_workspace_bytes", "dropit_compress_random"])
 
 
 def test_library_exports_every_declared_symbol():
@@ -75,6 +76,29 @@ def test_compress_rejects_bad_arguments_without_a_gpu():
     assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, ws, 16, None) == binding.EWORKSPACE
     # gamma = 1 keeps nothing: legal, nothing launched, outputs may be NULL
     assert call(fake, _shape(4, 4), 2, binding.BF16, 1.0, None, None, None, 0, None) == binding.OK
+
+
+def test_compress_random_rejects_bad_arguments_without_a_gpu():
+    L = dropit.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ws = ctypes.c_void_p(0x10000)
+    big = 1 << 30
+    call = L.dropit_compress_random
+    assert call(None, _shape(4, 4), 2, binding.BF16, 0.5, 1, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 0), 2, binding.BF16, 0.5, 1, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, 7, 0.5, 1, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.F32, 1.5, 1, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.F32, 0.5, 1, None, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.F32, 0.5, 1, fake, fake, ctypes.c_void_p(0x10010), big, None) == binding.EINVAL
+    need = L.dropit_compress_random_workspace_bytes(16, binding.F32)
+    assert need > L.dropit_compress_workspace_bytes(16, binding.F32)
+    assert call(fake, _shape(4, 4), 2, binding.F32, 0.5, 1, fake, fake, ws, need - 1, None) == binding.EWORKSPACE
+    assert call(fake, _shape(4, 4), 2, binding.F32, 1.0, 1, None, None, None, 0, None) == binding.OK
+    # one 32-bit draw per element, twice (keys and the select's copy of the kept ones)
+    n = 1 << 20
+    assert L.dropit_compress_random_workspace_bytes(n, binding.BF16) >= L.dropit_compress_workspace_bytes(n, binding.BF16) + 8 * n
+    assert L.dropit_compress_random_workspace_bytes(0, binding.BF16) == 0
+    assert L.dropit_compress_random_workspace_bytes(1 << 31, binding.BF16) == 0
 
 
 def test_select_mode_switch_validates():
