@@ -55,6 +55,10 @@ def _load():
         lib.oracle_random_key.argtypes = [i64, ctypes.c_uint64]
         lib.oracle_compress_random.restype = i32
         lib.oracle_compress_random.argtypes = [vp, i64, i32, i64, ctypes.c_uint64, vp, vp]
+        lib.oracle_rows_from_pairs.restype = i32
+        lib.oracle_rows_from_pairs.argtypes = [vp, i64, i64, i64, vp, vp]
+        lib.oracle_pairs_from_rows.restype = i32
+        lib.oracle_pairs_from_rows.argtypes = [vp, vp, i64, i64, vp]
         lib.oracle_widen.restype = None
         lib.oracle_widen.argtypes = [vp, i64, i32, vp]
         lib.oracle_densify.restype = i32
@@ -130,6 +134,29 @@ def compress_random(x: np.ndarray, k: int, seed: int):
     if rc != 0:
         raise ValueError("oracle_compress_random rejected its arguments")
     return vals, idx
+
+
+def rows_from_pairs(idx: np.ndarray, shape):
+    """Row form of a retained index set: (col uint16 [k], rowptr int32 [rows+1]); rows are the last
+    dimension of `shape`  [Sec. 5, index memory]."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    row_len = int(shape[-1])
+    rows = int(np.prod(shape[:-1], dtype=np.int64)) if len(shape) > 1 else 1
+    col = np.empty(idx.size, dtype=np.uint16)
+    rowptr = np.empty(rows + 1, dtype=np.int32)
+    if _load().oracle_rows_from_pairs(_ptr(idx), idx.size, rows, row_len, _ptr(col), _ptr(rowptr)) != 0:
+        raise ValueError("oracle_rows_from_pairs rejected its arguments")
+    return col, rowptr
+
+
+def pairs_from_rows(col: np.ndarray, rowptr: np.ndarray, shape) -> np.ndarray:
+    """Inverse of rows_from_pairs: the int32 flat indices."""
+    col = np.ascontiguousarray(col, dtype=np.uint16)
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    idx = np.empty(col.size, dtype=np.int32)
+    if _load().oracle_pairs_from_rows(_ptr(col), _ptr(rowptr), rowptr.size - 1, int(shape[-1]), _ptr(idx)) != 0:
+        raise ValueError("oracle_pairs_from_rows rejected its arguments")
+    return idx
 
 
 def widen(a: np.ndarray) -> np.ndarray:

@@ -13,6 +13,9 @@
  *                       absolute magnitude, with their indices
  *                                                         [Sec. 3.2; Sec. 3.3 Min-K; Sec. 4.1]
  *   - random dropping   D(a) with X_r a uniformly random k-subset            [Sec. 3.3 Random Elements]
+ *   - row form of X_r   the retained indices re-encoded as 16-bit positions within
+ *                       rows plus row offsets (lossless; the index cost the paper
+ *                       discusses)                          [Sec. 5, memory of indices; App. on choosing gamma]
  *   - recover           R(a^): dense tensor, dropped positions zero
  *                                                         [Sec. 3.2; Fig. 1 caption]
  *   - FC weight grad    g[j][c] = sum_n dz[n][j] * a^[n][c]
@@ -170,6 +173,44 @@ int oracle_compress_random(const void *x, int64_t numel, int dtype, int64_t k, u
     size_t es = (dtype == ORACLE_F32) ? 4 : 2;
     for (int64_t j = 0; j < k; ++j)
         memcpy((char *)vals + es * (size_t)j, (const char *)x + es * (size_t)idx[j], es);
+    return 0;
+}
+
+/* ---- row form of the retained index set ------------------------------- */
+/* The tensor is read as `rows` rows of `row_len` consecutive elements (its last
+ * dimension).  col[j] = idx[j] mod row_len; rowptr[r] = number of retained
+ * indices below r*row_len, r = 0..rows, so row r owns pairs rowptr[r] ..
+ * rowptr[r+1]-1.  Needs row_len <= 65536.  Returns 0, or -1 on bad arguments
+ * (including an index outside the tensor or out of order). */
+int oracle_rows_from_pairs(const int32_t *idx, int64_t k, int64_t rows, int64_t row_len,
+                           uint16_t *col, int32_t *rowptr)
+{
+    if (k < 0 || rows < 1 || row_len < 1 || row_len > 65536) return -1;
+    for (int64_t r = 0; r <= rows; ++r) rowptr[r] = 0;
+    for (int64_t j = 0; j < k; ++j) {
+        int64_t i = idx[j];
+        if (i < 0 || i >= rows * row_len) return -1;
+        if (j > 0 && idx[j - 1] >= idx[j]) return -1;
+        int64_t r = i / row_len;
+        col[j] = (uint16_t)(i - r * row_len);
+        rowptr[r + 1] += 1;                     /* count per row ... */
+    }
+    for (int64_t r = 0; r < rows; ++r) rowptr[r + 1] += rowptr[r];   /* ... then running sum */
+    return 0;
+}
+
+/* Inverse: idx[j] = r*row_len + col[j] for every j in row r. */
+int oracle_pairs_from_rows(const uint16_t *col, const int32_t *rowptr, int64_t rows, int64_t row_len,
+                           int32_t *idx)
+{
+    if (rows < 1 || row_len < 1 || row_len > 65536 || rowptr[0] != 0) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        if (rowptr[r + 1] < rowptr[r]) return -1;
+        for (int64_t j = rowptr[r]; j < rowptr[r + 1]; ++j) {
+            if (col[j] >= row_len) return -1;
+            idx[j] = (int32_t)(r * row_len + col[j]);
+        }
+    }
     return 0;
 }
 
