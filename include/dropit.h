@@ -163,6 +163,40 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
                                  void *hip_stream);
 
 /*
+ * Row form of the cache: cheaper indices (Sec. 5 counts the indices as the
+ * method's memory cost; the appendix on choosing gamma prices an int32 index like
+ * an fp32 activation).  The tensor is read as rows of its last dimension
+ * (row_len = shape[ndim-1] <= 65536, rows = numel / row_len).  A retained element
+ * keeps its 16-bit position in its row, and each row one offset:
+ *     col[j]    = idx[j] mod row_len                       (k uint16)
+ *     rowptr[r] = number of retained elements before row r  (rows + 1 int32;
+ *                 row r owns pairs rowptr[r] .. rowptr[r+1]-1, rowptr[rows] = k)
+ * i.e. 2k + 4(rows+1) bytes of indices instead of 4k, lossless.
+ *
+ * dropit_compress_rows: same selection, same vals as dropit_compress (min-k,
+ * ties to the lowest index, ascending order); col / rowptr [out] device.
+ * rowptr is always written, also for k == 0 (all zeros).  DROPIT_EINVAL if the
+ * last dimension exceeds 65536.  Workspace: dropit_compress_rows_workspace_bytes
+ * (the select's area plus 4k bytes for the flat indices it converts).
+ *
+ * dropit_weight_grad_rows: dropit_weight_grad from (vals, col, rowptr); same
+ * kernels, same results bit for bit.  The table is trusted like idx is (a
+ * malformed one gives a wrong gradient, never an out-of-bounds write into the
+ * workspace).  Workspace: dropit_weight_grad_rows_workspace_bytes.
+ */
+size_t dropit_compress_rows_workspace_bytes(int64_t numel, int64_t k, dropit_dtype dt);
+dropit_status dropit_compress_rows(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                                   double gamma, void *vals, uint16_t *col, int32_t *rowptr,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t dropit_weight_grad_rows_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                               int64_t k, int64_t c_out, const dropit_conv2d *conv);
+dropit_status dropit_weight_grad_rows(const void *vals, const uint16_t *col, const int32_t *rowptr,
+                                      int64_t k, const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                      const void *dY, int64_t c_out, const dropit_conv2d *conv,
+                                      float *dW, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream);
+
+/*
  * How dropit_compress runs its select (per host thread):
  *   0 (default)  one persistent kernel (it also clears its own exchange area), one workgroup per
  *                compute unit, grid barriers between its phases, launched as an ordinary kernel

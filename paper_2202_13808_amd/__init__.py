@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     compress,
     compress_random,
     compress_random_workspace_bytes,
+    compress_rows,
     compress_workspace_bytes,
     keep_count,
     lib,
@@ -19,5 +20,6 @@ from .binding import (  # noqa: F401
     set_select_mode,
     trace_events,
     weight_grad,
+    weight_grad_rows,
     weight_grad_workspace_bytes,
 )

@@ -61,6 +61,14 @@ def lib() -> ctypes.CDLL:
         L.dropit_compress_random_workspace_bytes.argtypes = [i64, i32]
         L.dropit_compress_random.restype = i32
         L.dropit_compress_random.argtypes = [vp, p64, i32, i32, dbl, ctypes.c_uint64, vp, vp, vp, sz, vp]
+        L.dropit_compress_rows_workspace_bytes.restype = sz
+        L.dropit_compress_rows_workspace_bytes.argtypes = [i64, i64, i32]
+        L.dropit_compress_rows.restype = i32
+        L.dropit_compress_rows.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp, vp, sz, vp]
+        L.dropit_weight_grad_rows_workspace_bytes.restype = sz
+        L.dropit_weight_grad_rows_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
+        L.dropit_weight_grad_rows.restype = i32
+        L.dropit_weight_grad_rows.argtypes = [vp, vp, vp, i64, p64, i32, i32, vp, i64, pconv, vp, vp, sz, vp]
         L.dropit_weight_grad_workspace_bytes.restype = sz
         L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
         L.dropit_set_select_mode.restype = i32
@@ -212,6 +220,57 @@ def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], d
             vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
             _shape_array(x_shape), len(x_shape), code, dY.data_ptr(), int(c_out),
             ctypes.byref(cs) if cs is not None else None, dW.data_ptr(),
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dW
+
+
+def compress_rows(x: torch.Tensor, gamma: float, workspace: Optional[torch.Tensor] = None,
+                  stream=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """dropit_compress_rows: (vals[k], col[k] int16 holding the uint16 in-row positions,
+    rowptr[rows+1] int32), rows being the last dimension of ``x``."""
+    _require_device(x, workspace)
+    code = _dtype_code(x.dtype)
+    k = keep_count(x.numel(), gamma)
+    if k < 0:
+        _check(EINVAL)
+    rows = x.numel() // x.shape[-1]
+    vals = torch.empty(k, dtype=x.dtype, device=x.device)
+    col = torch.empty(k, dtype=torch.int16, device=x.device)        # torch has no uint16 arithmetic; bits are uint16
+    rowptr = torch.empty(rows + 1, dtype=torch.int32, device=x.device)
+    if workspace is None:
+        need = int(lib().dropit_compress_rows_workspace_bytes(x.numel(), k, code))
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(lib().dropit_compress_rows(x.data_ptr(), _shape_array(x.shape), x.dim(), code, float(gamma),
+                                          vals.data_ptr() if k else None, col.data_ptr() if k else None,
+                                          rowptr.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                          _stream_ptr(stream)))
+    return vals, col, rowptr
+
+
+def weight_grad_rows(vals: torch.Tensor, col: torch.Tensor, rowptr: torch.Tensor, x_shape: Sequence[int],
+                     dY: torch.Tensor, c_out: int, conv=None, dW: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """dropit_weight_grad_rows: ``weight_grad`` from the row form of the cache."""
+    _require_device(vals, col, rowptr, dY, dW, workspace)
+    code = _dtype_code(dY.dtype)
+    if vals.dtype != dY.dtype or col.dtype != torch.int16 or rowptr.dtype != torch.int32:
+        raise ValueError("vals must have dY's dtype, col int16 (uint16 bits), rowptr int32")
+    cs = _conv_struct(conv)
+    x_shape = [int(s) for s in x_shape]
+    if dW is None:
+        dw_shape = (int(c_out), x_shape[-1]) if cs is None else (int(c_out), x_shape[1], cs.kh, cs.kw)
+        dW = torch.empty(dw_shape, dtype=torch.float32, device=dY.device)
+    k = int(vals.numel())
+    shape = _shape_array(x_shape)
+    ref = ctypes.byref(cs) if cs is not None else None
+    if workspace is None:
+        need = int(lib().dropit_weight_grad_rows_workspace_bytes(shape, len(x_shape), code, k, int(c_out), ref))
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dY.device)
+    with torch.cuda.device(dY.device):
+        _check(lib().dropit_weight_grad_rows(
+            vals.data_ptr() if k else None, col.data_ptr() if k else None, rowptr.data_ptr(), k,
+            shape, len(x_shape), code, dY.data_ptr(), int(c_out), ref, dW.data_ptr(),
             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dW
 

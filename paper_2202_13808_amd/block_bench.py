@@ -55,7 +55,7 @@ def encoder(depth: int, dim: int, heads: int, hidden: int, classes: int) -> torc
 def run(gamma: float, args) -> dict:
     torch.manual_seed(0)
     model = encoder(args.depth, args.dim, args.heads, 4 * args.dim, 1000).to("cuda:0", torch.bfloat16)
-    layers = dnn.apply_dropit(model, gamma) if gamma > 0 else []
+    layers = dnn.apply_dropit(model, gamma, index_format=args.index) if gamma > 0 else []
     opt = torch.optim.SGD(model.parameters(), lr=1e-3)
     x = torch.randn(args.batch, args.tokens, args.dim, device="cuda:0", dtype=torch.bfloat16)
     target = torch.randint(0, 1000, (args.batch,), device="cuda:0")
@@ -77,7 +77,7 @@ def run(gamma: float, args) -> dict:
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
     gib = 1.0 / (1 << 30)
-    return {"gamma": gamma, "dropit_layers": len(layers), "ms_per_iter": round(dt * 1e3, 2),
+    return {"gamma": gamma, "index": args.index, "dropit_layers": len(layers), "ms_per_iter": round(dt * 1e3, 2),
             "max_memory_GiB": round(torch.cuda.max_memory_allocated() * gib, 3),
             "dense_cache_GiB": round(meter.dense_bytes / args.steps * gib, 3),
             "value_cache_GiB": round(meter.value_bytes / args.steps * gib, 3),
@@ -93,6 +93,8 @@ def main() -> None:
     ap.add_argument("--depth", type=int, default=12)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--index", choices=["flat", "rows"], default="flat",
+                    help="cached index form: int32 flat indices, or 16-bit in-row positions + row offsets")
     ap.add_argument("--gammas", type=float, nargs="*", default=[0.0, 0.6, 0.7, 0.8, 0.9])
     args = ap.parse_args()
     if not torch.cuda.is_available():

@@ -29,6 +29,12 @@ from . import binding
 _Int2 = Union[int, Sequence[int]]
 
 
+def _check_format(index_format: str) -> str:
+    if index_format not in ("flat", "rows"):
+        raise ValueError("index_format must be 'flat' or 'rows'")
+    return index_format
+
+
 def _pair(v: _Int2) -> Tuple[int, int]:
     if isinstance(v, int):
         return (v, v)
@@ -46,13 +52,13 @@ class CacheMeter:
     def __init__(self) -> None:
         self.dense_bytes = 0     # what the same layers would have kept without dropping
         self.value_bytes = 0     # retained values
-        self.index_bytes = 0     # their int32 flat indices
+        self.index_bytes = 0     # their indices (int32 flat, or 16-bit in-row positions + row offsets)
         self.layers = 0
 
-    def _add(self, x: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor) -> None:
+    def _add(self, x: torch.Tensor, cache: Sequence[torch.Tensor]) -> None:
         self.dense_bytes += x.numel() * x.element_size()
-        self.value_bytes += vals.numel() * vals.element_size()
-        self.index_bytes += idx.numel() * idx.element_size()
+        self.value_bytes += cache[0].numel() * cache[0].element_size()
+        self.index_bytes += sum(t.numel() * t.element_size() for t in cache[1:])
         self.layers += 1
 
 
@@ -72,24 +78,36 @@ def cache_meter() -> Iterator[CacheMeter]:
         stack.pop()
 
 
-def _account(x: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor) -> None:
+def _account(x: torch.Tensor, cache: Sequence[torch.Tensor]) -> None:
     for meter in getattr(_meters, "stack", ()):
-        meter._add(x, vals, idx)
+        meter._add(x, cache)
 
 
-def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int]) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Min-k dropping, or (seed given) the random strategy of Sec. 3.3 with that seed."""
+def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int], rows: bool) -> Tuple[torch.Tensor, ...]:
+    """Min-k dropping, or (seed given) the random strategy of Sec. 3.3 with that seed.  Returns the
+    cache: (vals, idx), or with ``rows`` the cheaper (vals, col, rowptr) form."""
     if not x.is_cuda:
         raise RuntimeError("DropIT layers train on device tensors only: there is no CPU path")
     xc = x.detach()
     if not xc.is_contiguous():
         xc = xc.contiguous()
-    if seed is None:
-        vals, idx = binding.compress(xc, gamma)
+    if rows:
+        if seed is not None:
+            raise ValueError("the random strategy keeps flat indices (index_format='flat')")
+        cache = binding.compress_rows(xc, gamma)
+    elif seed is None:
+        cache = binding.compress(xc, gamma)
     else:
-        vals, idx = binding.compress_random(xc, gamma, seed)
-    _account(xc, vals, idx)
-    return vals, idx
+        cache = binding.compress_random(xc, gamma, seed)
+    _account(xc, cache)
+    return tuple(cache)
+
+
+def _weight_grad(cache: Sequence[torch.Tensor], x_shape, dy: torch.Tensor, c_out: int, conv=None) -> torch.Tensor:
+    dy = _match_dtype(dy, cache[0])
+    if len(cache) == 3:
+        return binding.weight_grad_rows(cache[0], cache[1], cache[2], x_shape, dy, c_out, conv=conv)
+    return binding.weight_grad(cache[0], cache[1], x_shape, dy, c_out, conv=conv)
 
 
 def _match_dtype(dy: torch.Tensor, vals: torch.Tensor) -> torch.Tensor:
@@ -102,34 +120,34 @@ def _match_dtype(dy: torch.Tensor, vals: torch.Tensor) -> torch.Tensor:
 # ---------------------------------------------------------------------------------------------
 class _LinearFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, gamma, seed):
+    def forward(ctx, x, weight, bias, gamma, seed, rows):
         y = F.linear(x, weight, bias)
-        vals, idx = _compress_input(x, gamma, seed)
-        ctx.save_for_backward(vals, idx, weight)
+        ctx.save_for_backward(weight, *_compress_input(x, gamma, seed, rows))
         ctx.x_shape = tuple(x.shape)
         ctx.has_bias = bias is not None
         return y
 
     @staticmethod
     def backward(ctx, dy):
-        vals, idx, weight = ctx.saved_tensors
+        weight, *cache = ctx.saved_tensors
         c_out, c_in = weight.shape
         dx = dw = db = None
         dy2 = dy.reshape(-1, c_out)
         if ctx.needs_input_grad[0]:
             dx = (dy2 @ weight.to(dy.dtype)).reshape(ctx.x_shape)
         if ctx.needs_input_grad[1]:
-            dw = binding.weight_grad(vals, idx, ctx.x_shape, _match_dtype(dy2, vals), c_out).to(weight.dtype)
+            dw = _weight_grad(cache, ctx.x_shape, dy2, c_out).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy2.sum(0)
-        return dx, dw, db, None, None
+        return dx, dw, db, None, None, None
 
 
 def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
-           gamma: float = 0.9, seed: Optional[int] = None) -> torch.Tensor:
+           gamma: float = 0.9, seed: Optional[int] = None, index_format: str = "flat") -> torch.Tensor:
     """``F.linear`` whose backward computes the weight gradient from the min-k cache of ``x``
-    (from a random cache drawn with ``seed`` when one is given)."""
-    return _LinearFn.apply(x, weight, bias, float(gamma), seed)
+    (from a random cache drawn with ``seed`` when one is given).  ``index_format`` "rows" caches
+    16-bit in-row positions and row offsets instead of int32 flat indices."""
+    return _LinearFn.apply(x, weight, bias, float(gamma), seed, _check_format(index_format) == "rows")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -137,10 +155,9 @@ def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] =
 # ---------------------------------------------------------------------------------------------
 class _Conv2dFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma, seed):
+    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma, seed, rows):
         y = F.conv2d(x, weight, bias, stride, padding, dilation, 1)
-        vals, idx = _compress_input(x, gamma, seed)
-        ctx.save_for_backward(vals, idx, weight)
+        ctx.save_for_backward(weight, *_compress_input(x, gamma, seed, rows))
         ctx.x_shape = tuple(x.shape)
         ctx.geometry = (stride, padding, dilation)
         ctx.has_bias = bias is not None
@@ -148,7 +165,7 @@ class _Conv2dFn(torch.autograd.Function):
 
     @staticmethod
     def backward(ctx, dy):
-        vals, idx, weight = ctx.saved_tensors
+        weight, *cache = ctx.saved_tensors
         stride, padding, dilation = ctx.geometry
         c_out, _, kh, kw = weight.shape
         dx = dw = db = None
@@ -156,18 +173,20 @@ class _Conv2dFn(torch.autograd.Function):
             dx = torch.nn.grad.conv2d_input(ctx.x_shape, weight.to(dy.dtype), dy, stride, padding, dilation, 1)
         if ctx.needs_input_grad[1]:
             conv = (kh, kw, stride[0], stride[1], padding[0], padding[1], dilation[0], dilation[1])
-            dw = binding.weight_grad(vals, idx, ctx.x_shape, _match_dtype(dy, vals), c_out, conv=conv).to(weight.dtype)
+            dw = _weight_grad(cache, ctx.x_shape, dy, c_out, conv=conv).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy.sum((0, 2, 3))
-        return dx, dw, db, None, None, None, None, None
+        return dx, dw, db, None, None, None, None, None, None
 
 
 def conv2d(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
            stride: _Int2 = 1, padding: _Int2 = 0, dilation: _Int2 = 1, gamma: float = 0.9,
-           seed: Optional[int] = None) -> torch.Tensor:
+           seed: Optional[int] = None, index_format: str = "flat") -> torch.Tensor:
     """``F.conv2d`` (groups = 1, zero padding, NCHW) whose backward computes the weight gradient
-    from the min-k cache of ``x`` (from a random cache drawn with ``seed`` when one is given)."""
-    return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma), seed)
+    from the min-k cache of ``x`` (from a random cache drawn with ``seed`` when one is given);
+    ``index_format`` as for ``linear``."""
+    return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma), seed,
+                           _check_format(index_format) == "rows")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -200,16 +219,19 @@ def _dropping(module: torch.nn.Module) -> bool:
 
 class Linear(torch.nn.Linear):
     def __init__(self, in_features: int, out_features: int, bias: bool = True, gamma: float = 0.9,
-                 strategy: str = "mink", seed: int = 0, device=None, dtype=None) -> None:
+                 strategy: str = "mink", seed: int = 0, index_format: str = "flat", device=None,
+                 dtype=None) -> None:
         super().__init__(in_features, out_features, bias, device=device, dtype=dtype)
         self.gamma = float(gamma)
         self.strategy = _check_strategy(strategy)
         self.seed = int(seed)
+        self.index_format = _check_format(index_format)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         if not _dropping(self):
             return F.linear(x, self.weight, self.bias)
-        return linear(x, self.weight, self.bias, self.gamma, _next_seed(self))
+        return linear(x, self.weight, self.bias, self.gamma, _next_seed(self),
+                      getattr(self, "index_format", "flat"))
 
     def extra_repr(self) -> str:
         return super().extra_repr() + ", gamma=%g" % self.gamma
@@ -220,26 +242,29 @@ def _conv_applicable(m: torch.nn.Conv2d) -> bool:
 
 
 class Conv2d(torch.nn.Conv2d):
-    def __init__(self, *args, gamma: float = 0.9, strategy: str = "mink", seed: int = 0, **kwargs) -> None:
+    def __init__(self, *args, gamma: float = 0.9, strategy: str = "mink", seed: int = 0,
+                 index_format: str = "flat", **kwargs) -> None:
         super().__init__(*args, **kwargs)
         if not _conv_applicable(self):
             raise ValueError("DropIT Conv2d supports groups=1, zero padding given as integers")
         self.gamma = float(gamma)
         self.strategy = _check_strategy(strategy)
         self.seed = int(seed)
+        self.index_format = _check_format(index_format)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         if not _dropping(self):
             return self._conv_forward(x, self.weight, self.bias)
         return conv2d(x, self.weight, self.bias, self.stride, self.padding, self.dilation, self.gamma,
-                      _next_seed(self))
+                      _next_seed(self), getattr(self, "index_format", "flat"))
 
     def extra_repr(self) -> str:
         return super().extra_repr() + ", gamma=%g" % self.gamma
 
 
 def apply_dropit(model: torch.nn.Module, gamma: float, skip_first: bool = True,
-                 skip_last: bool = True, strategy: str = "mink", seed: int = 0) -> List[str]:
+                 skip_last: bool = True, strategy: str = "mink", seed: int = 0,
+                 index_format: str = "flat") -> List[str]:
     """Switch the applicable layers of ``model`` to DropIT in place and return their names.
 
     Applicable: ``nn.Linear`` and ``nn.Conv2d`` (groups = 1, zero padding); the modules keep their
@@ -248,7 +273,8 @@ def apply_dropit(model: torch.nn.Module, gamma: float, skip_first: bool = True,
     otherwise: their inputs stay alive (or are created last) whatever the layer caches, so
     dropping there adds the sparse copy to the peak instead of lowering it.  ``strategy`` is
     "mink" (Sec. 3.3 Min-K Elements) or "random" (Sec. 3.3 Random Elements, seeded per layer
-    and per call from ``seed``)."""
+    and per call from ``seed``).  ``index_format`` "rows" caches 16-bit in-row positions and row
+    offsets instead of int32 flat indices (min-k only)."""
     found: List[Tuple[str, torch.nn.Module]] = []
     for name, m in model.named_modules():
         if type(m) is torch.nn.Linear or (type(m) is torch.nn.Conv2d and _conv_applicable(m)):
@@ -258,7 +284,9 @@ def apply_dropit(model: torch.nn.Module, gamma: float, skip_first: bool = True,
     if skip_last and found:
         found = found[:-1]
     _check_strategy(strategy)
+    _check_format(index_format)
     for number, (_, m) in enumerate(found):
+        m.index_format = index_format
         m.__class__ = Linear if isinstance(m, torch.nn.Linear) else Conv2d
         m.gamma = float(gamma)
         m.strategy = strategy

@@ -22,7 +22,9 @@ def test_header_declares_the_expected_entry_points():
     assert declared_symbols() == sorted([
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
         "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode",
-        "dropit_compress_random_workspace_bytes", "dropit_compress_random"])
+        "dropit_compress_random_workspace_bytes", "dropit_compress_random",
+        "dropit_compress_rows_workspace_bytes", "dropit_compress_rows",
+        "dropit_weight_grad_rows_workspace_bytes", "dropit_weight_grad_rows"])
 
 
 def test_library_exports_every_declared_symbol():
@@ -99,6 +101,29 @@ def test_compress_random_rejects_bad_arguments_without_a_gpu():
     assert L.dropit_compress_random_workspace_bytes(n, binding.BF16) >= L.dropit_compress_workspace_bytes(n, binding.BF16) + 8 * n
     assert L.dropit_compress_random_workspace_bytes(0, binding.BF16) == 0
     assert L.dropit_compress_random_workspace_bytes(1 << 31, binding.BF16) == 0
+
+
+def test_row_form_rejects_bad_arguments_without_a_gpu():
+    L = dropit.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ws = ctypes.c_void_p(0x10000)
+    big = 1 << 30
+    call = L.dropit_compress_rows
+    assert call(fake, _shape(2, 65537), 2, binding.BF16, 0.5, fake, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, None, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, None, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 2.0, fake, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, fake, ws, 64, None) == binding.EWORKSPACE
+    assert L.dropit_compress_rows_workspace_bytes(1 << 20, 1 << 18, binding.BF16) >= \
+        L.dropit_compress_workspace_bytes(1 << 20, binding.BF16) + 4 * (1 << 18)
+    assert L.dropit_compress_rows_workspace_bytes(16, 17, binding.BF16) == 0
+    wg = L.dropit_weight_grad_rows
+    dw = ctypes.c_void_p(0x2000)
+    assert wg(fake, fake, fake, 4, _shape(2, 65537), 2, binding.BF16, fake, 8, None, dw, ws, big, None) == binding.EINVAL
+    assert wg(fake, None, fake, 4, _shape(4, 8), 2, binding.BF16, fake, 8, None, dw, ws, big, None) == binding.EINVAL
+    assert wg(fake, fake, fake, 4, _shape(4, 8), 2, binding.BF16, fake, 8, None, dw, ws, 16, None) == binding.EWORKSPACE
+    assert L.dropit_weight_grad_rows_workspace_bytes(_shape(4, 8), 2, binding.BF16, 4, 8, None) > \
+        L.dropit_weight_grad_workspace_bytes(_shape(4, 8), 2, binding.BF16, 4, 8, None)
 
 
 def test_select_mode_switch_validates():

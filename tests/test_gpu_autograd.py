@@ -157,6 +157,34 @@ def test_cached_value_bytes_fall_by_gamma(gamma):
     assert abs(saved - expect) <= 0.02 * meter.dense_bytes, (saved, expect)
 
 
+def test_row_index_format_gives_the_same_gradients_with_half_the_index_bytes():
+    torch.manual_seed(8)
+    x_h = activation((6, 50, 96), "gelu", 61, "bf16")
+    dy = to_device(gradient((6, 50, 40), 0.02, 62, "bf16"))
+    flat = dnn.Linear(96, 40, gamma=0.8, device="cuda:0", dtype=torch.bfloat16)
+    rows = dnn.Linear(96, 40, gamma=0.8, index_format="rows", device="cuda:0", dtype=torch.bfloat16)
+    rows.load_state_dict(flat.state_dict())
+    with dnn.cache_meter() as mf:
+        flat(to_device(x_h)).backward(dy)
+    with dnn.cache_meter() as mr:
+        rows(to_device(x_h)).backward(dy)
+    torch.cuda.synchronize()
+    assert torch.equal(flat.weight.grad, rows.weight.grad)
+    k = dropit.keep_count(x_h.size, 0.8)
+    assert mf.index_bytes == 4 * k and mr.index_bytes == 2 * k + 4 * (300 + 1)
+    assert mf.value_bytes == mr.value_bytes == 2 * k
+    conv = dnn.Conv2d(8, 8, 3, padding=1, gamma=0.8, index_format="rows", device="cuda:0", dtype=torch.bfloat16)
+    xc = to_device(activation((2, 8, 16, 16), "relu", 63, "bf16"))
+    conv(xc).float().sum().backward()
+    ref = dnn.Conv2d(8, 8, 3, padding=1, gamma=0.8, device="cuda:0", dtype=torch.bfloat16)
+    ref.load_state_dict(conv.state_dict())
+    ref(xc).float().sum().backward()
+    torch.cuda.synchronize()
+    assert torch.equal(conv.weight.grad, ref.weight.grad)
+    with pytest.raises(ValueError):
+        dnn.Linear(8, 8, strategy="random", index_format="rows", device="cuda:0")(torch.randn(4, 8, device="cuda:0"))
+
+
 def test_training_steps_reduce_the_loss():
     """A few SGD steps on a small regression problem with gamma = 0.9: the approximate weight gradient
     (Sec. 3.4: still a descent direction in expectation) must drive the loss down."""
