@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time the vendor library's dense weight gradient (torch.mm / conv2d_weight) on the "
+                         "same shapes and inputs, reported as context under 'vendor_gemm'")
     ap.add_argument("--warm", action="store_true",
                     help="time with ONE input copy (x / dY then stay in the 256 MB Infinity Cache) instead of "
                          "rotating over > 600 MB of copies; the rotating (cold) figure is the default")
@@ -274,6 +277,28 @@ def main():
             "avg_kernel_ms": hist_ms,
         },
     }
+    if args.vendor_gemm and bf16:
+        # Context, not part of the path: what the dense weight gradient of the same layer costs through the
+        # vendor libraries torch calls (no dropping, no recover), same rotating inputs, events on the stream.
+        def vendor(i):
+            x, dy = xs[i % copies], dys[i % copies]
+            if w.conv is None:
+                return torch.mm(dy.reshape(-1, w.c_out).t(), x.reshape(-1, w.x_shape[-1]))
+            return torch.nn.grad.conv2d_weight(x, w.dw_shape, dy, stride=w.conv[2], padding=w.conv[3])
+        for i in range(10):
+            vendor(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(50):
+            vendor(i)
+        e1.record()
+        torch.cuda.synchronize()
+        v_ms = e0.elapsed_time(e1) / 50
+        out["vendor_gemm"] = {"ms": v_ms, "TFLOPs": flops / (v_ms * 1e-3) * 1e-12,
+                              "pct_mfma_peak": 100.0 * flops / (v_ms * 1e-3) * 1e-12 / MFMA_BF16_PEAK_TFLOPS,
+                              "note": "dense dW of the same layer by torch (vendor GEMM / convolution library), "
+                                      "bf16 output; this library's recover + GEMM + reduce take dw_ms"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, flops)
     print(json.dumps(out))
