@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "dropit.h"
 
 namespace dropit {
@@ -27,6 +29,21 @@ inline int64_t checked_numel(const int64_t *shape, int ndim)
         n *= shape[i];
     }
     return n;
+}
+
+// Runs `setup` (returns true on success) once for every device this process uses, on the device that
+// is current: kernel attributes and occupancy answers belong to a device, not to the process.  Two
+// threads may both run it the first time, which is harmless for idempotent set-up.  Devices beyond
+// the 64th run it on every call.
+template <typename F> inline bool once_per_device(std::atomic<uint64_t> &done, F &&setup)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && (done.load(std::memory_order_acquire) >> dev & 1)) return true;
+    if (!setup()) return false;
+    if (tracked) done.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+    return true;
 }
 
 inline dropit_status launch_status()

@@ -1132,22 +1132,28 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
                                       4 * size_t(TILE_WORDS > HIST_WORDS ? TILE_WORDS : HIST_WORDS);
         static_assert(size_t(FUSED_RES) * SEL_THREADS * 16 >= 4 * ((size_t(1) << 13) + 2 * WAVE),
                       "the serial fallback keeps its histogram where the chunk head was parked");
-        // how many workgroups of this kernel the device holds at once (asked once per element type)
-        static int capacity = 0;
-        if (capacity == 0) {
-            capacity = -1;
+        // how many workgroups of this kernel each device holds at once (asked once per element type and device)
+        static std::atomic<uint64_t> asked{0};
+        static int capacity_of[64] = {};
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        int fresh = -1;
+        const bool ok = once_per_device(asked, [&] {
             hipDeviceProp_t prop;
-            int dev = 0, per_cu = 0;
-            if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            int per_cu = 0;
+            if (hipGetDeviceProperties(&prop, dev) == hipSuccess &&
                 hipFuncSetAttribute(reinterpret_cast<const void *>(select_fused_kernel<RAW>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     static_cast<int>(smem_bytes)) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, select_fused_kernel<RAW>, SEL_THREADS,
                                                              smem_bytes) == hipSuccess &&
                 per_cu > 0 && prop.multiProcessorCount > 0)
-                capacity = std::min(per_cu * prop.multiProcessorCount, SEL_MAX_CHUNKS);
+                fresh = std::min(per_cu * prop.multiProcessorCount, SEL_MAX_CHUNKS);
             (void)hipGetLastError();
-        }
+            if (dev >= 0 && dev < 64) capacity_of[dev] = fresh;
+            return true;                       // a device that cannot hold the kernel is an answer too (-1)
+        });
+        const int capacity = !ok ? -1 : (dev >= 0 && dev < 64) ? capacity_of[dev] : fresh;
         if (capacity > 0) {
             // chunk geometry: at most one workgroup per resident slot, chunks start on 128-byte lines
             int64_t nvf = numel / VEC;

@@ -574,15 +574,15 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     float *partial = reinterpret_cast<float *>(ws + plan.dense_bytes);
     const int64_t ntok_pad = int64_t(plan.nkb) * Cfg::BK;
 
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, RECOVER_ELEMS_MAX * 2) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) != hipSuccess)
-            return DROPIT_EHIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> attr_set{0};
+    if (!once_per_device(attr_set, [] {
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       RECOVER_ELEMS_MAX * 2) == hipSuccess &&
+                   hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess;
+        }))
+        return DROPIT_EHIP;
 
     trace_mark(stream);
     const int recover_grid = int((ntok_pad + plan.rows_per_wg - 1) / plan.rows_per_wg);
