@@ -254,9 +254,10 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
 }
 
 // dW[j][c][tap] = sum over the GEMM workgroups' partials partial[p][tap][j][c], in a fixed order:
-// a workgroup takes 64 consecutive (tap, j, c) outputs; each of its 4 wavefronts adds a quarter
-// of the parts in ascending order, then the first wavefront adds the 4 sums in ascending order.
-constexpr int RED_GROUPS = 4;
+// a workgroup takes 64 consecutive (tap, j, c) outputs; each of its 16 wavefronts adds a sixteenth
+// of the parts in ascending order (enough loads in flight to cover the memory latency), then the
+// first wavefront adds the 16 sums in ascending order.
+constexpr int RED_GROUPS = 16;
 __global__ void __launch_bounds__(64 * RED_GROUPS)
 conv_reduce_kernel(const float *__restrict__ partial, int parts, int J, int C, float *__restrict__ dW)
 {
@@ -269,6 +270,7 @@ conv_reduce_kernel(const float *__restrict__ partial, int parts, int J, int C, f
     if (i < total) {
         const int per = (parts + RED_GROUPS - 1) / RED_GROUPS;
         const int p0 = grp * per, p1 = min(p0 + per, parts);
+#pragma unroll 8
         for (int p = p0; p < p1; ++p) s += partial[int64_t(p) * total + i];
     }
     s_sum[grp][o] = s;
