@@ -115,15 +115,32 @@ fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__
     int64_t lo, hi;
     block_lower_bound2<RECOVER_THREADS>(idx, k, first, last, lo, hi);  // its barriers also order the zero fill
     const uint32_t span = uint32_t(last - first);
-    for (int64_t j = lo + tid; j < hi; j += RECOVER_THREADS) {
-        const uint32_t rel = uint32_t(int64_t(idx[j]) - first);
-        if (rel >= span) continue;                                    // never for a sorted, in-range index array
-        uint32_t pos = rel;
-        if (pitch != cin) {
-            const uint32_t row = rel / uint32_t(cin);
-            pos = row * uint32_t(pitch) + (rel - row * uint32_t(cin));
+    // eight pairs per thread at a time: their loads are all in flight before the first LDS store
+    constexpr int BATCH = 8;
+    for (int64_t j0 = lo + tid; j0 < hi; j0 += int64_t(BATCH) * RECOVER_THREADS) {
+        int32_t pi[BATCH];
+        uint16_t pv[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
+            if (j < hi) {
+                pi[u] = idx[j];
+                pv[u] = vals[j];
+            }
         }
-        tile[pos] = vals[j];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
+            if (j >= hi) continue;
+            const uint32_t rel = uint32_t(int64_t(pi[u]) - first);
+            if (rel >= span) continue;                                // never for a sorted, in-range index array
+            uint32_t pos = rel;
+            if (pitch != cin) {
+                const uint32_t row = rel / uint32_t(cin);
+                pos = row * uint32_t(pitch) + (rel - row * uint32_t(cin));
+            }
+            tile[pos] = pv[u];
+        }
     }
     __syncthreads();
     u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
@@ -504,8 +521,17 @@ splitk_sum_kernel(const f32x4 *__restrict__ partial, int splits, int M, int N, i
     const int64_t tiles = int64_t(nb_count) * mb_count;
     const int64_t total = tiles * TILE4;
     for (int64_t g = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; g < total; g += int64_t(gridDim.x) * blockDim.x) {
+        // eight slices at a time: all their loads are issued before the first add
         f32x4 s = partial[g];
-        for (int p = 1; p < splits; ++p) s += partial[p * total + g];
+        for (int p0 = 1; p0 < splits; p0 += 8) {
+            f32x4 part[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (p0 + u < splits) part[u] = partial[(p0 + u) * total + g];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (p0 + u < splits) s += part[u];
+        }
         const int tile = int(g / TILE4), r = int(g % TILE4);
         const int tid = r % C::NTHREADS, slot = r / C::NTHREADS;   // slot = (i * FN + j) * 4 + q
         const int q = slot & 3, j = (slot >> 2) % C::FN, i = (slot >> 2) / C::FN;
@@ -602,7 +628,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     trace_mark(stream);
     if (plan.splits > 1) {
         const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (Cfg::BM * Cfg::BN / 4);
-        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 4096));
+        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
         splitk_sum_kernel<Cfg><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
                                                            int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
     }
