@@ -38,7 +38,7 @@ constexpr int SEL_THREADS = 1024;
 constexpr int SEL_MAX_CHUNKS = 512;
 constexpr int SEL_UNROLL = 4;
 constexpr int MAX_HIST_BITS = 13;
-constexpr int MAX_LAST_BINS = 32;
+constexpr int MAX_LAST_BINS = 48;       // rows of the per-chunk table: up to three 16-key bins of a sampled bracket, else 2^LAST_BITS
 
 struct SelState {
     uint32_t prefix;     // key digits resolved so far (key >> remaining bits)
@@ -49,7 +49,7 @@ struct SelState {
     uint32_t barrier;    // arrivals at the fused kernel's grid barriers (monotone within a call)
     uint32_t error;      // hint: some workgroup ran out of patience at a grid barrier (the others stop waiting)
     uint32_t exited;     // fused kernel: low 16 bits = workgroups done, high 16 bits = how many of them gave up
-    uint32_t pad0;
+    uint32_t path;       // fused kernel, for the tests: 0 exact digit histograms, 1 sampled bracket confirmed, 2 sampled bracket missed (exact retry)
     unsigned long long ready;    // == the call's generation number once workgroup 0 has cleared the words above and the histograms
     uint32_t pad[50];
 };
@@ -503,6 +503,76 @@ __device__ inline void resolve_digit_local(const uint32_t *hist, uint32_t &prefi
     __syncthreads();
 }
 
+// ---- sampled first digit (16-bit element types) ---------------------------------------------------
+// The first digit's histogram needs one LDS atomic per element, which is what bounds that pass
+// (an LDS atomic costs a wavefront ~16 cycles whatever it adds).  The bin that holds the k-th largest
+// key can be predicted from a sample instead: one 1 KB block of vectors (a wavefront's load) in
+// eight, picked by a hash of its position.  The prediction is a bracket of up to three adjacent bins
+// around the sample's quantile, wide enough for 8 standard deviations of the sampling error, and it
+// is only a prediction: the pass over all elements that follows counts exactly how many keys lie
+// above the bracket and how many on each key inside it, so a bracket that does not contain the k-th
+// largest key is detected, and the selection then repeats with the exact histogram.  The result is
+// the same in every case; only the time differs.
+constexpr int SAMPLE_BITS = 3;                        // 1 block in 8
+constexpr int64_t SAMPLE_MIN_NUMEL = int64_t(1) << 21; // below this the exact histogram is cheap and the sample thin
+constexpr int BRACKET_MAX_BINS = 3;
+
+// `first` = index of the first of the 64 consecutive vectors a wavefront handles together
+__device__ inline bool block_sampled(int64_t first)
+{
+    return ((static_cast<uint32_t>(first >> 3) * 0x9E3779B1u) >> (32 - SAMPLE_BITS)) == 0u;
+}
+
+// From the merged sample histogram: the bins that hold the sample ranks r - margin and r + margin,
+// r = the sample's share of k.  Returns false (in every thread) if there is no usable bracket (thin
+// or empty sample, a quantile too close to either end, more than BRACKET_MAX_BINS bins).
+template <int NB>
+__device__ inline bool sample_bracket(const uint32_t *hist, uint32_t k, int64_t numel, uint32_t *wave_tot,
+                                      uint32_t *bcast /*[3]*/, uint32_t &b_lo, uint32_t &b_hi)
+{
+    constexpr int PER = (NB + SEL_THREADS - 1) / SEL_THREADS;
+    const int tid = threadIdx.x;
+    const int hi_bin = NB - 1 - tid * PER;           // as in resolve_digit_local: descending bins, ascending ranks
+    uint32_t c[PER];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        c[i] = (hi_bin - i >= 0) ? dev_load(hist + hi_bin - i) : 0u;
+        mine += c[i];
+    }
+    uint32_t total;
+    const uint32_t above = block_exclusive_scan<SEL_THREADS>(mine, wave_tot, total);
+    const float frac = static_cast<float>(k) / static_cast<float>(numel);
+    const float r = frac * static_cast<float>(total);
+    const float margin = 8.0f * __builtin_sqrtf(fmaxf(r * (1.0f - frac), 1.0f)) + 16.0f;
+    const float lo_f = r - margin, hi_f = r + margin;
+    const bool usable = total >= 4096u && lo_f >= 1.0f && hi_f <= static_cast<float>(total) - 1.0f;
+    if (tid == 0) bcast[2] = usable ? 1u : 0u;
+    if (usable) {
+        const uint32_t rank[2] = {static_cast<uint32_t>(lo_f), static_cast<uint32_t>(hi_f) + 1u};   // higher bin first
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (above < rank[q] && rank[q] <= above + mine) {
+                uint32_t a = above;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) {
+                    if (a + c[i] >= rank[q]) {
+                        bcast[q] = static_cast<uint32_t>(hi_bin - i);
+                        break;
+                    }
+                    a += c[i];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    b_hi = bcast[0];
+    b_lo = bcast[1];
+    const bool ok = bcast[2] != 0 && b_hi >= b_lo && b_hi - b_lo < static_cast<uint32_t>(BRACKET_MAX_BINS);
+    __syncthreads();
+    return ok;
+}
+
 // The parallel selection.  Returns (the same in every thread) SEL_DONE, or SEL_GAVE_UP if a grid
 // barrier ran out of patience, or SEL_NEVER_READY if the exchange area was never published; in the
 // last two cases the outputs are incomplete (whatever was written is correct, nothing is out of bounds).
@@ -556,8 +626,11 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         // with probability 2^-64.  Device-scope atomic stores, like everything else that is exchanged.
         if (blockIdx.x == 0) {
             // only the bins this element type uses: bf16 one 2048-bin pass, fp32 two 8192-bin passes (hist1 follows hist0)
+            // (16-bit types: hist0 takes the sampled histogram, hist1 the exact one should the sample mislead)
             constexpr int CLEAR_WORDS = F32 ? 2 * (1 << MAX_HIST_BITS) : (1 << BITS1);
             for (int i = tid; i < CLEAR_WORDS; i += SEL_THREADS) dev_store(hist0 + i, 0u);
+            if constexpr (!F32)
+                for (int i = tid; i < CLEAR_WORDS; i += SEL_THREADS) dev_store(hist1 + i, 0u);
             if (tid == 0) {
                 dev_store(&st->barrier, 0u);
                 dev_store(&st->error, 0u);
@@ -606,27 +679,55 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     STAMP();
 
     // ---- digit histograms ---------------------------------------------------------
-    auto hist_pass = [&](auto shift_c, auto bits_c, auto first_c, uint32_t *ghist) {
+    __shared__ uint32_t verdict;
+    __shared__ uint32_t offs[2];
+    // visits only the sampled 1 KB blocks of the chunk (the ragged tail of the tensor is left out)
+    auto for_sample = [&](auto f) {
+        for (int i = 0; i < nres; ++i) {
+            const int64_t v = v0 + int64_t(i) * SEL_THREADS + tid;
+            if (block_sampled(v - lane) && v < v1)
+                for_each_raw(RAW(0), res[i * SEL_THREADS + tid], [&](uint32_t raw, int) { f(raw); });
+        }
+        for (int64_t vb = v_stream; vb < v1; vb += SEL_THREADS * SEL_UNROLL) {
+            u32x4 q[SEL_UNROLL];
+            bool on[SEL_UNROLL];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) {          // the sampled loads of four rows are in flight together
+                const int64_t v = vb + u * SEL_THREADS + tid;
+                on[u] = block_sampled(v - lane) && v < v1;
+                q[u] = on[u] ? xv[v] : u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u)
+                if (on[u]) for_each_raw(RAW(0), q[u], [&](uint32_t raw, int) { f(raw); });
+        }
+    };
+    // One digit's histogram of the chunk (of its sampled blocks only if SAMPLED), merged into ghist; ends
+    // with a grid barrier, after which ghist holds the whole tensor's (sample's) histogram.
+    auto hist_pass = [&](auto shift_c, auto bits_c, auto first_c, auto sampled_c, bool wait_ready,
+                         uint32_t *ghist) -> SelOutcome {
         constexpr int SHIFT = decltype(shift_c)::value, BITS = decltype(bits_c)::value;
-        constexpr bool FIRST = decltype(first_c)::value;
+        constexpr bool FIRST = decltype(first_c)::value, SAMPLED = decltype(sampled_c)::value;
         constexpr int NB = 1 << BITS;
         for (int i = tid; i < NB + 2 * WAVE; i += SEL_THREADS) lh[i] = 0;
         __syncthreads();
         const uint32_t zslot = NB + lane, dslot = NB + WAVE + lane;
-        for_chunk([&](uint32_t raw) {
+        auto add = [&](uint32_t raw) {
             const uint32_t key = raw & MASK;
             const uint32_t d = (key >> SHIFT) & (NB - 1);
             uint32_t a = d ? d : zslot;
             if (!FIRST) a = ((key >> (SHIFT + BITS)) == prefix) ? a : dslot;
             atomicAdd(&lh[a], 1u);
-        });
+        };
+        if constexpr (SAMPLED) for_sample(add);
+        else for_chunk(add);
         __syncthreads();
         if (tid < WAVE) {
             const uint32_t z = wave_sum(lh[NB + tid]);
             if (tid == 0) lh[0] += z;
         }
         __syncthreads();
-        if (FIRST) {                            // the exchange area must have been cleared for this call
+        if (wait_ready) {                       // the exchange area must have been cleared for this call
             if (tid == 0) {
                 uint32_t spins = 0, ok = 1;
                 while (dev_load64(&st->ready) != gen) {
@@ -648,82 +749,125 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         STAMP();
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
         STAMP();
-        resolve_digit_local<NB, BITS>(ghist, prefix, k_rem, wave_tot, bcast);
-        STAMP();
         return SEL_DONE;
     };
-    if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{},
-                                       std::true_type{}, hist0))
-        return o;
-    if constexpr (F32)
-        if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{},
-                                           std::false_type{}, hist1))
-            return o;
 
-    // ---- last digit and per-chunk counts -------------------------------------------
-    for (int i = tid; i <= LB; i += SEL_THREADS) lh[i] = 0;
-    __syncthreads();
-    {
-        // Few keys share the threshold's higher digits, so unlike the digit histograms this pass
-        // branches: a wavefront with no such key among its lanes skips the LDS atomic altogether
-        // (an LDS atomic costs its issue cycles whatever the number of active lanes).
-        uint32_t above = 0;
-        for_chunk([&](uint32_t raw) {
-            const uint32_t key = raw & MASK;
-            const uint32_t hi = key >> LAST_BITS;
-            above += (hi > prefix) ? 1u : 0u;
-            if (hi == prefix) atomicAdd(&lh[key & (LB - 1)], 1u);
-        });
-        above = wave_sum(above);
-        if (lane == 0 && above) atomicAdd(&lh[LB], above);
+    // The threshold lies in the key range [key_lo, key_lo + nf): exactly known after the digit
+    // histograms, or predicted from the sample (16-bit types, large tensors).
+    uint32_t key_lo = 0, nf = LB;
+    bool predicted = false, ready_seen = false, missed = false;
+    if constexpr (!F32) {
+        if (numel >= SAMPLE_MIN_NUMEL) {
+            if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{},
+                                               std::true_type{}, std::true_type{}, true, hist0))
+                return o;
+            ready_seen = true;
+            uint32_t b_lo, b_hi;
+            predicted = sample_bracket<(1 << BITS1)>(hist0, k, numel, wave_tot, bcast, b_lo, b_hi);
+            key_lo = b_lo << SHIFT1;                        // a first-digit bin is 2^SHIFT1 = 2^LAST_BITS keys
+            nf = (b_hi - b_lo + 1) << SHIFT1;
+            STAMP();
+        }
     }
-    __syncthreads();
-    if (tid <= LB) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
-    STAMP();
-    if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
-    STAMP();
 
-    for (int b = tid / WAVE; b < LB; b += NW) {      // totals per bin over all chunks
+    uint32_t t = 0, m = 0;
+    int d = 0;
+    for (;;) {
+        if (!predicted) {
+            // exact digits (after a sampled pass its histogram area is used up: the exact one goes to hist1)
+            prefix = 0;
+            k_rem = k;
+            uint32_t *h_first = ready_seen ? hist1 : hist0;
+            if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{},
+                                               std::true_type{}, std::false_type{}, !ready_seen, h_first))
+                return o;
+            ready_seen = true;
+            resolve_digit_local<(1 << BITS1), BITS1>(h_first, prefix, k_rem, wave_tot, bcast);
+            if constexpr (F32) {
+                if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{},
+                                                   std::false_type{}, std::false_type{}, false, hist1))
+                    return o;
+                resolve_digit_local<(1 << BITS2), BITS2>(hist1, prefix, k_rem, wave_tot, bcast);
+            }
+            key_lo = prefix << LAST_BITS;
+            nf = LB;
+            STAMP();
+        }
+
+        // ---- exact counts over the range and above it, per chunk ----------------------
+        for (int i = tid; i <= static_cast<int>(nf); i += SEL_THREADS) lh[i] = 0;
+        if (tid < 2) offs[tid] = 0;
+        __syncthreads();
+        {
+            // Few keys fall into the range, so unlike the digit histograms this pass branches: a
+            // wavefront with no such key among its lanes skips the LDS atomic altogether (an LDS
+            // atomic costs its issue cycles whatever the number of active lanes).
+            uint32_t above = 0;
+            const uint32_t key_end = key_lo + nf;
+            for_chunk([&](uint32_t raw) {
+                const uint32_t key = raw & MASK;
+                above += (key >= key_end) ? 1u : 0u;
+                const uint32_t rel = key - key_lo;             // wraps to a huge value below the range
+                if (rel < nf) atomicAdd(&lh[rel], 1u);
+            });
+            above = wave_sum(above);
+            if (lane == 0 && above) atomicAdd(&lh[nf], above);
+        }
+        __syncthreads();
+        if (tid <= static_cast<int>(nf)) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
+        STAMP();
+        if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
+        STAMP();
+
+        for (int b = tid / WAVE; b <= static_cast<int>(nf); b += NW) {      // totals per key (and above) over all chunks
+            uint32_t s = 0;
+            for (int c = lane; c < G; c += WAVE) s += dev_load(&table[b * G + c]);
+            s = wave_sum(s);
+            if (lane == 0) lh[b] = s;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            // the k-th largest key is in the range iff  #above < k <= #above + #in range
+            const uint32_t total_above = lh[nf];
+            uint32_t found = 0;
+            if (total_above < k) {
+                const uint32_t need = k - total_above;
+                uint32_t acc = 0;
+                for (int b = static_cast<int>(nf) - 1; b >= 0; --b) {
+                    if (acc + lh[b] >= need) {
+                        bcast[0] = key_lo + static_cast<uint32_t>(b);
+                        bcast[1] = need - acc;
+                        bcast[2] = static_cast<uint32_t>(b);
+                        found = 1;
+                        break;
+                    }
+                    acc += lh[b];
+                }
+            }
+            verdict = found;
+        }
+        __syncthreads();
+        if (verdict) break;
+        if (!predicted) return SEL_GAVE_UP;     // cannot happen with exact digits; the serial path would still answer
+        predicted = false;                       // the sample misled: once more with the exact histogram
+        missed = true;
+        __syncthreads();                         // everybody has read the verdict before it is written again
+    }
+    t = bcast[0];
+    m = bcast[1];
+    d = static_cast<int>(bcast[2]);
+    if (blockIdx.x == 0 && tid == 0) dev_store(&st->path, missed ? 2u : predicted ? 1u : 0u);
+    // exclusive offsets of this chunk: #{key > t} and #{key == t} in the chunks before it, one
+    // wavefront per row of the table from the threshold's row upwards (the last row counts the keys
+    // above the range)
+    for (int b = d + tid / WAVE; b <= static_cast<int>(nf); b += NW) {
         uint32_t s = 0;
-        for (int c = lane; c < G; c += WAVE) s += dev_load(&table[b * G + c]);
+        for (int c = lane; c < static_cast<int>(blockIdx.x); c += WAVE) s += dev_load(&table[b * G + c]);
         s = wave_sum(s);
-        if (lane == 0) lh[b] = s;
+        if (lane == 0 && s) atomicAdd(&offs[b == d ? 1 : 0], s);
     }
     __syncthreads();
-    if (tid == 0) {
-        uint32_t acc = 0;
-        int d = 0;
-        for (int b = LB - 1; b >= 0; --b) {
-            if (acc + lh[b] >= k_rem) { d = b; break; }
-            acc += lh[b];
-        }
-        bcast[0] = (prefix << LAST_BITS) | static_cast<uint32_t>(d);
-        bcast[1] = k_rem - acc;
-        bcast[2] = static_cast<uint32_t>(d);
-    }
-    __syncthreads();
-    const uint32_t t = bcast[0], m = bcast[1];
-    const int d = static_cast<int>(bcast[2]);
-    // exclusive offsets of this chunk: sums over the chunks before it
-    uint32_t mine_gt = 0, mine_eq = 0;
-    for (int c = tid; c < static_cast<int>(blockIdx.x); c += SEL_THREADS) {
-        uint32_t n[LB + 1];
-#pragma unroll
-        for (int b = 0; b <= LB; ++b) n[b] = dev_load(&table[b * G + c]);
-        uint32_t g = n[LB], e = 0;
-#pragma unroll
-        for (int b = 0; b < LB; ++b) {
-            g += (b > d) ? n[b] : 0u;
-            e = (b == d) ? n[b] : e;
-        }
-        mine_gt += g;
-        mine_eq += e;
-    }
-    uint32_t run_gt, run_eq;               // #{key > t}, #{key == t} before this chunk: the block totals
-    {
-        uint32_t ex_gt, ex_eq;
-        block_exclusive_scan2<SEL_THREADS>(mine_gt, mine_eq, wave_tot2, ex_gt, ex_eq, run_gt, run_eq);
-    }
+    uint32_t run_gt = offs[0], run_eq = offs[1];   // #{key > t}, #{key == t} before this chunk
     STAMP();
 
     // ---- ordered compaction -------------------------------------------------------

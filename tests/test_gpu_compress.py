@@ -139,6 +139,52 @@ def test_maximum_size_properties(dtype, mode):
     assert int(idx[kept == t][-1]) == want_last
 
 
+def _select_path(ws: torch.Tensor) -> int:
+    """White box: word 11 of the workspace's state block says how the persistent kernel found the threshold's
+    key range (0 exact digit histograms, 1 sampled bracket confirmed, 2 sampled bracket missed, exact retry)."""
+    return int(ws[:48].cpu().numpy().view(np.uint32)[11])
+
+
+def _run_with_path(x, gamma):
+    xd = to_device(x)
+    ws = torch.zeros(dropit.compress_workspace_bytes(x.size, xd.dtype), dtype=torch.uint8, device="cuda:0")
+    k = oracle.keep_count(x.size, gamma)
+    want_v, want_i = oracle.compress(x, k)
+    vals, idx = dropit.compress(xd, gamma, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(idx), want_i) and to_host(vals).tobytes() == want_v.tobytes()
+    return _select_path(ws)
+
+
+def test_sampled_bracket_paths():
+    """Large 16-bit tensors predict the threshold's bin from a sample of 1 KB blocks (1 in 8, by a hash of the
+    block's position) and confirm it with exact counts.  All three outcomes must give the oracle's bytes:
+    confirmed, unusable (quantile too close to an end), and missed -- forced here by giving exactly the blocks
+    the kernel samples a different scale from the rest, which no confidence margin can cover."""
+    numel = 1 << 22                                      # chunks are then whole multiples of 64 vectors: blocks align globally
+    rng = np.random.default_rng(99)
+    base = rng.standard_normal(numel, dtype=np.float32)
+    assert _run_with_path(f32_to_bf16_bits(base), 0.9) == 1
+    assert _run_with_path(f32_to_bf16_bits(base), 0.99999) == 0          # k = 41: no usable margin
+    assert _run_with_path(base, 0.9) == 0                                 # fp32 always builds the exact histograms
+    block = np.arange(numel // 512, dtype=np.uint64)                      # 64 vectors of 8 elements
+    sampled = (((block * 8) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)) >> np.uint64(29) == 0
+    assert 0.08 < sampled.mean() < 0.17
+    scale = np.where(np.repeat(sampled, 512), np.float32(0.01), np.float32(1.0))
+    assert _run_with_path(f32_to_bf16_bits(base * scale), 0.9) == 2
+    scale = np.where(np.repeat(sampled, 512), np.float32(100.0), np.float32(1.0))
+    assert _run_with_path(f32_to_bf16_bits(base * scale), 0.9) == 2
+    # a tensor of one value: every bin of the bracket but one is empty, the ties decide everything
+    assert _run_with_path(f32_to_bf16_bits(np.full(numel, 0.5, dtype=np.float32)), 0.9) in (0, 1)
+    # threshold exactly between two distant bins: 40 % large, 60 % small, k at the boundary +- 1
+    two = np.where(rng.random(numel) < 0.4, np.float32(8.0), np.float32(0.001)).astype(np.float32)
+    n_big = int((two == 8.0).sum())
+    for k in (n_big - 1, n_big, n_big + 1):
+        gamma = 1.0 - (k + 0.5) / numel
+        assert oracle.keep_count(numel, gamma) == k
+        _run_with_path(f32_to_bf16_bits(two), gamma)
+
+
 def test_deterministic_and_workspace_contents_irrelevant():
     x = activation((3001, 257), "gelu", 5, "bf16")
     xd = to_device(x)
