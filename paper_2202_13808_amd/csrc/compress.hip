@@ -516,6 +516,8 @@ __device__ inline void resolve_digit_local(const uint32_t *hist, uint32_t &prefi
 constexpr int SAMPLE_BITS = 3;                        // 1 block in 8
 constexpr int64_t SAMPLE_MIN_NUMEL = int64_t(1) << 21; // below this the exact histogram is cheap and the sample thin
 constexpr int BRACKET_MAX_BINS = 3;
+constexpr int SAMPLE_COPIES = 4;                      // the sample histogram is merged into 4 copies (workgroup index modulo 4):
+                                                      // 256 atomics on one hot bin's word take ~2.5 us one after the other
 
 // `first` = index of the first of the 64 consecutive vectors a wavefront handles together
 __device__ inline bool block_sampled(int64_t first)
@@ -537,7 +539,11 @@ __device__ inline bool sample_bracket(const uint32_t *hist, uint32_t k, int64_t 
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-        c[i] = (hi_bin - i >= 0) ? dev_load(hist + hi_bin - i) : 0u;
+        c[i] = 0u;
+        if (hi_bin - i >= 0) {
+#pragma unroll
+            for (int copy = 0; copy < SAMPLE_COPIES; ++copy) c[i] += dev_load(hist + copy * NB + hi_bin - i);
+        }
         mine += c[i];
     }
     uint32_t total;
@@ -627,10 +633,11 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         if (blockIdx.x == 0) {
             // only the bins this element type uses: bf16 one 2048-bin pass, fp32 two 8192-bin passes (hist1 follows hist0)
             // (16-bit types: hist0 takes the sampled histogram, hist1 the exact one should the sample mislead)
-            constexpr int CLEAR_WORDS = F32 ? 2 * (1 << MAX_HIST_BITS) : (1 << BITS1);
+            constexpr int CLEAR_WORDS = F32 ? 2 * (1 << MAX_HIST_BITS) : SAMPLE_COPIES * (1 << BITS1);
+            static_assert(SAMPLE_COPIES * (1 << 11) <= (1 << MAX_HIST_BITS), "the sample's copies share the first histogram area");
             for (int i = tid; i < CLEAR_WORDS; i += SEL_THREADS) dev_store(hist0 + i, 0u);
             if constexpr (!F32)
-                for (int i = tid; i < CLEAR_WORDS; i += SEL_THREADS) dev_store(hist1 + i, 0u);
+                for (int i = tid; i < (1 << BITS1); i += SEL_THREADS) dev_store(hist1 + i, 0u);
             if (tid == 0) {
                 dev_store(&st->barrier, 0u);
                 dev_store(&st->error, 0u);
@@ -681,6 +688,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     // ---- digit histograms ---------------------------------------------------------
     __shared__ uint32_t verdict;
     __shared__ uint32_t offs[2];
+    __shared__ uint32_t lp[MAX_LAST_BINS + 1];
     // visits only the sampled 1 KB blocks of the chunk (the ragged tail of the tensor is left out)
     auto for_sample = [&](auto f) {
         for (int i = 0; i < nres; ++i) {
@@ -742,9 +750,10 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             __syncthreads();
             if (bcast[3] == 0) return SEL_NEVER_READY;
         }
+        uint32_t *gcopy = SAMPLED ? ghist + (blockIdx.x % SAMPLE_COPIES) * NB : ghist;
         for (int i = tid; i < NB; i += SEL_THREADS) {
             const uint32_t c = lh[i];
-            if (c) atomicAdd(&ghist[i], c);
+            if (c) atomicAdd(&gcopy[i], c);
         }
         STAMP();
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
@@ -771,7 +780,6 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     }
 
     uint32_t t = 0, m = 0;
-    int d = 0;
     for (;;) {
         if (!predicted) {
             // exact digits (after a sampled pass its histogram area is used up: the exact one goes to hist1)
@@ -796,7 +804,6 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
 
         // ---- exact counts over the range and above it, per chunk ----------------------
         for (int i = tid; i <= static_cast<int>(nf); i += SEL_THREADS) lh[i] = 0;
-        if (tid < 2) offs[tid] = 0;
         __syncthreads();
         {
             // Few keys fall into the range, so unlike the digit histograms this pass branches: a
@@ -819,32 +826,56 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
         STAMP();
 
-        for (int b = tid / WAVE; b <= static_cast<int>(nf); b += NW) {      // totals per key (and above) over all chunks
-            uint32_t s = 0;
-            for (int c = lane; c < G; c += WAVE) s += dev_load(&table[b * G + c]);
-            s = wave_sum(s);
-            if (lane == 0) lh[b] = s;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            // the k-th largest key is in the range iff  #above < k <= #above + #in range
-            const uint32_t total_above = lh[nf];
-            uint32_t found = 0;
-            if (total_above < k) {
-                const uint32_t need = k - total_above;
-                uint32_t acc = 0;
-                for (int b = static_cast<int>(nf) - 1; b >= 0; --b) {
-                    if (acc + lh[b] >= need) {
-                        bcast[0] = key_lo + static_cast<uint32_t>(b);
-                        bcast[1] = need - acc;
-                        bcast[2] = static_cast<uint32_t>(b);
-                        found = 1;
-                        break;
-                    }
-                    acc += lh[b];
+        // Per row of the table (a key of the range; the last row = the keys above the range): the total
+        // over all chunks and the part in the chunks before this one, one wavefront per row.
+        {
+            // every wavefront takes up to ROWS rows (wave, wave + NW, ...); all their loads are issued together
+            constexpr int ROWS = (MAX_LAST_BINS + 1 + NW - 1) / NW;
+            constexpr int COLS = SEL_MAX_CHUNKS / WAVE;
+            const int wave = tid / WAVE;
+            uint32_t v[ROWS][COLS];
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+                for (int j = 0; j < COLS; ++j) {
+                    const int row = wave + r * NW, c = lane + j * WAVE;
+                    v[r][j] = (row <= static_cast<int>(nf) && c < G) ? dev_load(&table[row * G + c]) : 0u;
+                }
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int row = wave + r * NW;
+                if (row > static_cast<int>(nf)) break;         // uniform over the wavefront
+                uint32_t s = 0, sp = 0;
+#pragma unroll
+                for (int j = 0; j < COLS; ++j) {
+                    s += v[r][j];
+                    sp += (lane + j * WAVE < static_cast<int>(blockIdx.x)) ? v[r][j] : 0u;
+                }
+                s = wave_sum(s);
+                sp = wave_sum(sp);
+                if (lane == 0) {
+                    lh[row] = s;
+                    lp[row] = sp;
                 }
             }
-            verdict = found;
+        }
+        __syncthreads();
+        if (tid < WAVE) {
+            // Lane 0 takes the row above the range, lanes 1.. the range's keys in descending order, so a
+            // prefix scan over the lanes counts the keys above each key.  The k-th largest key is the one
+            // with  #above < k <= #above + #equal;  it is in the range iff that holds for a lane >= 1.
+            const int rr = static_cast<int>(nf) - lane;
+            const uint32_t full = rr >= 0 ? lh[rr] : 0u, part = rr >= 0 ? lp[rr] : 0u;
+            const uint32_t incl = wave_inclusive_scan(full), incl_p = wave_inclusive_scan(part);
+            const bool here = lane >= 1 && rr >= 0 && incl - full < k && k <= incl;
+            const unsigned long long hit = __ballot(here);
+            if (lane == 0) verdict = hit ? 1u : 0u;
+            if (here) {
+                bcast[0] = key_lo + static_cast<uint32_t>(rr);   // t
+                bcast[1] = k - (incl - full);                     // m: how many keys equal to t are kept
+                offs[0] = incl_p - part;                          // #{key > t} in the chunks before this one
+                offs[1] = part;                                   // #{key == t} there
+            }
         }
         __syncthreads();
         if (verdict) break;
@@ -855,18 +886,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     }
     t = bcast[0];
     m = bcast[1];
-    d = static_cast<int>(bcast[2]);
     if (blockIdx.x == 0 && tid == 0) dev_store(&st->path, missed ? 2u : predicted ? 1u : 0u);
-    // exclusive offsets of this chunk: #{key > t} and #{key == t} in the chunks before it, one
-    // wavefront per row of the table from the threshold's row upwards (the last row counts the keys
-    // above the range)
-    for (int b = d + tid / WAVE; b <= static_cast<int>(nf); b += NW) {
-        uint32_t s = 0;
-        for (int c = lane; c < static_cast<int>(blockIdx.x); c += WAVE) s += dev_load(&table[b * G + c]);
-        s = wave_sum(s);
-        if (lane == 0 && s) atomicAdd(&offs[b == d ? 1 : 0], s);
-    }
-    __syncthreads();
     uint32_t run_gt = offs[0], run_eq = offs[1];   // #{key > t}, #{key == t} before this chunk
     STAMP();
 
