@@ -987,9 +987,16 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                                            tot_gt, tot_eq);
         const uint32_t part_first = run_gt + min(run_eq, m);
         const uint32_t part_kept = (run_gt + tot_gt) + min(run_eq + tot_eq, m) - part_first;
-        if (part_kept <= uint32_t(TILE)) {                             // uniform over the workgroup
+        // 16-bit elements are staged as ONE word each, value << 16 | position within the super-tile,
+        // so the staging area holds half as many again (a super-tile that keeps a fifth of its
+        // elements still fits) and the scatter issues one LDS store per kept element.
+        constexpr bool PACKED = !F32;
+        static_assert(F32 || SUPER * VEC <= 65536, "a position within a super-tile fits 16 bits");
+        constexpr uint32_t STAGE_CAP = PACKED ? uint32_t(TILE + TILE / 2) : uint32_t(TILE);
+        if (part_kept <= STAGE_CAP) {                                  // uniform over the workgroup
             uint32_t my_gt = run_gt + ex_gt, my_eq = run_eq + ex_eq;
             const RAW *res_raw = reinterpret_cast<const RAW *>(res);
+            uint32_t *stage_pk = smem;
             unsigned long long todo = gtm | eqm;
             while (todo) {
                 const int b = __builtin_ctzll(todo);
@@ -997,8 +1004,13 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                 const bool gt = (gtm >> b) & 1ull;
                 if (gt || my_eq < m) {
                     const uint32_t slot = my_gt + min(my_eq, m) - part_first;
-                    stage_val[slot] = res_raw[mine0 * VEC + b];
-                    stage_idx[slot] = static_cast<int32_t>((sb + mine0) * VEC + b);
+                    const uint32_t off = static_cast<uint32_t>(mine0) * VEC + b;
+                    if constexpr (PACKED) {
+                        stage_pk[slot] = (static_cast<uint32_t>(res_raw[off]) << 16) | off;
+                    } else {
+                        stage_val[slot] = res_raw[off];
+                        stage_idx[slot] = static_cast<int32_t>(sb * VEC + off);
+                    }
                 }
                 my_gt += gt ? 1u : 0u;
                 my_eq += gt ? 0u : 1u;
@@ -1008,8 +1020,14 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             __syncthreads();
             for (uint32_t q = tid; q < part_kept; q += SEL_THREADS)
                 if (part_first + q < k) {          // always true for consistent counts
-                    vals[part_first + q] = stage_val[q];
-                    idx[part_first + q] = stage_idx[q];
+                    if constexpr (PACKED) {
+                        const uint32_t w = stage_pk[q];
+                        vals[part_first + q] = static_cast<RAW>(w >> 16);
+                        idx[part_first + q] = static_cast<int32_t>(sb * VEC + (w & 0xFFFFu));
+                    } else {
+                        vals[part_first + q] = stage_val[q];
+                        idx[part_first + q] = stage_idx[q];
+                    }
                 }
         } else {
             for (int i = 0; i < rows; ++i) {       // row by row; a row's scan starts with a barrier, which frees the staging buffers
