@@ -696,18 +696,21 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             if (block_sampled(v - lane) && v < v1)
                 for_each_raw(RAW(0), res[i * SEL_THREADS + tid], [&](uint32_t raw, int) { f(raw); });
         }
-        for (int64_t vb = v_stream; vb < v1; vb += SEL_THREADS * SEL_UNROLL) {
+        // streamed rows: a wavefront first looks up its next (up to) four sampled blocks -- the hash is
+        // uniform over the wavefront, so this is scalar work -- and then has their loads in flight together
+        const int64_t wave_first = v_stream + (tid - lane);
+        for (int64_t vb = wave_first; vb < v1;) {
+            int64_t pick[SEL_UNROLL];
+            int n = 0;
+            for (; vb < v1 && n < SEL_UNROLL; vb += SEL_THREADS)
+                if (block_sampled(vb)) pick[n++] = vb;
             u32x4 q[SEL_UNROLL];
-            bool on[SEL_UNROLL];
-#pragma unroll
-            for (int u = 0; u < SEL_UNROLL; ++u) {          // the sampled loads of four rows are in flight together
-                const int64_t v = vb + u * SEL_THREADS + tid;
-                on[u] = block_sampled(v - lane) && v < v1;
-                q[u] = on[u] ? xv[v] : u32x4{0, 0, 0, 0};
-            }
 #pragma unroll
             for (int u = 0; u < SEL_UNROLL; ++u)
-                if (on[u]) for_each_raw(RAW(0), q[u], [&](uint32_t raw, int) { f(raw); });
+                if (u < n && pick[u] + lane < v1) q[u] = xv[pick[u] + lane];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u)
+                if (u < n && pick[u] + lane < v1) for_each_raw(RAW(0), q[u], [&](uint32_t raw, int) { f(raw); });
         }
     };
     // One digit's histogram of the chunk (of its sampled blocks only if SAMPLED), merged into ghist; ends
