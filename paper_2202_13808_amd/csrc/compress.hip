@@ -21,7 +21,10 @@
 //
 // Default: ONE persistent kernel (select_fused_kernel) does all of it with grid
 // barriers between the steps, the chunk parked in LDS, and a serial redo path
-// should the barriers ever give up.  Alternative: the steps as separate kernels
+// should the barriers ever give up.  For large 16-bit tensors it predicts the
+// first digit from a sample of the tensor and lets the count pass, which is
+// exact, confirm the prediction (see "sampled first digit" below); the bytes
+// it writes are the same either way.  Alternative: the steps as separate kernels
 // (init, hist, count, compact) with a last-workgroup-to-arrive ticket instead of
 // barriers.  Nothing here synchronises with the host; counts are integer, so the
 // result does not depend on the order in which workgroups run.
