@@ -185,6 +185,47 @@ def test_sampled_bracket_paths():
         _run_with_path(f32_to_bf16_bits(two), gamma)
 
 
+def _structured(kind, numel, rng):
+    """Inputs whose values depend on the position in ways a block sample could trip over."""
+    base = rng.standard_normal(numel, dtype=np.float32)
+    if kind == "columns":            # every column of a 768-wide matrix has its own scale over four decades
+        scale = (10.0 ** rng.uniform(-2, 2, 768)).astype(np.float32)
+        return base * np.resize(scale, numel)
+    if kind == "sorted":             # magnitudes grow with the index
+        return np.sort(np.abs(base)) * np.where(rng.random(numel) < 0.5, np.float32(-1), np.float32(1))
+    if kind == "half_zero":          # nothing but zeros in the first half
+        base[: numel // 2] = 0.0
+        return base
+    if kind == "periodic":           # one 1 KB block in eight is a thousand times larger
+        blocks = np.arange(numel) // 512
+        return base * np.where(blocks % 8 == 3, np.float32(1000.0), np.float32(1.0))
+    if kind == "few_values":         # five distinct magnitudes: every threshold is a massive tie
+        return rng.choice(np.array([0.0, 0.25, -0.25, 1.0, -3.0, 7.0], dtype=np.float32), size=numel)
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["columns", "sorted", "half_zero", "periodic", "few_values"])
+def test_large_structured_inputs(kind):
+    """Large 16-bit tensors (the sampled first digit applies) with position-dependent structure, ragged tails and
+    several gammas: whichever path the kernel takes, the bytes are the oracle's."""
+    rng = np.random.default_rng(sum(kind.encode()))
+    numel = (1 << 21) + int(rng.integers(0, 1 << 20))
+    x = f32_to_bf16_bits(_structured(kind, numel, rng))
+    for gamma in (0.9, 0.5, 0.97):
+        path = _run_with_path(x, gamma)
+        print("structured", kind, numel, gamma, "path", path, flush=True)
+
+
+@pytest.mark.parametrize("numel", [(1 << 21) - 1, 1 << 21, (1 << 21) + 1, 3000017, 5 * (1 << 20) + 77])
+def test_sizes_around_the_sampling_threshold(numel):
+    rng = np.random.default_rng(numel)
+    x = f32_to_bf16_bits(rng.standard_normal(numel, dtype=np.float32))
+    expect_sampling = numel >= (1 << 21)
+    for gamma in (0.8, 0.95):
+        path = _run_with_path(x, gamma)
+        assert path in ((0, 1, 2) if expect_sampling else (0,)), (numel, gamma, path)
+
+
 def test_deterministic_and_workspace_contents_irrelevant():
     x = activation((3001, 257), "gelu", 5, "bf16")
     xd = to_device(x)
