@@ -23,12 +23,15 @@ rows_from_idx_kernel(const int32_t *__restrict__ idx, int64_t k, int64_t row_len
 {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
     for (int64_t j = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; j <= k; j += stride) {
-        const int64_t before = (j == 0) ? -1 : min<int64_t>(static_cast<int64_t>(idx[j - 1]) / row_len, rows);
+        // indices are below 2^31 and row_len <= 65536: 32-bit unsigned division
+        const uint32_t len = static_cast<uint32_t>(row_len);
+        const int64_t before = (j == 0) ? -1 : min<int64_t>(static_cast<uint32_t>(idx[j - 1]) / len, rows);
         int64_t here = rows;
         if (j < k) {
-            const int64_t flat = idx[j];
-            here = min<int64_t>(flat / row_len, rows);
-            col[j] = static_cast<uint16_t>(flat - here * row_len);
+            const uint32_t flat = static_cast<uint32_t>(idx[j]);
+            const uint32_t row = flat / len;
+            here = min<int64_t>(row, rows);
+            col[j] = static_cast<uint16_t>(flat - row * len);
         }
         for (int64_t r = before + 1; r <= here; ++r) rowptr[r] = static_cast<int32_t>(j);
     }

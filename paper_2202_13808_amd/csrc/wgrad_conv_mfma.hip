@@ -43,8 +43,9 @@ __global__ void __launch_bounds__(256)
 conv_rowptr_kernel(const int32_t *__restrict__ idx, int64_t k, int W, int64_t R, uint32_t *__restrict__ row_ptr)
 {
     for (int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; j <= k; j += int64_t(gridDim.x) * blockDim.x) {
-        const int64_t before = (j == 0) ? -1 : min<int64_t>(int64_t(idx[j - 1]) / W, R);
-        const int64_t here = (j == k) ? R : min<int64_t>(int64_t(idx[j]) / W, R);
+        // indices are below 2^31: 32-bit unsigned division (a 64-bit one is several times the instructions)
+        const int64_t before = (j == 0) ? -1 : min<int64_t>(uint32_t(idx[j - 1]) / uint32_t(W), R);
+        const int64_t here = (j == k) ? R : min<int64_t>(uint32_t(idx[j]) / uint32_t(W), R);
         for (int64_t r = max<int64_t>(before, -1) + 1; r <= here; ++r) row_ptr[r] = uint32_t(j);
     }
 }
