@@ -55,13 +55,15 @@ constexpr int RECOVER_ELEMS_MAX = 32768;
 // ---------------------------------------------------------------------------
 // Cooperative lower_bound over a sorted int32 array for two targets at once
 // (number of elements < t0 and < t1): THREADS-ary search, both targets share the
-// rounds, so ~3 rounds of one load each for a million elements.
+// rounds: 3 rounds of one load each over a million elements, 2 over a range of a few thousand.
 // All threads of the block must call it (contains barriers).
+// The search starts from the ranges [from0, to0) and [from1, to1), which must contain the respective
+// answers; the whole array is [0, n) for both.
 template <int THREADS>
-__device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64_t n, int64_t t0, int64_t t1,
-                                          int64_t &r0, int64_t &r1)
+__device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64_t t0, int64_t t1, int64_t from0,
+                                          int64_t to0, int64_t from1, int64_t to1, int64_t &r0, int64_t &r1)
 {
-    int64_t lo[2] = {0, 0}, hi[2] = {n, n};
+    int64_t lo[2] = {from0, from1}, hi[2] = {to0, to1};
     const int64_t target[2] = {t0, t1};
     while (hi[0] > lo[0] || hi[1] > lo[1]) {
         int pred[2];
@@ -98,9 +100,21 @@ __device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64
 // search), so the rows are assembled in LDS (zero fill, one 16-bit store per pair)
 // and leave as full 16-byte stores: every byte of the dense matrix is written exactly
 // once, no separate zero-fill pass.
+// Where the pairs of a flat-index range start is first guessed, not searched: min-k keeps a fixed
+// fraction of the tensor, so the pair with flat index f sits near position f * k / numel, and if the
+// kept elements are spread evenly the guess is off by a few sqrt(k) at most.  The workgroup loads a
+// window of pairs around the guesses for both ends of its rows in ONE round of loads (values included),
+// checks with the loaded indices themselves that the window covers its rows, and scatters what
+// belongs to them.  Only if the window does not cover them (density that varies along the tensor) does
+// it fall back to the exact search, three dependent rounds of loads, and a second round for the pairs.
+constexpr int RECOVER_WINDOW = 28;                    // window entries per thread, at most
+
+// WINDOWED = false is the same kernel without the guess (kept for tuning; the host uses
+// fc_recover_stream_kernel when the window would be several times the pairs a workgroup needs).
+template <bool WINDOWED>
 __global__ void __launch_bounds__(RECOVER_THREADS)
 fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int64_t ntok,
-                  int64_t ntok_pad, int cin, int pitch, int rows_per_wg, uint16_t *__restrict__ dense)
+                  int64_t ntok_pad, int cin, int pitch, int rows_per_wg, int64_t margin, uint16_t *__restrict__ dense)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [rows_per_wg][pitch]
     const int tid = threadIdx.x;
@@ -109,42 +123,168 @@ fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__
     const int rows = int(r1 - r0);
     const int chunks = rows * (pitch / 8);                            // 16-byte units
     u32x4 *tile16 = reinterpret_cast<u32x4 *>(tile);
-    for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
-
     const int64_t first = min(r0, ntok) * cin, last = min(r1, ntok) * cin;   // flat index range of these rows
-    int64_t lo, hi;
-    block_lower_bound2<RECOVER_THREADS>(idx, k, first, last, lo, hi);  // its barriers also order the zero fill
     const uint32_t span = uint32_t(last - first);
-    // eight pairs per thread at a time: their loads are all in flight before the first LDS store
-    constexpr int BATCH = 8;
-    for (int64_t j0 = lo + tid; j0 < hi; j0 += int64_t(BATCH) * RECOVER_THREADS) {
-        int32_t pi[BATCH];
-        uint16_t pv[BATCH];
+    const int64_t numel = ntok * cin;
+    auto place = [&](int32_t flat, uint32_t v) {
+        const uint32_t rel = uint32_t(int64_t(flat) - first);
+        if (rel >= span) return;                                      // not one of this workgroup's rows
+        uint32_t pos = rel;
+        if (pitch != cin) {
+            const uint32_t row = rel / uint32_t(cin);
+            pos = row * uint32_t(pitch) + (rel - row * uint32_t(cin));
+        }
+        tile[pos] = static_cast<uint16_t>(v);
+    };
+
+    // window of pairs around the interpolated positions of `first` and `last`
+    const int64_t g_lo = static_cast<int64_t>(static_cast<double>(first) * static_cast<double>(k) / static_cast<double>(numel));
+    const int64_t g_hi = static_cast<int64_t>(static_cast<double>(last) * static_cast<double>(k) / static_cast<double>(numel));
+    const int64_t w_lo = max<int64_t>(g_lo - margin, 0), w_hi = min<int64_t>(g_hi + margin, k);
+    const bool window_fits = WINDOWED && w_hi - w_lo <= int64_t(RECOVER_WINDOW) * RECOVER_THREADS;
+    constexpr int WN = WINDOWED ? RECOVER_WINDOW : 1;
+    int32_t wi[WN];
+    uint32_t wv[WN];        // a full register each: 16-bit destinations get packed in pairs, and the second load
+                            // of a pair then waits for the first
+    if (window_fits) {
 #pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
-            if (j < hi) {
-                pi[u] = idx[j];
-                pv[u] = vals[j];
+        for (int u = 0; u < WN; ++u) {
+            const int64_t j = w_lo + int64_t(u) * RECOVER_THREADS + tid;
+            if (j < w_hi) {
+                wi[u] = idx[j];
+                wv[u] = vals[j];
             }
         }
+    }
+    for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
+    // the window covers the rows iff nothing of them can lie before its first or after its last entry
+    bool uncovered = !window_fits;
+    if (window_fits && tid == 0) {
+        if (w_lo > 0 && w_lo < w_hi && int64_t(wi[0]) >= first) uncovered = true;
+        if (w_lo > 0 && w_lo >= w_hi) uncovered = first < last;       // empty window in the middle of the array
+    }
+    if (window_fits && w_hi < k) {
+        const int64_t j_last = w_hi - 1;                              // held by thread (j_last - w_lo) % THREADS, slot / THREADS
+        if (j_last >= w_lo && (j_last - w_lo) % RECOVER_THREADS == tid) {
+            bool short_of_end = false;
 #pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
-            if (j >= hi) continue;
-            const uint32_t rel = uint32_t(int64_t(pi[u]) - first);
-            if (rel >= span) continue;                                // never for a sorted, in-range index array
-            uint32_t pos = rel;
-            if (pitch != cin) {
-                const uint32_t row = rel / uint32_t(cin);
-                pos = row * uint32_t(pitch) + (rel - row * uint32_t(cin));
-            }
-            tile[pos] = pv[u];
+            for (int u = 0; u < WN; ++u)
+                if ((j_last - w_lo) / RECOVER_THREADS == u) short_of_end = int64_t(wi[u]) < last;
+            uncovered = uncovered || short_of_end;
         }
+    }
+    if (__syncthreads_or(uncovered)) {                                // also orders the zero fill before the scatter
+        int64_t lo, hi;
+        block_lower_bound2<RECOVER_THREADS>(idx, first, last, 0, k, 0, k, lo, hi);
+        // eight pairs per thread at a time: their loads are all in flight before the first LDS store
+        constexpr int BATCH = 8;
+        for (int64_t j0 = lo + tid; j0 < hi; j0 += int64_t(BATCH) * RECOVER_THREADS) {
+            int32_t pi[BATCH];
+            uint32_t pv[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
+                if (j < hi) {
+                    pi[u] = idx[j];
+                    pv[u] = vals[j];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u)
+                if (j0 + int64_t(u) * RECOVER_THREADS < hi) place(pi[u], pv[u]);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < WN; ++u)
+            if (w_lo + int64_t(u) * RECOVER_THREADS + tid < w_hi) place(wi[u], wv[u]);
     }
     __syncthreads();
     u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
     for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
+}
+
+// Recover for large k: the error of the interpolated guess grows with sqrt(k) (and with the ties at
+// the threshold, which are all kept at the low-index end of the tensor), the pairs of a tile do not, so
+// a window per tile would be mostly overlap -- and an exact search per tile costs ~500 scattered probes
+// of the index array (measured: 15 of 33 us on a 38 M-element tensor).  Here a workgroup takes several
+// consecutive tiles, searches once for the start of its first one, and then walks the pair arrays
+// forward: a tile's pairs follow the previous tile's.  A tile is done when a batch of pairs ends with
+// an index beyond it.
+__global__ void __launch_bounds__(RECOVER_THREADS)
+fc_recover_stream_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int64_t ntok,
+                         int64_t ntok_pad, int cin, int pitch, int rows_per_tile, int tiles_per_wg,
+                         uint16_t *__restrict__ dense)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [rows_per_tile][pitch]
+    constexpr int NWAVES = RECOVER_THREADS / WAVE;
+    constexpr int BATCH = 8;
+    __shared__ uint32_t wave_taken[2][NWAVES];
+    const int tid = threadIdx.x;
+    u32x4 *tile16 = reinterpret_cast<u32x4 *>(tile);
+    const int64_t tiles = (ntok_pad + rows_per_tile - 1) / rows_per_tile;
+    const int64_t t_begin = int64_t(blockIdx.x) * tiles_per_wg, t_end = min(t_begin + tiles_per_wg, tiles);
+
+    int64_t pos, unused;
+    {
+        const int64_t start = min(t_begin * rows_per_tile, ntok) * cin;
+        block_lower_bound2<RECOVER_THREADS>(idx, start, start, 0, k, 0, k, pos, unused);
+    }
+    uint32_t parity = 0;
+    for (int64_t t = t_begin; t < t_end; ++t) {
+        const int64_t r0 = t * rows_per_tile, r1 = min(r0 + rows_per_tile, ntok_pad);
+        const int chunks = int(r1 - r0) * (pitch / 8);                // 16-byte units
+        const int64_t first = min(r0, ntok) * cin, last = min(r1, ntok) * cin;
+        const uint32_t span = uint32_t(last - first);
+        // the first batch's loads are issued before the zero fill
+        for (bool more = true, zeroed = false; more;) {
+            int32_t pi[BATCH];
+            uint32_t pv[BATCH];     // a full register each (16-bit destinations get packed and the loads serialised)
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int64_t j = pos + int64_t(u) * RECOVER_THREADS + tid;
+                if (j < k) {
+                    pi[u] = idx[j];
+                    pv[u] = vals[j];
+                }
+            }
+            if (!zeroed) {
+                for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
+                __syncthreads();
+                zeroed = true;
+            }
+            uint32_t mine = 0;
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int64_t j = pos + int64_t(u) * RECOVER_THREADS + tid;
+                if (j < k && int64_t(pi[u]) < last) {
+                    ++mine;
+                    const uint32_t rel = uint32_t(int64_t(pi[u]) - first);
+                    if (rel < span) {                                 // always, for a sorted index array
+                        uint32_t at = rel;
+                        if (pitch != cin) {
+                            const uint32_t row = rel / uint32_t(cin);
+                            at = row * uint32_t(pitch) + (rel - row * uint32_t(cin));
+                        }
+                        tile[at] = static_cast<uint16_t>(pv[u]);
+                    }
+                }
+            }
+            mine = wave_sum(mine);
+            if ((tid & (WAVE - 1)) == 0) wave_taken[parity][tid / WAVE] = mine;
+            __syncthreads();
+            uint32_t taken = 0;
+#pragma unroll
+            for (int w = 0; w < NWAVES; ++w) taken += wave_taken[parity][w];
+            parity ^= 1u;
+            const int64_t loaded = min<int64_t>(int64_t(BATCH) * RECOVER_THREADS, k - pos);
+            pos += taken;
+            more = int64_t(taken) == loaded && pos < k;               // the batch lay wholly inside the tile: go on
+        }
+        __syncthreads();                                               // scatter complete
+        u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
+        for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
+        __syncthreads();                                               // tile read before the next one is zeroed
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -602,7 +742,10 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
 
     static std::atomic<uint64_t> attr_set{0};
     if (!once_per_device(attr_set, [] {
-            return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       RECOVER_ELEMS_MAX * 2) == hipSuccess &&
+                   hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_stream_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        RECOVER_ELEMS_MAX * 2) == hipSuccess &&
                    hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
@@ -613,9 +756,23 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     trace_mark(stream);
     const int recover_grid = int((ntok_pad + plan.rows_per_wg - 1) / plan.rows_per_wg);
     const size_t recover_lds = size_t(plan.rows_per_wg) * plan.pitch * 2;
-    fc_recover_kernel<<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
-        static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
-        dense);
+    // half-width of the window of pairs a recover workgroup loads around its interpolated positions:
+    // 4 standard deviations of an evenly spread selection (sqrt(k)/2 at worst) plus a little
+    const int64_t margin = 2 * static_cast<int64_t>(__builtin_sqrt(static_cast<double>(p.k))) + 256;
+    const double pairs_per_wg = static_cast<double>(p.k) * plan.rows_per_wg / static_cast<double>(std::max<int64_t>(p.ntok, 1));
+    const bool windowed = pairs_per_wg + 2.0 * margin <= double(RECOVER_WINDOW) * RECOVER_THREADS;
+    if (windowed) {
+        fc_recover_kernel<true><<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
+            static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
+            margin, dense);
+    } else {
+        // several consecutive tiles per workgroup, about four workgroups per compute unit
+        const int tiles_per_wg = std::max(1, (recover_grid + 1023) / 1024);
+        const int grid = (recover_grid + tiles_per_wg - 1) / tiles_per_wg;
+        fc_recover_stream_kernel<<<grid, RECOVER_THREADS, recover_lds, stream>>>(
+            static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
+            tiles_per_wg, dense);
+    }
 
     trace_mark(stream);
     const int total = plan.nb_count * plan.mb_count * plan.splits;
