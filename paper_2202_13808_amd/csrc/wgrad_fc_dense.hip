@@ -229,29 +229,28 @@ fc_recover_stream_kernel(const uint16_t *__restrict__ vals, const int32_t *__res
         const int64_t start = min(t_begin * rows_per_tile, ntok) * cin;
         block_lower_bound2<RECOVER_THREADS>(idx, start, start, 0, k, 0, k, pos, unused);
     }
+    int32_t pi[BATCH];
+    uint32_t pv[BATCH];             // a full register each (16-bit destinations get packed and the loads serialised)
+    auto load_batch = [&]() {       // the pairs at pos, pos + 1, ... : BATCH per thread, all loads in flight together
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int64_t j = pos + int64_t(u) * RECOVER_THREADS + tid;
+            if (j < k) {
+                pi[u] = idx[j];
+                pv[u] = vals[j];
+            }
+        }
+    };
+    load_batch();
     uint32_t parity = 0;
     for (int64_t t = t_begin; t < t_end; ++t) {
         const int64_t r0 = t * rows_per_tile, r1 = min(r0 + rows_per_tile, ntok_pad);
         const int chunks = int(r1 - r0) * (pitch / 8);                // 16-byte units
         const int64_t first = min(r0, ntok) * cin, last = min(r1, ntok) * cin;
         const uint32_t span = uint32_t(last - first);
-        // the first batch's loads are issued before the zero fill
-        for (bool more = true, zeroed = false; more;) {
-            int32_t pi[BATCH];
-            uint32_t pv[BATCH];     // a full register each (16-bit destinations get packed and the loads serialised)
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int64_t j = pos + int64_t(u) * RECOVER_THREADS + tid;
-                if (j < k) {
-                    pi[u] = idx[j];
-                    pv[u] = vals[j];
-                }
-            }
-            if (!zeroed) {
-                for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
-                __syncthreads();
-                zeroed = true;
-            }
+        for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
+        __syncthreads();
+        for (;;) {
             uint32_t mine = 0;
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
@@ -271,16 +270,19 @@ fc_recover_stream_kernel(const uint16_t *__restrict__ vals, const int32_t *__res
             }
             mine = wave_sum(mine);
             if ((tid & (WAVE - 1)) == 0) wave_taken[parity][tid / WAVE] = mine;
-            __syncthreads();
+            __syncthreads();                                           // also: this batch's scatter is complete
             uint32_t taken = 0;
 #pragma unroll
             for (int w = 0; w < NWAVES; ++w) taken += wave_taken[parity][w];
             parity ^= 1u;
             const int64_t loaded = min<int64_t>(int64_t(BATCH) * RECOVER_THREADS, k - pos);
             pos += taken;
-            more = int64_t(taken) == loaded && pos < k;               // the batch lay wholly inside the tile: go on
+            // The next pairs are fetched right away: more of this tile if the batch lay wholly inside
+            // it, else the start of the next tile, whose loads then overlap this tile's write-out.
+            const bool more = int64_t(taken) == loaded && pos < k;
+            if (more || t + 1 < t_end) load_batch();
+            if (!more) break;
         }
-        __syncthreads();                                               // scatter complete
         u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
         for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
         __syncthreads();                                               // tile read before the next one is zeroed
@@ -766,8 +768,8 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
             static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
             margin, dense);
     } else {
-        // several consecutive tiles per workgroup, about four workgroups per compute unit
-        const int tiles_per_wg = std::max(1, (recover_grid + 1023) / 1024);
+        // several consecutive tiles per workgroup, about two workgroups per compute unit (measured best of 1, 2, 4, 8)
+        const int tiles_per_wg = std::max(1, (recover_grid + 511) / 512);
         const int grid = (recover_grid + tiles_per_wg - 1) / tiles_per_wg;
         fc_recover_stream_kernel<<<grid, RECOVER_THREADS, recover_lds, stream>>>(
             static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
