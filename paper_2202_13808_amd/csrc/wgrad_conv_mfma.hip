@@ -125,7 +125,7 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
         }
         for (uint32_t off = lane; off < longest; off += WAVE) {
             int flat[SC];
-            uint16_t val[SC];
+            uint32_t val[SC];       // full registers: 16-bit destinations get packed in pairs and their loads serialised
 #pragma unroll
             for (int q = 0; q < SC; ++q) {
                 const uint32_t at = min(lo[q] + off, uint32_t(k) - 1);   // unconditional, clamped (k > 0)
@@ -143,7 +143,7 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
                 if (ih * uint32_t(W) > rel) --ih;
                 const uint32_t w = rel - ih * uint32_t(W);
                 if (int(ih) >= ih_lo && int(ih) <= ih_hi && w < uint32_t(W))
-                    *reinterpret_cast<uint16_t *>(lds + (int(ih) - (r0 - 1)) * slot_bytes + 16 + (c0 + q) * pitch_c + w * 2) = val[q];
+                    *reinterpret_cast<uint16_t *>(lds + (int(ih) - (r0 - 1)) * slot_bytes + 16 + (c0 + q) * pitch_c + w * 2) = uint16_t(val[q]);
             }
         }
     }
