@@ -109,9 +109,8 @@ __device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64
 // it fall back to the exact search, three dependent rounds of loads, and a second round for the pairs.
 constexpr int RECOVER_WINDOW = 28;                    // window entries per thread, at most
 
-// WINDOWED = false is the same kernel without the guess (kept for tuning; the host uses
-// fc_recover_stream_kernel when the window would be several times the pairs a workgroup needs).
-template <bool WINDOWED>
+// (The host uses fc_recover_stream_kernel instead when the window would be several times the pairs a
+// workgroup needs.)
 __global__ void __launch_bounds__(RECOVER_THREADS)
 fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int64_t ntok,
                   int64_t ntok_pad, int cin, int pitch, int rows_per_wg, int64_t margin, uint16_t *__restrict__ dense)
@@ -141,8 +140,8 @@ fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__
     const int64_t g_lo = static_cast<int64_t>(static_cast<double>(first) * static_cast<double>(k) / static_cast<double>(numel));
     const int64_t g_hi = static_cast<int64_t>(static_cast<double>(last) * static_cast<double>(k) / static_cast<double>(numel));
     const int64_t w_lo = max<int64_t>(g_lo - margin, 0), w_hi = min<int64_t>(g_hi + margin, k);
-    const bool window_fits = WINDOWED && w_hi - w_lo <= int64_t(RECOVER_WINDOW) * RECOVER_THREADS;
-    constexpr int WN = WINDOWED ? RECOVER_WINDOW : 1;
+    const bool window_fits = w_hi - w_lo <= int64_t(RECOVER_WINDOW) * RECOVER_THREADS;
+    constexpr int WN = RECOVER_WINDOW;
     int32_t wi[WN];
     uint32_t wv[WN];        // a full register each: 16-bit destinations get packed in pairs, and the second load
                             // of a pair then waits for the first
@@ -744,7 +743,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
 
     static std::atomic<uint64_t> attr_set{0};
     if (!once_per_device(attr_set, [] {
-            return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel<true>),
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        RECOVER_ELEMS_MAX * 2) == hipSuccess &&
                    hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_stream_kernel),
@@ -764,7 +763,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     const double pairs_per_wg = static_cast<double>(p.k) * plan.rows_per_wg / static_cast<double>(std::max<int64_t>(p.ntok, 1));
     const bool windowed = pairs_per_wg + 2.0 * margin <= double(RECOVER_WINDOW) * RECOVER_THREADS;
     if (windowed) {
-        fc_recover_kernel<true><<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
+        fc_recover_kernel<<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
             static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
             margin, dense);
     } else {

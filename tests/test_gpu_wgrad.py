@@ -80,6 +80,34 @@ def test_fc_bf16_tile_edges(ntok, cin, cout, gamma):
     assert_close(got, ref, TOL["bf16"])
 
 
+@pytest.mark.parametrize("case", [
+    # where the kept pairs sit in the index-sorted arrays is first guessed from an even spread; these inputs are not evenly spread
+    dict(ntok=3000, cin=256, cout=32, gamma=0.9, layout="tail"),      # everything kept lies in the last rows: the guess fails, exact search
+    dict(ntok=3000, cin=256, cout=32, gamma=0.9, layout="head"),      # ... in the first rows
+    dict(ntok=3000, cin=256, cout=32, gamma=0.9, layout="stripes"),   # dense and empty stretches alternate
+    dict(ntok=4000, cin=768, cout=64, gamma=0.3, layout="even"),      # large k: one search per workgroup, forward walk, several batches per tile
+    dict(ntok=4000, cin=768, cout=64, gamma=0.3, layout="tail"),      # large k with empty tiles in front
+    dict(ntok=5003, cin=520, cout=40, gamma=0.5, layout="stripes"),   # large k, padded rows (c_in not a multiple of the tile pitch), ragged last tile
+])
+def test_fc_bf16_uneven_density(case):
+    print("wgrad fc density", case, flush=True)
+    ntok, cin, cout, gamma = case["ntok"], case["cin"], case["cout"], case["gamma"]
+    rng = np.random.default_rng(ntok + cin)
+    xf = rng.standard_normal((ntok, cin), dtype=np.float32)
+    rows = np.arange(ntok)
+    if case["layout"] == "tail":
+        xf[rows < int(0.7 * ntok)] *= 1e-3
+    elif case["layout"] == "head":
+        xf[rows >= int(0.3 * ntok)] *= 1e-3
+    elif case["layout"] == "stripes":
+        xf[(rows // 200) % 2 == 0] *= 1e-3
+    x = f32_to_bf16_bits(xf)
+    dy = gradient((ntok, cout), 0.02, 500 + ntok, "bf16")
+    got, _, _ = gpu_dw(x, dy, gamma, cout)
+    ref = oracle.dw_fc(ref_xhat(x, gamma), oracle.widen(dy))
+    assert_close(got, ref, TOL["bf16"])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("conv", [None, CONV3])
 def test_everything_dropped_gives_zero(dtype, conv):
