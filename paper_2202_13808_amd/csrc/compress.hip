@@ -507,30 +507,35 @@ __device__ inline void resolve_digit_local(const uint32_t *hist, uint32_t &prefi
 }
 
 // ---- sampled first digit (16-bit element types) ---------------------------------------------------
-// The first digit's histogram needs one LDS atomic per element, which is what bounds that pass
-// (an LDS atomic costs a wavefront ~16 cycles whatever it adds).  The bin that holds the k-th largest
-// key can be predicted from a sample instead: one 1 KB block of vectors (a wavefront's load) in
-// eight, picked by a hash of its position.  The prediction is a bracket of up to three adjacent bins
-// around the sample's quantile, wide enough for 8 standard deviations of the sampling error, and it
-// is only a prediction: the pass over all elements that follows counts exactly how many keys lie
-// above the bracket and how many on each key inside it, so a bracket that does not contain the k-th
-// largest key is detected, and the selection then repeats with the exact histogram.  The result is
-// the same in every case; only the time differs.
-constexpr int SAMPLE_BITS = 3;                        // 1 block in 8
-constexpr int64_t SAMPLE_MIN_NUMEL = int64_t(1) << 21; // below this the exact histogram is cheap and the sample thin
+// The first digit's histogram needs one LDS atomic per element, which is what bounds that pass (the
+// LDS atomic unit of a compute unit takes ~16 cycles per wavefront instruction whatever it adds), then
+// a merge with global atomics, a grid barrier, and a read-back of the merged histogram.  The bin that
+// holds the k-th largest key can be predicted from a sample instead, and without any exchange: EVERY
+// workgroup reads the same 512 pieces of 64 bytes (one per equal stretch of the tensor, at a hashed
+// position inside it -- many small pieces, so that values that come in runs, like the tokens of an
+// activation, do not fool it; served by the L2 caches after the first reader), histograms them in its own LDS and
+// derives the same bracket of up to three adjacent bins around the sample's quantile, wide enough for
+// 5 standard deviations of the sampling error.  The bracket is only a prediction: the pass over all
+// elements that follows counts exactly how many keys lie above the bracket and how many on each key
+// inside it, so a bracket that does not contain the k-th largest key is detected, and the selection
+// then runs with the exact histogram.  The result is the same in every case; only the time differs.
+constexpr int SAMPLE_VECTORS_PER_THREAD = 2;          // x 1024 threads x 8 elements = 16 384 sampled elements
+constexpr int64_t SAMPLE_MIN_NUMEL = int64_t(1) << 21; // below this the exact histogram is cheap
 constexpr int BRACKET_MAX_BINS = 3;
-constexpr int SAMPLE_COPIES = 4;                      // the sample histogram is merged into 4 copies (workgroup index modulo 4):
-                                                      // 256 atomics on one hot bin's word take ~2.5 us one after the other
 
-// `first` = index of the first of the 64 consecutive vectors a wavefront handles together
-__device__ inline bool block_sampled(int64_t first)
+constexpr int SAMPLE_PIECE = 4;                       // vectors per sampled piece (64 bytes: four lanes share a cache line)
+
+// First vector of sample piece i of n: stretch i of the tensor, hashed offset inside it (whole pieces).
+__device__ inline int64_t sample_piece(int i, int n, int64_t nvf)
 {
-    return ((static_cast<uint32_t>(first >> 3) * 0x9E3779B1u) >> (32 - SAMPLE_BITS)) == 0u;
+    const int64_t seg = (nvf / SAMPLE_PIECE) / n;                     // pieces per stretch
+    const uint32_t h = (static_cast<uint32_t>(i) + 1u) * 0x9E3779B1u;
+    return (int64_t(i) * seg + static_cast<int64_t>((h >> 8) % static_cast<uint32_t>(seg))) * SAMPLE_PIECE;
 }
 
-// From the merged sample histogram: the bins that hold the sample ranks r - margin and r + margin,
-// r = the sample's share of k.  Returns false (in every thread) if there is no usable bracket (thin
-// or empty sample, a quantile too close to either end, more than BRACKET_MAX_BINS bins).
+// From the sample's histogram (in LDS): the bins that hold the sample ranks r - margin and r + margin,
+// r = the sample's share of k.  Returns false (in every thread) if there is no usable bracket (a
+// quantile too close to either end of the sample, more than BRACKET_MAX_BINS bins).
 template <int NB>
 __device__ inline bool sample_bracket(const uint32_t *hist, uint32_t k, int64_t numel, uint32_t *wave_tot,
                                       uint32_t *bcast /*[3]*/, uint32_t &b_lo, uint32_t &b_hi)
@@ -542,20 +547,16 @@ __device__ inline bool sample_bracket(const uint32_t *hist, uint32_t k, int64_t 
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-        c[i] = 0u;
-        if (hi_bin - i >= 0) {
-#pragma unroll
-            for (int copy = 0; copy < SAMPLE_COPIES; ++copy) c[i] += dev_load(hist + copy * NB + hi_bin - i);
-        }
+        c[i] = (hi_bin - i >= 0) ? hist[hi_bin - i] : 0u;
         mine += c[i];
     }
     uint32_t total;
     const uint32_t above = block_exclusive_scan<SEL_THREADS>(mine, wave_tot, total);
     const float frac = static_cast<float>(k) / static_cast<float>(numel);
     const float r = frac * static_cast<float>(total);
-    const float margin = 8.0f * __builtin_sqrtf(fmaxf(r * (1.0f - frac), 1.0f)) + 16.0f;
+    const float margin = 5.0f * __builtin_sqrtf(fmaxf(r * (1.0f - frac), 1.0f)) + 8.0f;
     const float lo_f = r - margin, hi_f = r + margin;
-    const bool usable = total >= 4096u && lo_f >= 1.0f && hi_f <= static_cast<float>(total) - 1.0f;
+    const bool usable = lo_f >= 1.0f && hi_f <= static_cast<float>(total) - 1.0f;
     if (tid == 0) bcast[2] = usable ? 1u : 0u;
     if (usable) {
         const uint32_t rank[2] = {static_cast<uint32_t>(lo_f), static_cast<uint32_t>(hi_f) + 1u};   // higher bin first
@@ -621,26 +622,34 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
 
     // ---- park the head of the chunk in LDS (each thread only ever reads its own slots) --
     const int nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
+    const bool sampling = !F32 && numel >= SAMPLE_MIN_NUMEL;       // uniform over the grid
+    // The threshold lies in the key range [key_lo, key_lo + nf): predicted from the sample here (16-bit
+    // types, large tensors), else (or if the prediction fails) exactly known after the digit histograms.
+    uint32_t key_lo = 0, nf = LB;
+    bool predicted = false;
     {
         u32x4 q[FUSED_RES];
+        u32x4 sq[SAMPLE_VECTORS_PER_THREAD];
         if (nvf > 0) {
 #pragma unroll
             for (int i = 0; i < FUSED_RES; ++i)     // unconditional, clamped: all loads in flight at once
                 q[i] = xv[min(v0 + int64_t(i) * SEL_THREADS + tid, nvf - 1)];
         }
-        // Workgroup 0 clears what the workgroups exchange through (histograms, barrier counter) while its
+        if (sampling) {
+#pragma unroll
+            for (int j = 0; j < SAMPLE_VECTORS_PER_THREAD; ++j)
+                sq[j] = xv[sample_piece((j * SEL_THREADS + tid) / SAMPLE_PIECE,
+                                        SAMPLE_VECTORS_PER_THREAD * SEL_THREADS / SAMPLE_PIECE, nvf) + tid % SAMPLE_PIECE];
+        }
+        // Workgroup 0 clears what the workgroups exchange through (histograms, barrier counters) while its
         // loads are in flight, then publishes this call's generation number; the others look for it before
         // their first global atomic.  No separate clearing kernel, and a workspace with arbitrary contents
         // is fine: a stale word equals the generation (a per-process random number plus a call count)
         // with probability 2^-64.  Device-scope atomic stores, like everything else that is exchanged.
         if (blockIdx.x == 0) {
             // only the bins this element type uses: bf16 one 2048-bin pass, fp32 two 8192-bin passes (hist1 follows hist0)
-            // (16-bit types: hist0 takes the sampled histogram, hist1 the exact one should the sample mislead)
-            constexpr int CLEAR_WORDS = F32 ? 2 * (1 << MAX_HIST_BITS) : SAMPLE_COPIES * (1 << BITS1);
-            static_assert(SAMPLE_COPIES * (1 << 11) <= (1 << MAX_HIST_BITS), "the sample's copies share the first histogram area");
+            constexpr int CLEAR_WORDS = F32 ? 2 * (1 << MAX_HIST_BITS) : (1 << BITS1);
             for (int i = tid; i < CLEAR_WORDS; i += SEL_THREADS) dev_store(hist0 + i, 0u);
-            if constexpr (!F32)
-                for (int i = tid; i < (1 << BITS1); i += SEL_THREADS) dev_store(hist1 + i, 0u);
             if (tid == 0) {
                 dev_store(&st->barrier, 0u);
                 dev_store(&st->error, 0u);
@@ -654,6 +663,29 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         if (nvf > 0) {
 #pragma unroll
             for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
+        }
+        if (sampling) {
+            constexpr int NB = 1 << BITS1;
+            for (int i = tid; i < NB + WAVE; i += SEL_THREADS) lh[i] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < SAMPLE_VECTORS_PER_THREAD; ++j)
+                for_each_raw(RAW(0), sq[j], [&](uint32_t raw, int) {
+                    const uint32_t dgt = ((raw & MASK) >> SHIFT1) & (NB - 1);
+                    atomicAdd(&lh[dgt ? dgt : NB + lane], 1u);          // exact zeros go to per-lane slots
+                });
+            __syncthreads();
+            if (tid < WAVE) {
+                const uint32_t z = wave_sum(lh[NB + tid]);
+                if (tid == 0) lh[0] += z;
+            }
+            __syncthreads();
+            uint32_t b_lo, b_hi;
+            predicted = sample_bracket<NB>(lh, k, numel, wave_tot, bcast, b_lo, b_hi);
+            if (predicted) {
+                key_lo = b_lo << SHIFT1;                                // a first-digit bin is 2^SHIFT1 = 2^LAST_BITS keys
+                nf = (b_hi - b_lo + 1) << SHIFT1;
+            }
         }
     }
     const int64_t v_stream = v0 + int64_t(nres) * SEL_THREADS;        // first vector that is not parked
@@ -692,36 +724,31 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     __shared__ uint32_t verdict;
     __shared__ uint32_t offs[2];
     __shared__ uint32_t lp[MAX_LAST_BINS + 1];
-    // visits only the sampled 1 KB blocks of the chunk (the ragged tail of the tensor is left out)
-    auto for_sample = [&](auto f) {
-        for (int i = 0; i < nres; ++i) {
-            const int64_t v = v0 + int64_t(i) * SEL_THREADS + tid;
-            if (block_sampled(v - lane) && v < v1)
-                for_each_raw(RAW(0), res[i * SEL_THREADS + tid], [&](uint32_t raw, int) { f(raw); });
+    // Waits until workgroup 0 has published this call's generation number: the exchange area is then
+    // cleared.  False (in every thread) if that never happens.
+    bool ready_seen = false;
+    auto wait_ready = [&]() -> bool {
+        if (ready_seen) return true;
+        if (tid == 0) {
+            uint32_t spins = 0, ok = 1;
+            while (dev_load64(&st->ready) != gen) {
+                if (++spins > SPIN_LIMIT) {      // workgroup 0 never ran: not this workgroup's patience setting
+                    ok = 0;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            bcast[3] = ok;
         }
-        // streamed rows: a wavefront first looks up its next (up to) four sampled blocks -- the hash is
-        // uniform over the wavefront, so this is scalar work -- and then has their loads in flight together
-        const int64_t wave_first = v_stream + (tid - lane);
-        for (int64_t vb = wave_first; vb < v1;) {
-            int64_t pick[SEL_UNROLL];
-            int n = 0;
-            for (; vb < v1 && n < SEL_UNROLL; vb += SEL_THREADS)
-                if (block_sampled(vb)) pick[n++] = vb;
-            u32x4 q[SEL_UNROLL];
-#pragma unroll
-            for (int u = 0; u < SEL_UNROLL; ++u)
-                if (u < n && pick[u] + lane < v1) q[u] = xv[pick[u] + lane];
-#pragma unroll
-            for (int u = 0; u < SEL_UNROLL; ++u)
-                if (u < n && pick[u] + lane < v1) for_each_raw(RAW(0), q[u], [&](uint32_t raw, int) { f(raw); });
-        }
+        __syncthreads();
+        ready_seen = bcast[3] != 0;
+        return ready_seen;
     };
-    // One digit's histogram of the chunk (of its sampled blocks only if SAMPLED), merged into ghist; ends
-    // with a grid barrier, after which ghist holds the whole tensor's (sample's) histogram.
-    auto hist_pass = [&](auto shift_c, auto bits_c, auto first_c, auto sampled_c, bool wait_ready,
-                         uint32_t *ghist) -> SelOutcome {
+    // One digit's histogram of the chunk, merged into ghist; ends with a grid barrier, after which
+    // ghist holds the whole tensor's histogram.
+    auto hist_pass = [&](auto shift_c, auto bits_c, auto first_c, uint32_t *ghist) -> SelOutcome {
         constexpr int SHIFT = decltype(shift_c)::value, BITS = decltype(bits_c)::value;
-        constexpr bool FIRST = decltype(first_c)::value, SAMPLED = decltype(sampled_c)::value;
+        constexpr bool FIRST = decltype(first_c)::value;
         constexpr int NB = 1 << BITS;
         for (int i = tid; i < NB + 2 * WAVE; i += SEL_THREADS) lh[i] = 0;
         __syncthreads();
@@ -733,33 +760,17 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             if (!FIRST) a = ((key >> (SHIFT + BITS)) == prefix) ? a : dslot;
             atomicAdd(&lh[a], 1u);
         };
-        if constexpr (SAMPLED) for_sample(add);
-        else for_chunk(add);
+        for_chunk(add);
         __syncthreads();
         if (tid < WAVE) {
             const uint32_t z = wave_sum(lh[NB + tid]);
             if (tid == 0) lh[0] += z;
         }
         __syncthreads();
-        if (wait_ready) {                       // the exchange area must have been cleared for this call
-            if (tid == 0) {
-                uint32_t spins = 0, ok = 1;
-                while (dev_load64(&st->ready) != gen) {
-                    if (++spins > SPIN_LIMIT) {  // workgroup 0 never ran: not this workgroup's patience setting
-                        ok = 0;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(1);
-                }
-                bcast[3] = ok;
-            }
-            __syncthreads();
-            if (bcast[3] == 0) return SEL_NEVER_READY;
-        }
-        uint32_t *gcopy = SAMPLED ? ghist + (blockIdx.x % SAMPLE_COPIES) * NB : ghist;
+        if (!wait_ready()) return SEL_NEVER_READY;      // the exchange area must have been cleared for this call
         for (int i = tid; i < NB; i += SEL_THREADS) {
             const uint32_t c = lh[i];
-            if (c) atomicAdd(&gcopy[i], c);
+            if (c) atomicAdd(&ghist[i], c);
         }
         STAMP();
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
@@ -767,39 +778,21 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         return SEL_DONE;
     };
 
-    // The threshold lies in the key range [key_lo, key_lo + nf): exactly known after the digit
-    // histograms, or predicted from the sample (16-bit types, large tensors).
-    uint32_t key_lo = 0, nf = LB;
-    bool predicted = false, ready_seen = false, missed = false;
-    if constexpr (!F32) {
-        if (numel >= SAMPLE_MIN_NUMEL) {
-            if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{},
-                                               std::true_type{}, std::true_type{}, true, hist0))
-                return o;
-            ready_seen = true;
-            uint32_t b_lo, b_hi;
-            predicted = sample_bracket<(1 << BITS1)>(hist0, k, numel, wave_tot, bcast, b_lo, b_hi);
-            key_lo = b_lo << SHIFT1;                        // a first-digit bin is 2^SHIFT1 = 2^LAST_BITS keys
-            nf = (b_hi - b_lo + 1) << SHIFT1;
-            STAMP();
-        }
-    }
-
+    bool missed = false;
+    if (sampling) STAMP();
     uint32_t t = 0, m = 0;
     for (;;) {
         if (!predicted) {
-            // exact digits (after a sampled pass its histogram area is used up: the exact one goes to hist1)
+            // exact digits
             prefix = 0;
             k_rem = k;
-            uint32_t *h_first = ready_seen ? hist1 : hist0;
             if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT1>{}, std::integral_constant<int, BITS1>{},
-                                               std::true_type{}, std::false_type{}, !ready_seen, h_first))
+                                               std::true_type{}, hist0))
                 return o;
-            ready_seen = true;
-            resolve_digit_local<(1 << BITS1), BITS1>(h_first, prefix, k_rem, wave_tot, bcast);
+            resolve_digit_local<(1 << BITS1), BITS1>(hist0, prefix, k_rem, wave_tot, bcast);
             if constexpr (F32) {
                 if (const SelOutcome o = hist_pass(std::integral_constant<int, SHIFT2>{}, std::integral_constant<int, BITS2>{},
-                                                   std::false_type{}, std::false_type{}, false, hist1))
+                                                   std::false_type{}, hist1))
                     return o;
                 resolve_digit_local<(1 << BITS2), BITS2>(hist1, prefix, k_rem, wave_tot, bcast);
             }
@@ -827,6 +820,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             if (lane == 0 && above) atomicAdd(&lh[nf], above);
         }
         __syncthreads();
+        if (!wait_ready()) return SEL_NEVER_READY;      // (already seen, unless the range was predicted)
         if (tid <= static_cast<int>(nf)) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
         STAMP();
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;

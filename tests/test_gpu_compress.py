@@ -157,22 +157,28 @@ def _run_with_path(x, gamma):
 
 
 def test_sampled_bracket_paths():
-    """Large 16-bit tensors predict the threshold's bin from a sample of 1 KB blocks (1 in 8, by a hash of the
-    block's position) and confirm it with exact counts.  All three outcomes must give the oracle's bytes:
-    confirmed, unusable (quantile too close to an end), and missed -- forced here by giving exactly the blocks
-    the kernel samples a different scale from the rest, which no confidence margin can cover."""
-    numel = 1 << 22                                      # chunks are then whole multiples of 64 vectors: blocks align globally
+    """Large 16-bit tensors predict the threshold's bin from a sample every workgroup reads for itself (512 pieces
+    of 32 elements, one per equal stretch of the tensor at a hashed position inside it) and confirm it with exact
+    counts.  All three outcomes must give the oracle's bytes: confirmed, unusable (quantile too close to an
+    end), and missed -- forced here by giving exactly the sampled pieces a different scale from the rest, which
+    no confidence margin can cover."""
+    numel = 1 << 22
     rng = np.random.default_rng(99)
     base = rng.standard_normal(numel, dtype=np.float32)
     assert _run_with_path(f32_to_bf16_bits(base), 0.9) == 1
     assert _run_with_path(f32_to_bf16_bits(base), 0.99999) == 0          # k = 41: no usable margin
     assert _run_with_path(base, 0.9) == 0                                 # fp32 always builds the exact histograms
-    block = np.arange(numel // 512, dtype=np.uint64)                      # 64 vectors of 8 elements
-    sampled = (((block * 8) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)) >> np.uint64(29) == 0
-    assert 0.08 < sampled.mean() < 0.17
-    scale = np.where(np.repeat(sampled, 512), np.float32(0.01), np.float32(1.0))
+    nvf = numel // 8
+    seg = (nvf // 4) // 512                                               # 512 pieces of 4 vectors
+    sampled = np.zeros(nvf, dtype=bool)
+    for i in range(512):
+        h = ((i + 1) * 0x9E3779B1) & 0xFFFFFFFF
+        first = (i * seg + (h >> 8) % seg) * 4
+        sampled[first:first + 4] = True
+    assert sampled.sum() == 2048
+    scale = np.where(np.repeat(sampled, 8), np.float32(0.01), np.float32(1.0))
     assert _run_with_path(f32_to_bf16_bits(base * scale), 0.9) == 2
-    scale = np.where(np.repeat(sampled, 512), np.float32(100.0), np.float32(1.0))
+    scale = np.where(np.repeat(sampled, 8), np.float32(100.0), np.float32(1.0))
     assert _run_with_path(f32_to_bf16_bits(base * scale), 0.9) == 2
     # a tensor of one value: every bin of the bracket but one is empty, the ties decide everything
     assert _run_with_path(f32_to_bf16_bits(np.full(numel, 0.5, dtype=np.float32)), 0.9) in (0, 1)
