@@ -689,11 +689,11 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         }
     }
     const int64_t v_stream = v0 + int64_t(nres) * SEL_THREADS;        // first vector that is not parked
-    // visits every element of the chunk: f(raw bits)
-    auto for_chunk = [&](auto f) {
+    // visits the chunk: fv(vector) for every full 16-byte vector, ft(raw bits) for the ragged tail's elements
+    auto for_chunk_v = [&](auto fv, auto ft) {
         for (int i = 0; i < nres; ++i) {
             const int64_t v = v0 + int64_t(i) * SEL_THREADS + tid;
-            if (v < v1) for_each_raw(RAW(0), res[i * SEL_THREADS + tid], [&](uint32_t raw, int) { f(raw); });
+            if (v < v1) fv(res[i * SEL_THREADS + tid]);
         }
         int64_t vb = v_stream;
         for (; vb + SEL_THREADS * SEL_UNROLL <= v1; vb += SEL_THREADS * SEL_UNROLL) {
@@ -701,12 +701,15 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
 #pragma unroll
             for (int u = 0; u < SEL_UNROLL; ++u) q[u] = xv[vb + u * SEL_THREADS + tid];
 #pragma unroll
-            for (int u = 0; u < SEL_UNROLL; ++u) for_each_raw(RAW(0), q[u], [&](uint32_t raw, int) { f(raw); });
+            for (int u = 0; u < SEL_UNROLL; ++u) fv(q[u]);
         }
-        for (int64_t v = vb + tid; v < v1; v += SEL_THREADS)
-            for_each_raw(RAW(0), xv[v], [&](uint32_t raw, int) { f(raw); });
+        for (int64_t v = vb + tid; v < v1; v += SEL_THREADS) fv(xv[v]);
         if (last_chunk && tid == 0)
-            for (int64_t i = nvf * VEC; i < numel; ++i) f(x[i]);
+            for (int64_t i = nvf * VEC; i < numel; ++i) ft(x[i]);
+    };
+    // visits every element of the chunk: f(raw bits)
+    auto for_chunk = [&](auto f) {
+        for_chunk_v([&](const u32x4 &q) { for_each_raw(RAW(0), q, [&](uint32_t raw, int) { f(raw); }); }, f);
     };
 
     uint32_t prefix = 0, k_rem = k;
@@ -810,12 +813,40 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             // atomic costs its issue cycles whatever the number of active lanes).
             uint32_t above = 0;
             const uint32_t key_end = key_lo + nf;
-            for_chunk([&](uint32_t raw) {
+            auto one = [&](uint32_t raw) {
                 const uint32_t key = raw & MASK;
                 above += (key >= key_end) ? 1u : 0u;
                 const uint32_t rel = key - key_lo;             // wraps to a huge value below the range
                 if (rel < nf) atomicAdd(&lh[rel], 1u);
-            });
+            };
+            if constexpr (F32) {
+                for_chunk(one);
+            } else {
+                // Two 15-bit keys per 32-bit word are classified together: adding 0x8000 - E to a key sets
+                // its bit 15 iff key >= E, and neither half can carry into the other (E <= 0x8000).
+                const uint32_t c_end = (0x8000u - key_end) * 0x00010001u;
+                const uint32_t c_lo = (0x8000u - key_lo) * 0x00010001u;
+                for_chunk_v(
+                    [&](const u32x4 &q) {
+                        uint32_t kw[4], in_range[4], any = 0;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            kw[w] = q[w] & 0x7FFF7FFFu;
+                            const uint32_t ge_end = kw[w] + c_end, ge_lo = kw[w] + c_lo;
+                            above += __builtin_popcount(ge_end & 0x80008000u);
+                            in_range[w] = (ge_lo ^ ge_end) & 0x80008000u;     // >= key_lo and not >= key_end
+                            any |= in_range[w];
+                        }
+                        if (any) {
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) {
+                                if (in_range[w] & 0x8000u) atomicAdd(&lh[(kw[w] & 0xFFFFu) - key_lo], 1u);
+                                if (in_range[w] & 0x80000000u) atomicAdd(&lh[(kw[w] >> 16) - key_lo], 1u);
+                            }
+                        }
+                    },
+                    one);
+            }
             above = wave_sum(above);
             if (lane == 0 && above) atomicAdd(&lh[nf], above);
         }
