@@ -620,6 +620,14 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
     const int64_t v1 = min(v0 + vpc, nvf);
 
+#ifdef DROPIT_TUNING
+    int stamp_i = 0;
+#define STAMP() do { if (tid == 0 && blockIdx.x == gridDim.x / 2) reinterpret_cast<unsigned long long *>(st->pad + 6)[stamp_i] = wall_clock64(); ++stamp_i; } while (0)
+#else
+#define STAMP() do { } while (0)
+#endif
+    STAMP();
+
     // ---- park the head of the chunk in LDS (each thread only ever reads its own slots) --
     const int nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
     const bool sampling = !F32 && numel >= SAMPLE_MIN_NUMEL;       // uniform over the grid
@@ -664,6 +672,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
 #pragma unroll
             for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
         }
+        STAMP();
         if (sampling) {
             constexpr int NB = 1 << BITS1;
             for (int i = tid; i < NB + WAVE; i += SEL_THREADS) lh[i] = 0;
@@ -715,13 +724,6 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     uint32_t prefix = 0, k_rem = k;
     uint32_t barriers = 0;
     uint32_t *xbar = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(st) + SelWorkspace::xbar_off);
-#ifdef DROPIT_TUNING
-    int stamp_i = 0;
-#define STAMP() do { if (tid == 0 && blockIdx.x == gridDim.x / 2) reinterpret_cast<unsigned long long *>(st->pad + 6)[stamp_i] = wall_clock64(); ++stamp_i; } while (0)
-#else
-#define STAMP() do { } while (0)
-#endif
-    STAMP();
 
     // ---- digit histograms ---------------------------------------------------------
     __shared__ uint32_t verdict;
