@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # by what the same counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0); see
 # profiles/fc_dense_select_fused_vitb_fc1_hbm_traffic.txt.  None for workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("vitb_fc1", "dw"): int((59045.4 * 2.0 + 64512.0) * 1024),       # fc_dense_kernel: 120.9 MB read + 66.1 MB written
-    ("vitb_fc1", "hist"): int((12641.5 * 2.0 + 6004.0) * 1024),      # select_fused_kernel: 25.9 MB read + 6.1 MB written
+    ("vitb_fc1", "dw"): int((59045.5 * 2.0 + 64512.0) * 1024),       # fc_dense_kernel: 120.9 MB read + 66.1 MB written
+    ("vitb_fc1", "hist"): int((12767.9 * 2.0 + 5976.5) * 1024),      # select_fused_kernel: 26.1 MB read + 6.1 MB written
 }
 
 
