@@ -761,7 +761,10 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     // 4 standard deviations of an evenly spread selection (sqrt(k)/2 at worst) plus a little
     const int64_t margin = 2 * static_cast<int64_t>(__builtin_sqrt(static_cast<double>(p.k))) + 256;
     const double pairs_per_wg = static_cast<double>(p.k) * plan.rows_per_wg / static_cast<double>(std::max<int64_t>(p.ntok, 1));
-    const bool windowed = pairs_per_wg + 2.0 * margin <= double(RECOVER_WINDOW) * RECOVER_THREADS;
+    bool windowed = pairs_per_wg + 2.0 * margin <= double(RECOVER_WINDOW) * RECOVER_THREADS;
+#ifdef DROPIT_TUNING
+    if (getenv("DROPIT_RECOVER_STREAM")) windowed = false;
+#endif
     if (windowed) {
         fc_recover_kernel<<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
             static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,
