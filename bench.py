@@ -270,7 +270,7 @@ def main():
             "avg_kernel_ms": main_ms,
         },
         "roofline_compress": {
-            "kernel": "select_fused_kernel (histograms + count + ordered compaction, x read once)",
+            "kernel": "select_fused_kernel (key range from a sample or digit histograms, exact count, ordered compaction)",
             "bound": "hbm",
             "achieved": hist_gbps,
             "peak": HBM_PEAK_GBPS,

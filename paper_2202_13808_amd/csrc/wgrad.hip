@@ -43,8 +43,11 @@ __global__ void __launch_bounds__(256) scatter_kernel(const RAW *__restrict__ va
 
 // ---- FC: 64x64 output tile per workgroup, 4x4 per thread, fp32 FMA --------
 constexpr int FT = 64;      // tile edge
-constexpr int FK = 16;      // tokens per step
+constexpr int FK = 64;      // tokens per step
 
+// The next step's operands are fetched into registers while the current step multiplies, so a short
+// problem (a few steps) does not pay one memory round trip per step.  Every output element still adds
+// its terms in ascending token order: the result does not depend on FK.
 template <typename RAW>
 __global__ void __launch_bounds__(256)
 fc_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int64_t ntok, int cin, int cout,
@@ -52,19 +55,32 @@ fc_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int64_t 
 {
     __shared__ float sA[FK][FT + 4];   // dY tile  [token][j]
     __shared__ float sB[FK][FT + 4];   // x^ tile  [token][c]
+    constexpr int PER = FK * FT / 256; // elements of each tile a thread moves
     const int tid = threadIdx.x;
     const int j0 = blockIdx.y * FT, c0 = blockIdx.x * FT;
     const int tj = (tid / 16) * 4, tc = (tid % 16) * 4;
     float acc[4][4] = {};
-    for (int64_t n0 = 0; n0 < ntok; n0 += FK) {
-        for (int e = tid; e < FK * FT; e += 256) {
-            const int r = e / FT, q = e % FT;
+    float na[PER], nb[PER];
+    auto fetch = [&](int64_t n0) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid + u * 256, r = e / FT, q = e % FT;
             const int64_t n = n0 + r;
-            sA[r][q] = (n < ntok && j0 + q < cout) ? to_f32(dY[n * cout + j0 + q]) : 0.f;
-            sB[r][q] = (n < ntok && c0 + q < cin) ? to_f32(xhat[n * cin + c0 + q]) : 0.f;
+            na[u] = (n < ntok && j0 + q < cout) ? to_f32(dY[n * cout + j0 + q]) : 0.f;
+            nb[u] = (n < ntok && c0 + q < cin) ? to_f32(xhat[n * cin + c0 + q]) : 0.f;
+        }
+    };
+    fetch(0);
+    for (int64_t n0 = 0; n0 < ntok; n0 += FK) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid + u * 256, r = e / FT, q = e % FT;
+            sA[r][q] = na[u];
+            sB[r][q] = nb[u];
         }
         __syncthreads();
-#pragma unroll
+        if (n0 + FK < ntok) fetch(n0 + FK);
+#pragma unroll 16
         for (int r = 0; r < FK; ++r) {
             float a[4], b[4];
 #pragma unroll
