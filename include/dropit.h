@@ -141,7 +141,7 @@ size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, drop
  *     OH = (H + 2*pad_h - dil_h*(kh-1) - 1)/stride_h + 1 (OW alike), type dt
  *     dW  [c_out, C, kh, kw] fp32:
  *     dW[j][c][u][v] = sum_{n,oy,ox} dY[n][j][oy][ox] * R(a^)[n][c][oy*sh-ph+u*dh][ox*sw-pw+v*dw]
- *     bf16 with kh = kw = 3, stride 1, pad 1, dilation 1 (and W a multiple of 8, W <= 120)
+ *     bf16 with kh = kw = 3, stride 1, pad 1, dilation 1 (and W <= 120)
  *     runs on the matrix cores; every other geometry (kernel extents up to 1024,
  *     stride / pad / dilation up to 65535) takes an exact but slow fp32 kernel.
  *     DROPIT_EINVAL if the window does not fit the padded input.

@@ -19,7 +19,7 @@
 //             ox+v-1: one aligned 16-byte read plus its two neighbouring dwords,
 //             funnel-shifted by one element in registers for v = 0 and v = 2.
 // One K step = 8 consecutive ox of TWO adjacent output rows (the two K-halves of the
-// MFMA), so any even or odd H works and W only has to be a multiple of 8.
+// MFMA), so any even or odd H works; a W that is not a multiple of 8 goes through a zero-padded copy of dY.
 // Each workgroup keeps all 9 x 64 x 64 partial sums in registers and writes them
 // once; a second kernel adds the per-workgroup partials in fixed order, so dW is
 // bit-reproducible.
@@ -57,9 +57,9 @@ template <int AG>
 __global__ void __launch_bounds__(CT)
 conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ vals,
                     const int32_t *__restrict__ idx, int64_t k, const uint32_t *__restrict__ row_ptr, int C, int H,
-                    int W, int J, int RB, int bands,
-                    int cb_count, int jb_count, int pitch_c /*bytes per (row, channel)*/,
-                    float *__restrict__ partial /*[N*bands][9][J][C]*/)
+                    int W, int Wp /*row width of dY as passed: W rounded up to a multiple of 8*/, int J, int RB, int bands,
+                    int cb_count, int jb_count, int pitch_c /*bytes per (row, channel)*/, int N, int imgs_per_wg,
+                    float *__restrict__ partial /*[image groups * bands][9][J][C]*/)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,7 +69,8 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     const int cb = v % cb_count; v /= cb_count;
     const int jb = v % jb_count; v /= jb_count;
     const int band = v % bands;
-    const int n = v / bands;
+    const int ng = v / bands;                          // image group: images ng * imgs_per_wg ...
+    const int n_begin = ng * imgs_per_wg, n_end = min(n_begin + imgs_per_wg, N);
     const int r0 = band * RB;
     const int rows = min(RB, H - r0);                  // output rows of this band
     const int slots = rows + 2;                        // input rows r0-1 .. r0+rows
@@ -79,6 +80,15 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     unsigned long long pc[5];
     pc[0] = wall_clock64();
 #endif
+    // accumulators live across the images of the group
+    f32x16 acc[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+    for (int n = n_begin; n < n_end; ++n) {
+    if (n != n_begin) __syncthreads();             // the previous image's rows have been read by every wavefront
     // ---- recover R(a^) for this band into LDS: zero fill, then scatter ------------
     // Pairs of this band: for each of the 64 channels one contiguous run [first, last) of the arrays
     // (input rows ih_lo .. ih_hi of that channel).  The runs are laid end to end (prefix sums of
@@ -153,16 +163,10 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     pc[2] = wall_clock64();
 #endif
     // ---- multiply ---------------------------------------------------------------
-    f32x16 acc[9];
-#pragma unroll
-    for (int i = 0; i < 9; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-
     const int kg = lane >> 5;                          // K-half: which row of the pair
     const int j = jb * BJ + wj * 32 + (lane & 31);
     const int cl_b = wc * 32 + (lane & 31);            // this lane's input channel inside the block
-    const int groups = W / 8;
+    const int groups = Wp / 8;
     const int jc = min(j, J - 1);
     // The dY fragments come straight from global memory; they are fetched one chunk (a row pair x
     // AG groups of 8 columns) ahead of the chunk being multiplied, all loads of a chunk in flight
@@ -176,7 +180,7 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
         const int oy_l = pr + kg;                      // row inside the band
         const bool a_ok = (j < J) && (oy_l < rows);
         const int oy = r0 + min(oy_l, rows - 1);
-        const uint16_t *arow = dY + ((int64_t(n) * J + jc) * H + oy) * W;
+        const uint16_t *arow = dY + ((int64_t(n) * J + jc) * H + oy) * Wp;
 #pragma unroll
         for (int g = 0; g < AG; ++g) {
             const u32x4 v4 = *reinterpret_cast<const u32x4 *>(arow + min(t0 + g, groups - 1) * 8);   // clamped, unconditional
@@ -219,6 +223,8 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
         for (int g = 0; g < AG; ++g) cur[g] = nxt[g];
     }
 
+    }   // images of the group
+
 #ifdef DROPIT_PHASE_CLOCK
     pc[3] = wall_clock64();
 #endif
@@ -235,7 +241,7 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     __syncthreads();
     if (wk == 0) {
         // partial sums: [workgroup][tap][j][c]
-        float *dst = partial + (int64_t(n) * bands + band) * 9 * int64_t(J) * C;
+        float *dst = partial + (int64_t(ng) * bands + band) * 9 * int64_t(J) * C;
 #pragma unroll
         for (int s = 0; s < 9; ++s)
 #pragma unroll
@@ -252,6 +258,26 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
         for (int i = 0; i < 4; ++i) o[i] = float(pc[i + 1] - pc[i]);
     }
 #endif
+}
+
+// Rows of a width that is not a multiple of 8 (28, 14, 7 in the later stages of a ResNet): dY is copied
+// once into rows of Wp = W rounded up, zero beyond W, so that the kernel's 16-byte fragment loads stay
+// aligned; the added columns multiply zeros (the LDS rows of the recovered input are zero there too).
+// One thread per group of 8 output columns.
+__global__ void __launch_bounds__(256)
+conv_pad_rows_kernel(const uint16_t *__restrict__ dY, int64_t rows, int W, int Wp, uint16_t *__restrict__ out)
+{
+    const int gpr = Wp / 8;                             // groups per row
+    const int64_t total = rows * gpr;
+    for (int64_t g = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; g < total; g += int64_t(gridDim.x) * blockDim.x) {
+        const int64_t r = g / gpr;
+        const int w0 = int(g - r * gpr) * 8;
+        uint32_t e[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e[i] = (w0 + i < W) ? uint32_t(dY[r * W + w0 + i]) : 0u;
+        *reinterpret_cast<u32x4 *>(out + r * Wp + w0) =
+            u32x4{e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16};
+    }
 }
 
 // dW[j][c][tap] = sum over the GEMM workgroups' partials partial[p][tap][j][c], in a fixed order:
@@ -289,10 +315,10 @@ conv_reduce_kernel(const float *__restrict__ partial, int parts, int J, int C, f
 
 bool conv_mfma_supported(const ConvProblem &p)
 {
-    if (p.W % 8 != 0 || p.W > 120 || p.H < 1) return false;
+    if (p.W < 2 || p.W > 120 || p.H < 1) return false;     // (the scatter divides by W with a 32-bit reciprocal: W >= 2)
     const ConvPlan plan = conv_mfma_plan(p);
     return plan.lds_bytes <= 150 * 1024 && p.N * p.C * p.H < INT32_MAX &&
-           int64_t(p.N) * plan.bands * plan.cb_count * plan.jb_count <= INT32_MAX;
+           int64_t(plan.img_groups) * plan.bands * plan.cb_count * plan.jb_count <= INT32_MAX;
 }
 
 ConvPlan conv_mfma_plan(const ConvProblem &p)
@@ -300,7 +326,8 @@ ConvPlan conv_mfma_plan(const ConvProblem &p)
     ConvPlan plan;
     plan.cb_count = int((p.C + BC - 1) / BC);
     plan.jb_count = int((p.J + BJ - 1) / BJ);
-    plan.pitch_c = int(p.W + 16) * 2;
+    plan.wp = int((p.W + 7) / 8 * 8);
+    plan.pitch_c = (plan.wp + 16) * 2;
     if ((plan.pitch_c / 16) % 2 == 0) plan.pitch_c += 16;            // odd multiple of 16: conflict-free row reads
     // bands: enough workgroups for the 256 compute units, bounded by the LDS a band's rows need
     const int64_t per_band_wgs = p.N * plan.cb_count * plan.jb_count;
@@ -316,9 +343,14 @@ ConvPlan conv_mfma_plan(const ConvProblem &p)
     plan.bands = int((p.H + rb - 1) / rb);
     // the rows of a band, and afterwards the parked accumulators of one K-group (4 x 9 x 16 x 64 floats)
     plan.lds_bytes = std::max(size_t(rb + 2) * BC * plan.pitch_c, size_t(4) * 9 * 16 * WAVE * 4);
-    plan.packed_bytes = 0;
     plan.rowptr_bytes = round_up(size_t(p.N * p.C * p.H + 1) * 4, 256);
-    plan.partial_bytes = round_up(size_t(p.N) * plan.bands * 9 * p.J * p.C * 4, 256);
+    // A workgroup accumulates over several images when there are more (image, band, block) units than
+    // compute units: the partial sums it writes are a whole 9 x 64 x 64 tile however much it summed.
+    const int64_t units = p.N * plan.bands * plan.cb_count * plan.jb_count;
+    plan.imgs_per_wg = int(std::min<int64_t>(std::max<int64_t>(units / 256, 1), p.N));
+    plan.img_groups = int((p.N + plan.imgs_per_wg - 1) / plan.imgs_per_wg);
+    plan.partial_bytes = round_up(size_t(plan.img_groups) * plan.bands * 9 * p.J * p.C * 4, 256);
+    plan.dypad_bytes = plan.wp != p.W ? round_up(size_t(p.N) * p.J * p.H * plan.wp * 2, 256) : 0;
     return plan;
 }
 
@@ -333,8 +365,17 @@ dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const vo
     const int prep_blocks = int(std::min<int64_t>((p.k + 1 + 255) / 256, 4096));
     conv_rowptr_kernel<<<prep_blocks, 256, 0, stream>>>(idx, p.k, int(p.W), R, row_ptr);
     trace_mark(stream);
+    const uint16_t *dy_rows = static_cast<const uint16_t *>(dY);
+    if (plan.wp != p.W) {
+        uint16_t *padded = reinterpret_cast<uint16_t *>(ws + plan.rowptr_bytes + plan.partial_bytes);
+        const int64_t rows = p.N * p.J * p.H;
+        const int blocks = int(std::min<int64_t>((rows * (plan.wp / 8) + 255) / 256, 8192));
+        conv_pad_rows_kernel<<<blocks, 256, 0, stream>>>(dy_rows, rows, int(p.W), plan.wp, padded);
+        dy_rows = padded;
+        trace_mark(stream);
+    }
     // groups of 8 columns per row: take the chunk width (8, 7, 6 or 5) that pads the row least
-    const int groups = int(p.W / 8);
+    const int groups = plan.wp / 8;
     int ag = 8, padded = (groups + 7) / 8 * 8;
     for (int cand = 7; cand >= 5; --cand) {
         const int pc = (groups + cand - 1) / cand * cand;
@@ -343,14 +384,15 @@ dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const vo
             padded = pc;
         }
     }
-    const int grid = int(p.N) * plan.bands * plan.jb_count * plan.cb_count;
+    const int grid = plan.img_groups * plan.bands * plan.jb_count * plan.cb_count;
     auto launch = [&](auto kernel) -> dropit_status {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 150 * 1024) != hipSuccess)
             return DROPIT_EHIP;
-        kernel<<<grid, CT, plan.lds_bytes, stream>>>(static_cast<const uint16_t *>(dY), static_cast<const uint16_t *>(vals),
-                                                     idx, p.k, row_ptr, int(p.C), int(p.H), int(p.W), int(p.J), plan.rb,
-                                                     plan.bands, plan.cb_count, plan.jb_count, plan.pitch_c, partial);
+        kernel<<<grid, CT, plan.lds_bytes, stream>>>(dy_rows, static_cast<const uint16_t *>(vals),
+                                                     idx, p.k, row_ptr, int(p.C), int(p.H), int(p.W), plan.wp, int(p.J), plan.rb,
+                                                     plan.bands, plan.cb_count, plan.jb_count, plan.pitch_c, int(p.N),
+                                                     plan.imgs_per_wg, partial);
         return DROPIT_OK;
     };
     dropit_status st = DROPIT_OK;
@@ -363,7 +405,7 @@ dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const vo
     if (st != DROPIT_OK) return st;
     trace_mark(stream);
     const int64_t total = p.J * p.C * 9;
-    conv_reduce_kernel<<<int((total + 63) / 64), 64 * RED_GROUPS, 0, stream>>>(partial, int(p.N) * plan.bands, int(p.J), int(p.C), dW);
+    conv_reduce_kernel<<<int((total + 63) / 64), 64 * RED_GROUPS, 0, stream>>>(partial, plan.img_groups * plan.bands, int(p.J), int(p.C), dW);
     trace_mark(stream);
     return launch_status();
 }

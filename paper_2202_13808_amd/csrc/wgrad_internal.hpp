@@ -29,8 +29,11 @@ struct ConvProblem {
 
 struct ConvPlan {
     int cb_count, jb_count, bands, rb, pitch_c;
-    size_t lds_bytes, packed_bytes, rowptr_bytes, partial_bytes;
-    size_t total() const { return packed_bytes + rowptr_bytes + partial_bytes; }
+    int wp;                                    // row width the kernel works with: W rounded up to whole groups of 8
+    int imgs_per_wg, img_groups;               // a workgroup accumulates over this many images; ceil(N / imgs_per_wg) groups
+    size_t lds_bytes, rowptr_bytes, partial_bytes;
+    size_t dypad_bytes;                        // zero-padded copy of dY when wp != W, else 0
+    size_t total() const { return rowptr_bytes + partial_bytes + dypad_bytes; }
 };
 
 // bf16 3x3/s1/p1 convolution weight gradient on the matrix cores (wgrad_conv_mfma.hip)

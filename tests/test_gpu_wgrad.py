@@ -166,6 +166,24 @@ def test_conv3x3_shapes(dtype, N, C, H, W, J):
     assert_close(got, ref, TOL[dtype])
 
 
+@pytest.mark.parametrize("N,C,H,W,J", [
+    (4, 64, 28, 28, 64),      # ResNet stage 2 plane: rows of 28 go through the zero-padded copy of dY (rows of 32)
+    (6, 128, 14, 14, 96),     # stage 3 plane, two channel blocks, a ragged filter block
+    (32, 256, 7, 7, 256),     # stage 4 plane: more (image, block) units than compute units -> several images per workgroup
+    (40, 192, 7, 7, 128),     # ... with a ragged last image group
+    (3, 16, 9, 1, 8),         # a single column: the exact fp32 kernel
+    (3, 16, 9, 2, 8),         # two columns: the narrowest plane of the matrix-core path
+    (2, 24, 10, 119, 16),     # the widest padded row (120)
+])
+def test_conv3x3_matrix_core_path_widths_and_image_groups(N, C, H, W, J):
+    print("wgrad conv3x3 widths", N, C, H, W, J, flush=True)
+    x = activation((N, C, H, W), "relu", 310 + W, "bf16")
+    dy = gradient((N, J, H, W), 0.02, 410 + W, "bf16")
+    got, _, _ = gpu_dw(x, dy, 0.8, J, conv=CONV3)
+    ref = oracle.dw_conv(ref_xhat(x, 0.8), oracle.widen(dy), 3, 3, (1, 1), (1, 1))
+    assert_close(got, ref, TOL["bf16"])
+
+
 def test_conv3x3_integer_values_are_exact():
     rng = np.random.default_rng(6)
     x = f32_to_bf16_bits(rng.integers(-3, 4, (2, 16, 28, 28)).astype(np.float32))
