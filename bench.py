@@ -106,7 +106,7 @@ def main():
     import torch
 
     import paper_2202_13808_amd as dropit
-    from dropit_inputs import WORKLOADS, make
+    from dropit_inputs import EXTRA_WORKLOADS, WORKLOADS, make
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
@@ -114,7 +114,7 @@ def main():
     dropit.lib()  # fail loudly if the extension is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    w = WORKLOADS[args.workload]
+    w = {**WORKLOADS, **EXTRA_WORKLOADS}[args.workload]
     xh, dyh = make(w)
 
     def dev_tensor(a):
@@ -207,15 +207,17 @@ def main():
     # marks recorded per compress call: before and after the one persistent select kernel
     n_c = 2
     fc_mfma = bf16 and w.conv is None and w.c_out % 8 == 0
-    conv_mfma = bf16 and w.conv is not None and w.x_shape[3] % 8 == 0
+    conv_mfma = bf16 and w.conv is not None and 2 <= w.x_shape[3] <= 120
+    conv_padded = conv_mfma and w.x_shape[3] % 8 != 0       # one more kernel: the zero-padded copy of dY
     mfma = fc_mfma or conv_mfma
-    n_g = 4 if mfma else 3                   # prep, gemm, reduce, end  |  zero+scatter, gemm, end
+    n_g = 5 if conv_padded else 4 if mfma else 3   # prep, [pad,] gemm, reduce, end  |  zero+scatter, gemm, end
     c_ms = np.maximum(np.array([event_ms(e[:n_c]) for e in ce]) - event_overhead_ms, 0.0)   # [n_meas, n_c-1]
     g_ms = np.maximum(np.array([event_ms(e[:n_g]) for e in ge]) - event_overhead_ms, 0.0)
     c_med = np.median(c_ms, axis=0)
     g_med = np.median(g_ms, axis=0)
     c_names = ["select_fused"]
     g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
+               ["row_starts", "pad_dY", "mfma_conv", "partial_reduce"] if conv_padded else
                ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
     grad_ms = float(g_med.sum())
@@ -223,7 +225,7 @@ def main():
     esz = 2 if bf16 else 4
     compress_bytes = w.numel * esz + k * (esz + 4)           # read x once + write k (value, index) pairs
     flops = float(w.dense_flops)
-    main_idx = 1
+    main_idx = 2 if conv_padded else 1
     main_ms = float(np.mean(g_ms[:, main_idx]))
     dw_tflops_kernel = flops / (main_ms * 1e-3) * 1e-12
     hist_ms = float(np.mean(c_ms[:, 0]))

@@ -92,6 +92,17 @@ WORKLOADS = {
                                1006, 2006, conv=(3, 3, 1, 1)),
 }
 
+# Further shapes the benchmark can run (`bench.py --workload NAME`); not part of the five configurations above.
+# The 3x3 convolutions of the later ResNet-50 stages at batch 64: planes of 28, 14 and 7.
+EXTRA_WORKLOADS = {
+    "resnet_conv3x3_28": Workload("resnet_conv3x3_28", "bf16", (64, 128, 28, 28), "relu", 0.8, 128, 0.02,
+                                  1007, 2007, conv=(3, 3, 1, 1)),
+    "resnet_conv3x3_14": Workload("resnet_conv3x3_14", "bf16", (64, 256, 14, 14), "relu", 0.8, 256, 0.02,
+                                  1008, 2008, conv=(3, 3, 1, 1)),
+    "resnet_conv3x3_7": Workload("resnet_conv3x3_7", "bf16", (64, 512, 7, 7), "relu", 0.8, 512, 0.02,
+                                 1009, 2009, conv=(3, 3, 1, 1)),
+}
+
 
 def _normal(shape, seed: int) -> np.ndarray:
     return np.random.default_rng(seed).standard_normal(size=shape, dtype=np.float32)

@@ -281,33 +281,40 @@ conv_pad_rows_kernel(const uint16_t *__restrict__ dY, int64_t rows, int W, int W
 }
 
 // dW[j][c][tap] = sum over the GEMM workgroups' partials partial[p][tap][j][c], in a fixed order:
-// a workgroup takes 64 consecutive (tap, j, c) outputs; each of its 16 wavefronts adds a sixteenth
+// a workgroup takes 64 consecutive (tap, j, c) outputs; each of its (up to 16) wavefronts adds its share
 // of the parts in ascending order (enough loads in flight to cover the memory latency), then the
-// first wavefront adds the 16 sums in ascending order.
+// first wavefront adds the wavefronts' sums in ascending order.
+// VEC = 4 (taken when J * C is a multiple of 4): a thread sums four consecutive outputs with 16-byte loads.
 constexpr int RED_GROUPS = 16;
+template <int VEC>
 __global__ void __launch_bounds__(64 * RED_GROUPS)
 conv_reduce_kernel(const float *__restrict__ partial, int parts, int J, int C, float *__restrict__ dW)
 {
-    __shared__ float s_sum[RED_GROUPS][64];
+    typedef float vec_t __attribute__((ext_vector_type(VEC == 1 ? 2 : VEC)));   // (a 1-vector is not indexable: lane 0 of a pair)
+    __shared__ vec_t s_sum[RED_GROUPS][64];
+    const int groups = blockDim.x / 64;                 // wavefronts of this launch (a power of two up to 16)
     const int64_t jc = int64_t(J) * C;
     const int64_t total = jc * 9;
     const int o = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int64_t i = int64_t(blockIdx.x) * 64 + o;
-    float s = 0.f;
+    const int64_t i = (int64_t(blockIdx.x) * 64 + o) * VEC;              // first of this thread's outputs
+    vec_t s = 0.f;
     if (i < total) {
-        const int per = (parts + RED_GROUPS - 1) / RED_GROUPS;
+        const int per = (parts + groups - 1) / groups;
         const int p0 = grp * per, p1 = min(p0 + per, parts);
 #pragma unroll 8
-        for (int p = p0; p < p1; ++p) s += partial[int64_t(p) * total + i];
+        for (int p = p0; p < p1; ++p) {
+            if constexpr (VEC == 1) s[0] += partial[int64_t(p) * total + i];
+            else s += *reinterpret_cast<const vec_t *>(partial + int64_t(p) * total + i);
+        }
     }
     s_sum[grp][o] = s;
     __syncthreads();
     if (grp == 0 && i < total) {
-        float t = s_sum[0][o];
+        vec_t t = s_sum[0][o];
+        for (int g = 1; g < groups; ++g) t += s_sum[g][o];
+        const int64_t tap = i / jc, rem = i - tap * jc;                 // i = (tap, j, c); the VEC outputs share tap and j
 #pragma unroll
-        for (int g = 1; g < RED_GROUPS; ++g) t += s_sum[g][o];
-        const int64_t tap = i / jc, rem = i - tap * jc;                 // i = (tap, j, c)
-        dW[rem * 9 + tap] = t;
+        for (int e = 0; e < VEC; ++e) dW[(rem + e) * 9 + tap] = t[e];
     }
 }
 
@@ -405,7 +412,14 @@ dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const vo
     if (st != DROPIT_OK) return st;
     trace_mark(stream);
     const int64_t total = p.J * p.C * 9;
-    conv_reduce_kernel<<<int((total + 63) / 64), 64 * RED_GROUPS, 0, stream>>>(partial, plan.img_groups * plan.bands, int(p.J), int(p.C), dW);
+    // wavefronts per 64 (x4) outputs: enough that a thread has about four loads in flight, at most 16
+    const int parts = plan.img_groups * plan.bands;
+    int red_groups = 1;
+    while (red_groups * 8 <= parts && red_groups < RED_GROUPS) red_groups *= 2;
+    if ((p.J * p.C) % 4 == 0)
+        conv_reduce_kernel<4><<<int((total / 4 + 63) / 64), 64 * red_groups, 0, stream>>>(partial, parts, int(p.J), int(p.C), dW);
+    else
+        conv_reduce_kernel<1><<<int((total + 63) / 64), 64 * red_groups, 0, stream>>>(partial, parts, int(p.J), int(p.C), dW);
     trace_mark(stream);
     return launch_status();
 }
