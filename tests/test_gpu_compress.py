@@ -232,6 +232,26 @@ def test_sizes_around_the_sampling_threshold(numel):
         assert path in ((0, 1, 2) if expect_sampling else (0,)), (numel, gamma, path)
 
 
+def test_two_streams_at_once():
+    """Two persistent selects submitted on two streams at the same time (each with its own workspace): both finish,
+    both match the oracle.  The device runs them one after the other, or -- should their workgroups ever share the
+    compute units -- the bounded barriers send one of them to its serial redo; either way the bytes are the same."""
+    xs = [activation((3001, 700), "gelu", 71 + i, "bf16") for i in range(2)]
+    want = [oracle.compress(x, oracle.keep_count(x.size, 0.9)) for x in xs]
+    xd = [to_device(x) for x in xs]
+    wss = [torch.empty(dropit.compress_workspace_bytes(x.size, torch.bfloat16), dtype=torch.uint8, device="cuda:0") for x in xs]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        outs = []
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                outs.append(dropit.compress(xd[i], 0.9, workspace=wss[i], stream=streams[i]))
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert np.array_equal(to_host(outs[i][1]), want[i][1]) and to_host(outs[i][0]).tobytes() == want[i][0].tobytes()
+
+
 def test_deterministic_and_workspace_contents_irrelevant():
     x = activation((3001, 257), "gelu", 5, "bf16")
     xd = to_device(x)
