@@ -53,7 +53,7 @@ conv_rowptr_kernel(const int32_t *__restrict__ idx, int64_t k, int W, int64_t R,
 // GEMM: workgroup = (image n, band of RB output rows, 64 x 64 block of (j, c)).
 // AG = column groups (of 8) multiplied per step; the host picks the instantiation that wastes the
 // fewest padded groups for the row width at hand.
-template <int AG>
+template <int AG, bool MULTI>
 __global__ void __launch_bounds__(CT)
 conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ vals,
                     const int32_t *__restrict__ idx, int64_t k, const uint32_t *__restrict__ row_ptr, int C, int H,
@@ -80,14 +80,17 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     unsigned long long pc[5];
     pc[0] = wall_clock64();
 #endif
-    // accumulators live across the images of the group
+    // With several images per workgroup (MULTI) the accumulators live across the images; with one they
+    // start after the scatter, which leaves the scatter the registers to keep two batches of loads in flight.
     f32x16 acc[9];
+    if constexpr (MULTI) {
 #pragma unroll
-    for (int i = 0; i < 9; ++i)
+        for (int i = 0; i < 9; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    }
 
-    for (int n = n_begin; n < n_end; ++n) {
+    for (int n = n_begin; n < (MULTI ? n_end : n_begin + 1); ++n) {
     if (n != n_begin) __syncthreads();             // the previous image's rows have been read by every wavefront
     // ---- recover R(a^) for this band into LDS: zero fill, then scatter ------------
     // Pairs of this band: for each of the 64 channels one contiguous run [first, last) of the arrays
@@ -133,15 +136,24 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
             hi[q] = __builtin_amdgcn_readfirstlane(s_last[c0 + q]);
             longest = max(longest, hi[q] - lo[q]);
         }
-        for (uint32_t off = lane; off < longest; off += WAVE) {
-            int flat[SC];
-            uint32_t val[SC];       // full registers: 16-bit destinations get packed in pairs and their loads serialised
+        // the loads of the next 64 positions are issued before the current ones are stored: one memory
+        // round trip per channel batch instead of one per 64 positions
+        int flat[SC], flat_next[SC];
+        uint32_t val[SC], val_next[SC];     // full registers: 16-bit destinations get packed in pairs and their loads serialised
+        auto fetch_pairs = [&](uint32_t off, int (&f)[SC], uint32_t (&v)[SC]) {
 #pragma unroll
             for (int q = 0; q < SC; ++q) {
                 const uint32_t at = min(lo[q] + off, uint32_t(k) - 1);   // unconditional, clamped (k > 0)
-                flat[q] = idx[at];
-                val[q] = vals[at];
+                f[q] = idx[at];
+                v[q] = vals[at];
             }
+        };
+        // (not with several images per workgroup: their accumulators leave no registers for a second batch)
+        if (!MULTI && lane < longest) fetch_pairs(lane, flat, val);
+        for (uint32_t off = lane; off < longest; off += WAVE) {
+            const bool more = !MULTI && off + WAVE < longest;
+            if (MULTI) fetch_pairs(off, flat, val);
+            if (more) fetch_pairs(off + WAVE, flat_next, val_next);
 #pragma unroll
             for (int q = 0; q < SC; ++q) {
                 if (lo[q] + off >= hi[q]) continue;
@@ -155,6 +167,13 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
                 if (int(ih) >= ih_lo && int(ih) <= ih_hi && w < uint32_t(W))
                     *reinterpret_cast<uint16_t *>(lds + (int(ih) - (r0 - 1)) * slot_bytes + 16 + (c0 + q) * pitch_c + w * 2) = uint16_t(val[q]);
             }
+            if (more) {
+#pragma unroll
+                for (int q = 0; q < SC; ++q) {
+                    flat[q] = flat_next[q];
+                    val[q] = val_next[q];
+                }
+            }
         }
     }
     __syncthreads();
@@ -163,6 +182,12 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     pc[2] = wall_clock64();
 #endif
     // ---- multiply ---------------------------------------------------------------
+    if constexpr (!MULTI) {
+#pragma unroll
+        for (int i = 0; i < 9; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    }
     const int kg = lane >> 5;                          // K-half: which row of the pair
     const int j = jb * BJ + wj * 32 + (lane & 31);
     const int cl_b = wc * 32 + (lane & 31);            // this lane's input channel inside the block
@@ -403,11 +428,12 @@ dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const vo
         return DROPIT_OK;
     };
     dropit_status st = DROPIT_OK;
+    const bool multi = plan.imgs_per_wg > 1;
     switch (ag) {
-    case 5: st = launch(conv3x3_mfma_kernel<5>); break;
-    case 6: st = launch(conv3x3_mfma_kernel<6>); break;
-    case 7: st = launch(conv3x3_mfma_kernel<7>); break;
-    default: st = launch(conv3x3_mfma_kernel<8>); break;
+    case 5: st = multi ? launch(conv3x3_mfma_kernel<5, true>) : launch(conv3x3_mfma_kernel<5, false>); break;
+    case 6: st = multi ? launch(conv3x3_mfma_kernel<6, true>) : launch(conv3x3_mfma_kernel<6, false>); break;
+    case 7: st = multi ? launch(conv3x3_mfma_kernel<7, true>) : launch(conv3x3_mfma_kernel<7, false>); break;
+    default: st = multi ? launch(conv3x3_mfma_kernel<8, true>) : launch(conv3x3_mfma_kernel<8, false>); break;
     }
     if (st != DROPIT_OK) return st;
     trace_mark(stream);
