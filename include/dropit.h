@@ -126,6 +126,18 @@ typedef struct {
 size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
                                           int64_t k, int64_t c_out, const dropit_conv2d *conv);
 
+/* Which kernels dropit_weight_grad runs for these arguments (arguments as there; host-only, no GPU work):
+ * DROPIT_PATH_NONE for invalid or unsupported arguments. */
+typedef enum {
+    DROPIT_PATH_NONE = 0,
+    DROPIT_PATH_FC_MFMA = 1,        /* recover + split-K bf16 MFMA GEMM */
+    DROPIT_PATH_CONV_BANDS = 2,     /* 3x3/s1/p1 bf16: row bands in LDS, implicit im2col on the matrix cores */
+    DROPIT_PATH_CONV_GEMM = 3,      /* 3x3/s1/p1 bf16, small planes with many channels: explicit im2col rows + the FC GEMM */
+    DROPIT_PATH_FMA = 4             /* exact fp32 multiply-add kernels (fp32 inputs, odd shapes, other geometries) */
+} dropit_wgrad_path;
+dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,
+                                          int64_t c_out, const dropit_conv2d *conv);
+
 /*
  * Weight gradient from the sparsified cache (Sec. 3.2): the recover step R(a^)
  * (zeros at dropped positions) followed by the ordinary dense weight gradient;
@@ -142,7 +154,8 @@ size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, drop
  *     dW  [c_out, C, kh, kw] fp32:
  *     dW[j][c][u][v] = sum_{n,oy,ox} dY[n][j][oy][ox] * R(a^)[n][c][oy*sh-ph+u*dh][ox*sw-pw+v*dw]
  *     bf16 with kh = kw = 3, stride 1, pad 1, dilation 1 (and W <= 120)
- *     runs on the matrix cores; every other geometry (kernel extents up to 1024,
+ *     runs on the matrix cores (in one of two forms, see dropit_weight_grad_path);
+ *     every other geometry (kernel extents up to 1024,
  *     stride / pad / dilation up to 65535) takes an exact but slow fp32 kernel.
  *     DROPIT_EINVAL if the window does not fit the padded input.
  *

@@ -22,4 +22,5 @@ from .binding import (  # noqa: F401
     weight_grad,
     weight_grad_rows,
     weight_grad_workspace_bytes,
+    weight_grad_path,
 )

@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.dropit_weight_grad_rows.argtypes = [vp, vp, vp, i64, p64, i32, i32, vp, i64, pconv, vp, vp, sz, vp]
         L.dropit_weight_grad_workspace_bytes.restype = sz
         L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
+        L.dropit_weight_grad_path.restype = i32
+        L.dropit_weight_grad_path.argtypes = [p64, i32, i32, i64, i64, pconv]
         L.dropit_set_select_mode.restype = i32
         L.dropit_set_select_mode.argtypes = [i32]
         L.dropit_trace_events.restype = None
@@ -191,6 +193,17 @@ def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, k: i
     return int(lib().dropit_weight_grad_workspace_bytes(
         _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out),
         ctypes.byref(cs) if cs is not None else None))
+
+
+WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma"}
+
+
+def weight_grad_path(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int, conv=None) -> str:
+    """dropit_weight_grad_path: which kernels ``weight_grad`` runs for these arguments."""
+    cs = _conv_struct(conv)
+    return WGRAD_PATHS[int(lib().dropit_weight_grad_path(
+        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out),
+        ctypes.byref(cs) if cs is not None else None))]
 
 
 def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], dY: torch.Tensor,

@@ -154,4 +154,46 @@ __device__ inline void block_exclusive_scan2(uint32_t va, uint32_t vb, uint32_t 
     eb = uint32_t(__builtin_amdgcn_readlane(int(sb), w)) - uint32_t(__builtin_amdgcn_readlane(int(xb), w)) + ib - vb;
 }
 
+// ---------------------------------------------------------------------------
+// Cooperative lower_bound over a sorted int32 array for two targets at once
+// (number of elements < t0 and < t1): THREADS-ary search, both targets share the
+// rounds: 3 rounds of one load each over a million elements, 2 over a range of a few thousand.
+// All threads of the block must call it (contains barriers).
+// The search starts from the ranges [from0, to0) and [from1, to1), which must contain the respective
+// answers; the whole array is [0, n) for both.
+template <int THREADS>
+__device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64_t t0, int64_t t1, int64_t from0,
+                                          int64_t to0, int64_t from1, int64_t to1, int64_t &r0, int64_t &r1)
+{
+    int64_t lo[2] = {from0, from1}, hi[2] = {to0, to1};
+    const int64_t target[2] = {t0, t1};
+    while (hi[0] > lo[0] || hi[1] > lo[1]) {
+        int pred[2];
+        int64_t step[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int64_t span = hi[q] - lo[q];
+            step[q] = (span + THREADS - 1) / THREADS;
+            const int64_t pos = lo[q] + int64_t(threadIdx.x) * step[q];
+            pred[q] = (pos < hi[q]) && (int64_t(idx[pos]) < target[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c = __syncthreads_count(pred[q]);   // probes are monotone: the first c are true
+            if (hi[q] > lo[q]) {
+                if (c == 0) {
+                    hi[q] = lo[q];
+                } else {
+                    const int64_t nlo = lo[q] + int64_t(c - 1) * step[q] + 1;
+                    const int64_t nhi = min(lo[q] + int64_t(c) * step[q], hi[q]);
+                    lo[q] = nlo;
+                    hi[q] = nhi;
+                }
+            }
+        }
+    }
+    r0 = lo[0];
+    r1 = lo[1];
+}
+
 }  // namespace dropit

@@ -281,6 +281,17 @@ using namespace dropit;
 
 static bool use_fc_dense(const FcProblem &fp) { return fc_dense_supported(fp); }
 
+// which matrix-core path a 3x3/s1/p1 bf16 convolution takes: 2 im2col GEMM, 1 row-band kernel, 0 neither
+static int conv_path(const ConvProblem &cp)
+{
+    bool gemm = conv_gemm_preferred(cp);
+#ifdef DROPIT_TUNING
+    if (const char *e = getenv("DROPIT_CONV_PATH")) gemm = e[0] == 'g' && conv_gemm_supported(cp);
+#endif
+    if (gemm) return 2;
+    return conv_mfma_supported(cp) ? 1 : 0;
+}
+
 // Workspace need of the path dropit_weight_grad will take for this problem.
 static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
 {
@@ -290,9 +301,26 @@ static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
     }
     if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
-        if (conv_mfma_supported(cp)) return conv_mfma_plan(cp).total();
+        const int path = conv_path(cp);
+        if (path == 2) return conv_gemm_plan(cp).total();
+        if (path == 1) return conv_mfma_plan(cp).total();
     }
     return dense_bytes(p, dt);
+}
+
+extern "C" dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,
+                                                     int64_t c_out, const dropit_conv2d *conv)
+{
+    Problem p;
+    if (describe(x_shape, ndim, dt, c_out, conv, p) != DROPIT_OK) return DROPIT_PATH_NONE;
+    if (k < 0 || k > p.numel) return DROPIT_PATH_NONE;
+    if (!p.conv && dt == DROPIT_BF16 && use_fc_dense(FcProblem{p.ntok, p.cin, p.cout, k})) return DROPIT_PATH_FC_MFMA;
+    if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16) {
+        const int path = conv_path(ConvProblem{p.N, p.C, p.H, p.W, p.cout, k});
+        if (path == 2) return DROPIT_PATH_CONV_GEMM;
+        if (path == 1) return DROPIT_PATH_CONV_BANDS;
+    }
+    return DROPIT_PATH_FMA;
 }
 
 extern "C" size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
@@ -332,7 +360,9 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
     }
     if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16 && k > 0) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
-        if (conv_mfma_supported(cp)) return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
+        const int path = conv_path(cp);
+        if (path == 2) return conv_gemm_run(cp, conv_gemm_plan(cp), vals, idx, dY, dW, ws, stream);
+        if (path == 1) return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
     }
     if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
     return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);

@@ -53,48 +53,6 @@ constexpr int RECOVER_ELEMS = recover_cfg[1];
 constexpr int RECOVER_ELEMS_MAX = 32768;
 
 // ---------------------------------------------------------------------------
-// Cooperative lower_bound over a sorted int32 array for two targets at once
-// (number of elements < t0 and < t1): THREADS-ary search, both targets share the
-// rounds: 3 rounds of one load each over a million elements, 2 over a range of a few thousand.
-// All threads of the block must call it (contains barriers).
-// The search starts from the ranges [from0, to0) and [from1, to1), which must contain the respective
-// answers; the whole array is [0, n) for both.
-template <int THREADS>
-__device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64_t t0, int64_t t1, int64_t from0,
-                                          int64_t to0, int64_t from1, int64_t to1, int64_t &r0, int64_t &r1)
-{
-    int64_t lo[2] = {from0, from1}, hi[2] = {to0, to1};
-    const int64_t target[2] = {t0, t1};
-    while (hi[0] > lo[0] || hi[1] > lo[1]) {
-        int pred[2];
-        int64_t step[2];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int64_t span = hi[q] - lo[q];
-            step[q] = (span + THREADS - 1) / THREADS;
-            const int64_t pos = lo[q] + int64_t(threadIdx.x) * step[q];
-            pred[q] = (pos < hi[q]) && (int64_t(idx[pos]) < target[q]);
-        }
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int c = __syncthreads_count(pred[q]);   // probes are monotone: the first c are true
-            if (hi[q] > lo[q]) {
-                if (c == 0) {
-                    hi[q] = lo[q];
-                } else {
-                    const int64_t nlo = lo[q] + int64_t(c - 1) * step[q] + 1;
-                    const int64_t nhi = min(lo[q] + int64_t(c) * step[q], hi[q]);
-                    lo[q] = nlo;
-                    hi[q] = nhi;
-                }
-            }
-        }
-    }
-    r0 = lo[0];
-    r1 = lo[1];
-}
-
-// ---------------------------------------------------------------------------
 // Recover R(a^): workgroup b owns rows [b * rows_per_wg, ...) of the padded dense
 // matrix.  Its pairs are one contiguous run of the index-sorted arrays (found by
 // search), so the rows are assembled in LDS (zero fill, one 16-bit store per pair)
@@ -697,8 +655,11 @@ using Cfg = GemmCfg<DROPIT_GEMM_CFG>;
 int tuned_splits(int tiles, int nkb)
 {
     // as many K-slices as fill the 256 compute units (one or two resident workgroups each)
-    // without starting a second round
-    int splits = 256 * Cfg::WGS_PER_CU / tiles;
+    // without starting a second round -- but a slice of at least ~20 token blocks: every slice
+    // writes a whole partial tile however little it summed, and below that depth the partial
+    // traffic costs more than the idle compute units (measured on 3136 and 12544 tokens:
+    // the best slice count was the one with 19.6 blocks per slice both times)
+    int splits = std::min(256 * Cfg::WGS_PER_CU / tiles, std::max(1, (nkb + 10) / 20));
 #ifdef DROPIT_TUNING
     if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
 #endif
@@ -728,10 +689,48 @@ FcDensePlan fc_dense_plan(const FcProblem &p)
     plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
     plan.pitch = int((p.cin + 7) / 8 * 8);
     plan.rows_per_wg = std::max(1, (plan.pitch <= RECOVER_ELEMS ? RECOVER_ELEMS : RECOVER_ELEMS_MAX) / plan.pitch);
-    plan.dense_bytes = round_up(size_t(plan.nkb) * Cfg::BK * plan.pitch * 2, 256);
+    plan.ntok_pad = int64_t(plan.nkb) * Cfg::BK;
+    plan.dense_bytes = round_up(size_t(plan.ntok_pad) * plan.pitch * 2, 256);
     // K-slice partials are whole tiles (ragged edge tiles included) in accumulator order
     plan.partial_bytes = plan.splits > 1 ? size_t(plan.splits) * plan.nb_count * plan.mb_count * Cfg::BM * Cfg::BN * 4 : 0;
     return plan;
+}
+
+static bool fc_dense_attributes()
+{
+    static std::atomic<uint64_t> attr_set{0};
+    return once_per_device(attr_set, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   RECOVER_ELEMS_MAX * 2) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_stream_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   RECOVER_ELEMS_MAX * 2) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess;
+    });
+}
+
+dropit_status fc_dense_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
+                            float *partial, float *dW, hipStream_t stream)
+{
+    if (!fc_dense_attributes()) return DROPIT_EHIP;
+    const int total = plan.nb_count * plan.mb_count * plan.splits;
+    const int grid = (total + 7) / 8 * 8;
+    float *out = plan.splits > 1 ? partial : dW;
+    fc_dense_kernel<Cfg><<<grid, Cfg::NTHREADS, Cfg::LDS_BYTES, stream>>>(
+        static_cast<const uint16_t *>(dY), dense, p.ntok, int(p.cout), int(p.cin), plan.pitch, plan.nb_count,
+        plan.mb_count, plan.nkb, plan.splits, out);
+
+    trace_mark(stream);
+    if (plan.splits > 1) {
+        const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (Cfg::BM * Cfg::BN / 4);
+        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
+        splitk_sum_kernel<Cfg><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
+                                                           int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
+    }
+    trace_mark(stream);
+    return launch_status();
 }
 
 dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
@@ -739,20 +738,8 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
 {
     uint16_t *dense = reinterpret_cast<uint16_t *>(ws);
     float *partial = reinterpret_cast<float *>(ws + plan.dense_bytes);
-    const int64_t ntok_pad = int64_t(plan.nkb) * Cfg::BK;
-
-    static std::atomic<uint64_t> attr_set{0};
-    if (!once_per_device(attr_set, [] {
-            return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       RECOVER_ELEMS_MAX * 2) == hipSuccess &&
-                   hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_stream_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       RECOVER_ELEMS_MAX * 2) == hipSuccess &&
-                   hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess;
-        }))
-        return DROPIT_EHIP;
+    const int64_t ntok_pad = plan.ntok_pad;
+    if (!fc_dense_attributes()) return DROPIT_EHIP;
 
     trace_mark(stream);
     const int recover_grid = int((ntok_pad + plan.rows_per_wg - 1) / plan.rows_per_wg);
@@ -779,22 +766,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     }
 
     trace_mark(stream);
-    const int total = plan.nb_count * plan.mb_count * plan.splits;
-    const int grid = (total + 7) / 8 * 8;
-    float *out = plan.splits > 1 ? partial : dW;
-    fc_dense_kernel<Cfg><<<grid, Cfg::NTHREADS, Cfg::LDS_BYTES, stream>>>(
-        static_cast<const uint16_t *>(dY), dense, p.ntok, int(p.cout), int(p.cin), plan.pitch, plan.nb_count,
-        plan.mb_count, plan.nkb, plan.splits, out);
-
-    trace_mark(stream);
-    if (plan.splits > 1) {
-        const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (Cfg::BM * Cfg::BN / 4);
-        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
-        splitk_sum_kernel<Cfg><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
-                                                           int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
-    }
-    trace_mark(stream);
-    return launch_status();
+    return fc_dense_gemm(p, plan, dY, dense, partial, dW, stream);
 }
 
 }  // namespace dropit

@@ -13,6 +13,7 @@ struct FcProblem {
 
 struct FcDensePlan {
     int nkb, nb_count, mb_count, splits, pitch, rows_per_wg;
+    int64_t ntok_pad;                          // rows of the dense operand: the tokens rounded up to whole token blocks
     size_t dense_bytes, partial_bytes;
     size_t total() const { return dense_bytes + partial_bytes; }
 };
@@ -22,6 +23,11 @@ bool fc_dense_supported(const FcProblem &p);
 FcDensePlan fc_dense_plan(const FcProblem &p);
 dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
                            const void *dY, float *dW, char *ws, hipStream_t stream);
+
+// the GEMM and the K-slice sum alone, on operands that are already dense: dY [ntok][cout], dense [plan.ntok_pad][plan.pitch]
+// (rows past ntok zero); `partial` holds plan.partial_bytes
+dropit_status fc_dense_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
+                            float *partial, float *dW, hipStream_t stream);
 
 struct ConvProblem {
     int64_t N, C, H, W, J, k;
@@ -40,6 +46,21 @@ struct ConvPlan {
 bool conv_mfma_supported(const ConvProblem &p);
 ConvPlan conv_mfma_plan(const ConvProblem &p);
 dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const void *vals, const int32_t *idx,
+                            const void *dY, float *dW, char *ws, hipStream_t stream);
+
+// The same gradient as one GEMM over explicit im2col rows, for small planes with many channels
+// (wgrad_conv_gemm.hip)
+struct ConvGemmPlan {
+    FcProblem fp;                              // tokens = N*H*W output positions, c_in = 9*C taps, c_out = J
+    FcDensePlan gemm;
+    int cb, cblocks;                           // input channels per im2col workgroup
+    size_t lds_bytes, dyt_bytes;
+    size_t total() const { return gemm.dense_bytes + gemm.partial_bytes + dyt_bytes; }
+};
+bool conv_gemm_supported(const ConvProblem &p);
+bool conv_gemm_preferred(const ConvProblem &p);
+ConvGemmPlan conv_gemm_plan(const ConvProblem &p);
+dropit_status conv_gemm_run(const ConvProblem &p, const ConvGemmPlan &plan, const void *vals, const int32_t *idx,
                             const void *dY, float *dW, char *ws, hipStream_t stream);
 
 }  // namespace dropit

@@ -5,6 +5,7 @@ import os
 import re
 
 import pytest
+import torch
 
 import paper_2202_13808_amd as dropit
 from paper_2202_13808_amd import binding
@@ -22,6 +23,7 @@ def test_header_declares_the_expected_entry_points():
     assert declared_symbols() == sorted([
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
         "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode",
+        "dropit_weight_grad_path",
         "dropit_compress_random_workspace_bytes", "dropit_compress_random",
         "dropit_compress_rows_workspace_bytes", "dropit_compress_rows",
         "dropit_weight_grad_rows_workspace_bytes", "dropit_weight_grad_rows"])
@@ -124,6 +126,29 @@ def test_row_form_rejects_bad_arguments_without_a_gpu():
     assert wg(fake, fake, fake, 4, _shape(4, 8), 2, binding.BF16, fake, 8, None, dw, ws, 16, None) == binding.EWORKSPACE
     assert L.dropit_weight_grad_rows_workspace_bytes(_shape(4, 8), 2, binding.BF16, 4, 8, None) > \
         L.dropit_weight_grad_workspace_bytes(_shape(4, 8), 2, binding.BF16, 4, 8, None)
+
+
+def test_weight_grad_path_of_the_benchmark_shapes():
+    """Host-only query: which kernels a call would run.  The measured choice for the paper's layer
+    shapes is part of the contract the benchmarks rely on."""
+    c3 = (3, 3, 1, 1, 1, 1, 1, 1)
+    bf, f32 = torch.bfloat16, torch.float32
+    path = dropit.weight_grad_path
+    assert path((64, 197, 768), bf, 1000, 3072) == "fc_mfma"
+    assert path((64, 197, 3072), bf, 1000, 768) == "fc_mfma"
+    assert path((64, 197, 768), f32, 1000, 3072) == "fma"
+    assert path((64, 197, 768), bf, 1000, 3070) == "fma"               # c_out not a multiple of 8
+    assert path((64, 64, 56, 56), bf, 1000, 64, conv=c3) == "conv_bands"
+    assert path((64, 128, 28, 28), bf, 1000, 128, conv=c3) == "conv_bands"
+    assert path((64, 256, 14, 14), bf, 1000, 256, conv=c3) == "conv_gemm"
+    assert path((64, 512, 7, 7), bf, 1000, 512, conv=c3) == "conv_gemm"
+    assert path((64, 64, 7, 7), bf, 1000, 64, conv=c3) == "conv_bands"  # few channels
+    assert path((64, 516, 7, 7), bf, 1000, 512, conv=c3) == "conv_bands"  # channels not a multiple of 8
+    assert path((64, 512, 7, 7), f32, 1000, 512, conv=c3) == "fma"
+    assert path((2, 3, 20, 22), bf, 100, 8, conv=(7, 7, 2, 2, 3, 3, 1, 1)) == "fma"
+    assert path((3, 16, 9, 1), bf, 10, 8, conv=c3) == "fma"             # a single column
+    assert path((64, 512, 7, 7), bf, -1, 512, conv=c3) == "none"
+    assert path((1, 2, 4, 4), bf, 4, 2, conv=(7, 7, 1, 1, 0, 0, 1, 1)) == "none"
 
 
 def test_select_mode_switch_validates():

@@ -166,19 +166,28 @@ def test_conv3x3_shapes(dtype, N, C, H, W, J):
     assert_close(got, ref, TOL[dtype])
 
 
-@pytest.mark.parametrize("N,C,H,W,J", [
-    (4, 64, 28, 28, 64),      # ResNet stage 2 plane: rows of 28 go through the zero-padded copy of dY (rows of 32)
-    (6, 128, 14, 14, 96),     # stage 3 plane, two channel blocks, a ragged filter block
-    (32, 256, 7, 7, 256),     # stage 4 plane: more (image, block) units than compute units -> several images per workgroup
-    (40, 192, 7, 7, 128),     # ... with a ragged last image group
-    (3, 16, 9, 1, 8),         # a single column: the exact fp32 kernel
-    (3, 16, 9, 2, 8),         # two columns: the narrowest plane of the matrix-core path
-    (2, 24, 10, 119, 16),     # the widest padded row (120)
+@pytest.mark.parametrize("N,C,H,W,J,path", [
+    (4, 64, 28, 28, 64, "conv_bands"),     # ResNet stage 2 plane: rows of 28 go through the zero-padded copy of dY (rows of 32)
+    (6, 128, 14, 14, 96, "conv_bands"),    # stage 3 plane, two channel blocks, a ragged filter block; too small for the GEMM form
+    (32, 256, 7, 7, 256, "conv_gemm"),     # stage 4 plane, many channels: one GEMM over im2col rows
+    (40, 192, 7, 7, 128, "conv_gemm"),     # ... with zero pad rows after the last token block
+    (24, 128, 14, 14, 264, "conv_gemm"),   # ... 16-channel im2col tiles, c_out not a multiple of 64
+    (48, 136, 5, 9, 72, "conv_gemm"),      # ... a non-square plane, a ragged last channel block (136 = 64 + 64 + 8)
+    (128, 128, 1, 16, 64, "conv_gemm"),    # ... a single row
+    (128, 128, 16, 1, 64, "conv_gemm"),    # ... a single column
+    (600, 64, 7, 7, 64, "conv_bands"),     # few channels: more (image, block) units than compute units
+                                           # -> several images per workgroup
+    (778, 64, 7, 7, 64, "conv_bands"),     # ... with a ragged last image group
+    (3, 16, 9, 1, 8, "fma"),               # a single column with few channels: the exact fp32 kernel
+    (3, 16, 9, 2, 8, "conv_bands"),        # two columns: the narrowest plane of the row-band kernel
+    (2, 24, 10, 119, 16, "conv_bands"),    # the widest padded row (120)
 ])
-def test_conv3x3_matrix_core_path_widths_and_image_groups(N, C, H, W, J):
-    print("wgrad conv3x3 widths", N, C, H, W, J, flush=True)
+def test_conv3x3_matrix_core_paths_widths_and_image_groups(N, C, H, W, J, path):
+    print("wgrad conv3x3 widths", N, C, H, W, J, path, flush=True)
     x = activation((N, C, H, W), "relu", 310 + W, "bf16")
     dy = gradient((N, J, H, W), 0.02, 410 + W, "bf16")
+    k = oracle.keep_count(x.size, 0.8)
+    assert dropit.weight_grad_path(x.shape, torch.bfloat16, k, J, conv=CONV3) == path
     got, _, _ = gpu_dw(x, dy, 0.8, J, conv=CONV3)
     ref = oracle.dw_conv(ref_xhat(x, 0.8), oracle.widen(dy), 3, 3, (1, 1), (1, 1))
     assert_close(got, ref, TOL["bf16"])
