@@ -212,15 +212,15 @@ def main():
     conv_mfma = path == "conv_bands"
     conv_padded = conv_mfma and w.x_shape[3] % 8 != 0       # one more kernel: the zero-padded copy of dY
     mfma = fc_mfma or conv_mfma or conv_gemm
-    # marks per call: prep, [second prep,] gemm, reduce, end  |  zero+scatter, gemm, end
-    n_g = 5 if (conv_padded or conv_gemm) else 4 if mfma else 3
+    # marks per call: prep, [pad,] gemm, reduce, end  |  zero+scatter, gemm, end
+    n_g = 5 if conv_padded else 4 if mfma else 3
     c_ms = np.maximum(np.array([event_ms(e[:n_c]) for e in ce]) - event_overhead_ms, 0.0)   # [n_meas, n_c-1]
     g_ms = np.maximum(np.array([event_ms(e[:n_g]) for e in ge]) - event_overhead_ms, 0.0)
     c_med = np.median(c_ms, axis=0)
     g_med = np.median(g_ms, axis=0)
     c_names = ["select_fused"]
     g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
-               ["im2col_recover", "dY_to_tokens", "mfma_gemm", "splitk_reduce"] if conv_gemm else
+               ["im2col_recover_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if conv_gemm else
                ["row_starts", "pad_dY", "mfma_conv", "partial_reduce"] if conv_padded else
                ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
@@ -229,7 +229,7 @@ def main():
     esz = 2 if bf16 else 4
     compress_bytes = w.numel * esz + k * (esz + 4)           # read x once + write k (value, index) pairs
     flops = float(w.dense_flops)
-    main_idx = 2 if (conv_padded or conv_gemm) else 1
+    main_idx = 2 if conv_padded else 1
     main_ms = float(np.mean(g_ms[:, main_idx]))
     dw_tflops_kernel = flops / (main_ms * 1e-3) * 1e-12
     hist_ms = float(np.mean(c_ms[:, 0]))

@@ -196,4 +196,84 @@ __device__ inline void block_lower_bound2(const int32_t *__restrict__ idx, int64
     r1 = lo[1];
 }
 
+// ---------------------------------------------------------------------------
+// Calls place(flat, value) for the pairs of the index-sorted arrays whose flat index lies in
+// [first, last), and possibly for some neighbours outside it (place must ignore those).
+// Where the pairs of a flat-index range start is first guessed, not searched: min-k keeps a fixed
+// fraction of the tensor, so the pair with flat index f sits near position f * k / numel, and if the
+// kept elements are spread evenly the guess is off by a few sqrt(k) at most.  The workgroup loads a
+// window of pairs around the guesses for both ends (margin `margin` on either side) in ONE round of
+// loads, values included, checks with the loaded indices themselves that the window covers the
+// range, and hands over what it loaded.  Only if the window does not cover it (density that varies
+// along the tensor) or would not fit WN entries per thread does it fall back to the exact search,
+// three dependent rounds of loads, and a further round for the pairs.
+// between() runs after the window's loads are issued and before any place(): the place for the
+// caller's LDS zero fill (a barrier follows it).  All threads of the block must call this.
+template <int THREADS, int WN, typename Place, typename Between>
+__device__ inline void for_pairs_in_range(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx,
+                                          int64_t k, int64_t numel, int64_t first, int64_t last, int64_t margin,
+                                          Place &&place, Between &&between)
+{
+    const int tid = threadIdx.x;
+    const int64_t g_lo = static_cast<int64_t>(static_cast<double>(first) * static_cast<double>(k) / static_cast<double>(numel));
+    const int64_t g_hi = static_cast<int64_t>(static_cast<double>(last) * static_cast<double>(k) / static_cast<double>(numel));
+    const int64_t w_lo = max<int64_t>(g_lo - margin, 0), w_hi = min<int64_t>(g_hi + margin, k);
+    const bool window_fits = w_hi - w_lo <= int64_t(WN) * THREADS;
+    int32_t wi[WN];
+    uint32_t wv[WN];        // a full register each: 16-bit destinations get packed in pairs, and the second load
+                            // of a pair then waits for the first
+    if (window_fits) {
+#pragma unroll
+        for (int u = 0; u < WN; ++u) {
+            const int64_t j = w_lo + int64_t(u) * THREADS + tid;
+            if (j < w_hi) {
+                wi[u] = idx[j];
+                wv[u] = vals[j];
+            }
+        }
+    }
+    between();
+    // the window covers the range iff nothing of it can lie before its first or after its last entry
+    bool uncovered = !window_fits;
+    if (window_fits && tid == 0) {
+        if (w_lo > 0 && w_lo < w_hi && int64_t(wi[0]) >= first) uncovered = true;
+        if (w_lo > 0 && w_lo >= w_hi) uncovered = first < last;       // empty window in the middle of the array
+    }
+    if (window_fits && w_hi < k) {
+        const int64_t j_last = w_hi - 1;                              // held by thread (j_last - w_lo) % THREADS, slot / THREADS
+        if (j_last >= w_lo && (j_last - w_lo) % THREADS == tid) {
+            bool short_of_end = false;
+#pragma unroll
+            for (int u = 0; u < WN; ++u)
+                if ((j_last - w_lo) / THREADS == u) short_of_end = int64_t(wi[u]) < last;
+            uncovered = uncovered || short_of_end;
+        }
+    }
+    if (__syncthreads_or(uncovered)) {                                // also orders between() before the first place()
+        int64_t lo, hi;
+        block_lower_bound2<THREADS>(idx, first, last, 0, k, 0, k, lo, hi);
+        // eight pairs per thread at a time: their loads are all in flight before the first place()
+        constexpr int BATCH = 8;
+        for (int64_t j0 = lo + tid; j0 < hi; j0 += int64_t(BATCH) * THREADS) {
+            int32_t pi[BATCH];
+            uint32_t pv[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int64_t j = j0 + int64_t(u) * THREADS;
+                if (j < hi) {
+                    pi[u] = idx[j];
+                    pv[u] = vals[j];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u)
+                if (j0 + int64_t(u) * THREADS < hi) place(pi[u], pv[u]);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < WN; ++u)
+            if (w_lo + int64_t(u) * THREADS + tid < w_hi) place(wi[u], wv[u]);
+    }
+}
+
 }  // namespace dropit

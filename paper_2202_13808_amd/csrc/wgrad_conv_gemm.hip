@@ -1,6 +1,6 @@
 // 3x3 / stride 1 / pad 1 convolution weight gradient as ONE dense GEMM over explicit im2col rows.
 //
-// Sec. 3.3 (convolution): dW[j][c][u][v] = sum over images and output positions of
+// Sec. 3.2 (convolution weight gradient): dW[j][c][u][v] = sum over images and output positions of
 // dY[n][j][oy][ox] * R(a^)[n][c][oy + u - 1][ox + v - 1].  Read as a matrix product this is
 // dW[j][(c, u, v)] = sum_t dYt[t][j] * B[t][(c, u, v)] with one "token" t per output position
 // (n, oy, ox) and B the im2col rows of the recovered input: exactly the fully-connected form
@@ -8,38 +8,88 @@
 //
 // For small planes with many channels (the last stages of a ResNet: 14x14x256, 7x7x512) B is
 // small (tens of MB) and the product has hundreds of output tiles, so it runs on the
-// fully-connected GEMM kernel at its full rate, where the row-band kernel of wgrad_conv_mfma.hip
+// fully-connected GEMM kernel, where the row-band kernel of wgrad_conv_mfma.hip
 // spends most of its time staging a few hundred positions per workgroup.  Large planes with few
 // channels are the opposite case (B would be nine times the activation) and stay there.
 //
-// Two small kernels prepare the operands: B is assembled from the (value, index) pairs in LDS
+// One small kernel prepares both operands: B is assembled from the (value, index) pairs in LDS
 // tiles (one image x a block of channels: its pairs are one contiguous run of the sorted arrays)
-// and written once in full lines, no separate zero fill; dY is transposed from [N][J][H][W] to
-// token-major [N*H*W][J].  The result lands in dW's own layout [J][C][3][3].
+// and written once in full lines, no separate zero fill; other workgroups of the same launch transpose
+// dY from [N][J][H][W] to token-major [N*H*W][J].  The result lands in dW's own layout [J][C][3][3].
 #include "wgrad_internal.hpp"
 
 namespace dropit {
 namespace {
 
 constexpr int IM2COL_THREADS = 256;
+constexpr int IM2COL_WINDOW = 32;             // window entries per thread (see for_pairs_in_range)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Workgroup (n, channel block): the im2col columns [9 * c0, 9 * (c0 + cw)) of the H * W token rows
-// of image n.  Extra workgroups past N * cblocks zero the pad rows [ntok, ntok_pad).
+constexpr int DYT_JB = 64;                    // output channels per transposing workgroup
+
+// dY [N][J][HW] -> dYt [N * HW][J]: workgroup (n, block of 64 output channels) moves a contiguous
+// 64 x HW slab through LDS.  J % 8 == 0, so the slab starts on a 16-byte boundary and is whole
+// 16-byte vectors: each thread's loads are independent vector loads, all issued before the first
+// LDS store; the stores leave as pairs of neighbouring channels.
+__device__ inline void dy_to_tokens(const uint16_t *__restrict__ dY, int J, int HW, int unit, int jblocks,
+                                    uint16_t *__restrict__ dYt, uint16_t *slab /* [64][HW | 1] */)
+{
+    const int n = unit / jblocks, j0 = (unit % jblocks) * DYT_JB;
+    const int jw = min(DYT_JB, J - j0);                                   // a multiple of 8
+    const int ld = HW | 1;                                                // odd pitch: the transposed reads spread over the banks
+    const u32x4 *src = reinterpret_cast<const u32x4 *>(dY + (int64_t(n) * J + j0) * HW);
+    const int vecs = jw * HW / 8;
+    constexpr int BATCH = 4;
+    for (int i0 = threadIdx.x; i0 < vecs; i0 += BATCH * IM2COL_THREADS) {
+        u32x4 v[BATCH];
+#pragma unroll
+        for (int q = 0; q < BATCH; ++q)
+            if (i0 + q * IM2COL_THREADS < vecs) v[q] = src[i0 + q * IM2COL_THREADS];
+#pragma unroll
+        for (int q = 0; q < BATCH; ++q) {
+            const int i = i0 + q * IM2COL_THREADS;
+            if (i >= vecs) continue;
+            int jj = (i * 8) / HW, t = i * 8 - jj * HW;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                slab[jj * ld + t] = uint16_t(v[q][e >> 1] >> ((e & 1) * 16));
+                if (++t == HW) {
+                    t = 0;
+                    ++jj;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *dst = reinterpret_cast<uint32_t *>(dYt + int64_t(n) * HW * J + j0);     // j0 and J are even
+    for (int i = threadIdx.x; i < HW * (DYT_JB / 2); i += IM2COL_THREADS) {
+        const int t = i / (DYT_JB / 2), jj = (i % (DYT_JB / 2)) * 2;
+        if (jj < jw) dst[(int64_t(t) * J + jj) / 2] = uint32_t(slab[jj * ld + t]) | (uint32_t(slab[(jj + 1) * ld + t]) << 16);
+    }
+}
+
+// Both operands of the GEMM in one launch.  Workgroup (n, channel block), the first N * cblocks: the
+// im2col columns [9 * c0, 9 * (c0 + cw)) of the H * W token rows of image n.  The next pad_wgs
+// workgroups zero the pad rows [ntok, ntok_pad) of B; the last N * jblocks transpose dY.
 __global__ void __launch_bounds__(IM2COL_THREADS)
 conv_im2col_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, int N, int C,
-                   int H, int W, int cb, int cblocks, int pitch, int64_t ntok, int64_t ntok_pad,
-                   uint16_t *__restrict__ B)
+                   int H, int W, int cb, int cblocks, int pitch, int64_t ntok, int64_t ntok_pad, int pad_wgs,
+                   int64_t margin, uint16_t *__restrict__ B, const uint16_t *__restrict__ dY, int J, int jblocks,
+                   uint16_t *__restrict__ dYt)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t tile[];      // [H * W][cw * 9]
+    extern __shared__ __attribute__((aligned(16))) uint16_t tile[];      // [H * W][cw * 9], or the dY slab
     const int tid = threadIdx.x;
     const int units = N * cblocks;
+    if (int(blockIdx.x) >= units + pad_wgs) {
+        dy_to_tokens(dY, J, H * W, int(blockIdx.x) - units - pad_wgs, jblocks, dYt, tile);
+        return;
+    }
     if (int(blockIdx.x) >= units) {
         // pad rows: 16-byte zero stores, shared among the extra workgroups
         const int64_t chunks = (ntok_pad - ntok) * pitch / 8;
         u32x4 *dst = reinterpret_cast<u32x4 *>(B + ntok * pitch);
-        const int64_t stride = int64_t(gridDim.x - units) * IM2COL_THREADS;
+        const int64_t stride = int64_t(pad_wgs) * IM2COL_THREADS;
         for (int64_t i = int64_t(blockIdx.x - units) * IM2COL_THREADS + tid; i < chunks; i += stride)
             dst[i] = u32x4{0u, 0u, 0u, 0u};
         return;
@@ -51,16 +101,11 @@ conv_im2col_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict_
 
     u32x4 *tile16 = reinterpret_cast<u32x4 *>(tile);
     const int chunks = HW * row / 8;                                      // cw % 8 == 0
-    for (int i = tid; i < chunks; i += IM2COL_THREADS) tile16[i] = u32x4{0u, 0u, 0u, 0u};
-
-    int64_t r0, r1;
-    block_lower_bound2<IM2COL_THREADS>(idx, lo, hi, 0, k, 0, k, r0, r1);
-    __syncthreads();
 
     // element (c, ih, iw) is the (u, v) tap of output position (ih + 1 - u, iw + 1 - v)
     auto place = [&](int32_t flat, uint32_t v16) {
         const uint32_t rel = uint32_t(int64_t(flat) - lo);
-        if (rel >= uint32_t(cw * HW)) return;                             // unsorted input must not write outside the tile
+        if (rel >= uint32_t(cw * HW)) return;                             // another workgroup's pair
         const uint32_t c = rel / uint32_t(HW), rem = rel - c * uint32_t(HW);
         const int ih = int(rem / uint32_t(W)), iw = int(rem - uint32_t(ih) * uint32_t(W));
 #pragma unroll
@@ -75,24 +120,10 @@ conv_im2col_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict_
             }
         }
     };
-    // eight pairs per thread at a time, all loads in flight before the first LDS store; the values are
-    // held in full registers (16-bit destinations get packed in pairs and their loads serialised)
-    constexpr int BATCH = 8;
-    for (int64_t j0 = r0 + tid; j0 < r1; j0 += int64_t(BATCH) * IM2COL_THREADS) {
-        int32_t pi[BATCH];
-        uint32_t pv[BATCH];
-#pragma unroll
-        for (int q = 0; q < BATCH; ++q) {
-            const int64_t j = j0 + int64_t(q) * IM2COL_THREADS;
-            if (j < r1) {
-                pi[q] = idx[j];
-                pv[q] = vals[j];
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < BATCH; ++q)
-            if (j0 + int64_t(q) * IM2COL_THREADS < r1) place(pi[q], pv[q]);
-    }
+    // the pairs of [lo, hi): one round of loads around their interpolated position, else a search
+    for_pairs_in_range<IM2COL_THREADS, IM2COL_WINDOW>(vals, idx, k, int64_t(N) * C * HW, lo, hi, margin, place, [&] {
+        for (int i = tid; i < chunks; i += IM2COL_THREADS) tile16[i] = u32x4{0u, 0u, 0u, 0u};
+    });
     __syncthreads();
 
     // a token's segment is row * 2 bytes (a multiple of 144) at a 16-byte aligned column offset
@@ -104,29 +135,6 @@ conv_im2col_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict_
     }
 }
 
-// dY [N][J][HW] -> dYt [N * HW][J]: workgroup (n, block of 64 output channels) moves a contiguous
-// 64 x HW slab through LDS.
-constexpr int DYT_JB = 64;
-__global__ void __launch_bounds__(256)
-conv_dy_tokens_kernel(const uint16_t *__restrict__ dY, int J, int HW, int jblocks, uint16_t *__restrict__ dYt)
-{
-    extern __shared__ __attribute__((aligned(16))) uint16_t slab[];      // [jw][HW + 1]
-    const int n = blockIdx.x / jblocks, j0 = (blockIdx.x % jblocks) * DYT_JB;
-    const int jw = min(DYT_JB, J - j0);
-    const int ld = HW | 1;                                                // odd pitch: the transposed reads spread over the banks
-    const uint16_t *src = dY + (int64_t(n) * J + j0) * HW;
-    for (int i = threadIdx.x; i < jw * HW; i += 256) {
-        const int jj = i / HW, t = i - jj * HW;
-        slab[jj * ld + t] = src[i];
-    }
-    __syncthreads();
-    uint16_t *dst = dYt + int64_t(n) * HW * J + j0;
-    for (int i = threadIdx.x; i < HW * DYT_JB; i += 256) {
-        const int t = i / DYT_JB, jj = i % DYT_JB;
-        if (jj < jw) dst[int64_t(t) * J + jj] = slab[jj * ld + t];
-    }
-}
-
 }  // namespace
 
 ConvGemmPlan conv_gemm_plan(const ConvProblem &p)
@@ -135,8 +143,15 @@ ConvGemmPlan conv_gemm_plan(const ConvProblem &p)
     plan.fp = FcProblem{p.N * p.H * p.W, 9 * p.C, p.J, p.k};
     plan.gemm = fc_dense_plan(plan.fp);
     const int64_t HW = p.H * p.W;
-    // channel block: a multiple of 8, its tile within 64 KB of LDS where that leaves at least 8 channels
-    int64_t cb = (64 * 1024) / (HW * 18) / 8 * 8;
+    // channel block: a multiple of 8, its tile within the LDS budget where that leaves at least 8 channels
+    int64_t budget = 32 * 1024;                // several workgroups per compute unit (measured: 16-24 KB and 64+ KB slower)
+#ifdef DROPIT_TUNING
+    if (const char *e = getenv("DROPIT_IM2COL_LDS")) budget = atol(e);
+#endif
+    int64_t cb = budget / (HW * 18) / 8 * 8;
+    // ... but token segments of at least 16 channels (288 bytes) while the tile stays within 64 KB:
+    // with 8 (144 bytes, 2.25 lines) the writes of B were 3 us slower on 14x14 planes
+    if (cb < 16 && HW * 16 * 18 <= 64 * 1024) cb = 16;
     cb = std::max<int64_t>(8, std::min<int64_t>(cb, 64));
     cb = std::min<int64_t>(cb, p.C);
     plan.cb = int(cb);
@@ -188,13 +203,13 @@ dropit_status conv_gemm_run(const ConvProblem &p, const ConvGemmPlan &plan, cons
     const int units = int(p.N) * plan.cblocks;
     const int64_t pad_chunks = (ntok_pad - plan.fp.ntok) * plan.gemm.pitch / 8;
     const int pad_wgs = int(std::min<int64_t>((pad_chunks + IM2COL_THREADS - 1) / IM2COL_THREADS, 64));
-    conv_im2col_kernel<<<units + pad_wgs, IM2COL_THREADS, plan.lds_bytes, stream>>>(
-        static_cast<const uint16_t *>(vals), idx, p.k, int(p.N), int(p.C), int(p.H), int(p.W), plan.cb, plan.cblocks,
-        plan.gemm.pitch, plan.fp.ntok, ntok_pad, B);
-    trace_mark(stream);
     const int jblocks = int((p.J + DYT_JB - 1) / DYT_JB);
-    conv_dy_tokens_kernel<<<int(p.N) * jblocks, 256, size_t(DYT_JB) * (HW | 1) * 2, stream>>>(
-        static_cast<const uint16_t *>(dY), int(p.J), HW, jblocks, dYt);
+    // half-width of the pair window: 4 standard deviations of an evenly spread selection plus a little
+    const int64_t margin = 2 * static_cast<int64_t>(__builtin_sqrt(static_cast<double>(p.k))) + 256;
+    const size_t lds = std::max(plan.lds_bytes, size_t(DYT_JB) * (HW | 1) * 2);
+    conv_im2col_kernel<<<units + pad_wgs + int(p.N) * jblocks, IM2COL_THREADS, lds, stream>>>(
+        static_cast<const uint16_t *>(vals), idx, p.k, int(p.N), int(p.C), int(p.H), int(p.W), plan.cb, plan.cblocks,
+        plan.gemm.pitch, plan.fp.ntok, ntok_pad, pad_wgs, margin, B, static_cast<const uint16_t *>(dY), int(p.J), jblocks, dYt);
     trace_mark(stream);
     if (launch_status() != DROPIT_OK) return DROPIT_EHIP;
     return fc_dense_gemm(plan.fp, plan.gemm, dYt, B, partial, dW, stream);

@@ -58,13 +58,8 @@ constexpr int RECOVER_ELEMS_MAX = 32768;
 // search), so the rows are assembled in LDS (zero fill, one 16-bit store per pair)
 // and leave as full 16-byte stores: every byte of the dense matrix is written exactly
 // once, no separate zero-fill pass.
-// Where the pairs of a flat-index range start is first guessed, not searched: min-k keeps a fixed
-// fraction of the tensor, so the pair with flat index f sits near position f * k / numel, and if the
-// kept elements are spread evenly the guess is off by a few sqrt(k) at most.  The workgroup loads a
-// window of pairs around the guesses for both ends of its rows in ONE round of loads (values included),
-// checks with the loaded indices themselves that the window covers its rows, and scatters what
-// belongs to them.  Only if the window does not cover them (density that varies along the tensor) does
-// it fall back to the exact search, three dependent rounds of loads, and a second round for the pairs.
+// The pairs come through for_pairs_in_range: a window around the interpolated positions of the
+// rows' first and last flat index, one round of loads, with the exact search as the fallback.
 constexpr int RECOVER_WINDOW = 28;                    // window entries per thread, at most
 
 // (The host uses fc_recover_stream_kernel instead when the window would be several times the pairs a
@@ -94,67 +89,9 @@ fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__
         tile[pos] = static_cast<uint16_t>(v);
     };
 
-    // window of pairs around the interpolated positions of `first` and `last`
-    const int64_t g_lo = static_cast<int64_t>(static_cast<double>(first) * static_cast<double>(k) / static_cast<double>(numel));
-    const int64_t g_hi = static_cast<int64_t>(static_cast<double>(last) * static_cast<double>(k) / static_cast<double>(numel));
-    const int64_t w_lo = max<int64_t>(g_lo - margin, 0), w_hi = min<int64_t>(g_hi + margin, k);
-    const bool window_fits = w_hi - w_lo <= int64_t(RECOVER_WINDOW) * RECOVER_THREADS;
-    constexpr int WN = RECOVER_WINDOW;
-    int32_t wi[WN];
-    uint32_t wv[WN];        // a full register each: 16-bit destinations get packed in pairs, and the second load
-                            // of a pair then waits for the first
-    if (window_fits) {
-#pragma unroll
-        for (int u = 0; u < WN; ++u) {
-            const int64_t j = w_lo + int64_t(u) * RECOVER_THREADS + tid;
-            if (j < w_hi) {
-                wi[u] = idx[j];
-                wv[u] = vals[j];
-            }
-        }
-    }
-    for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
-    // the window covers the rows iff nothing of them can lie before its first or after its last entry
-    bool uncovered = !window_fits;
-    if (window_fits && tid == 0) {
-        if (w_lo > 0 && w_lo < w_hi && int64_t(wi[0]) >= first) uncovered = true;
-        if (w_lo > 0 && w_lo >= w_hi) uncovered = first < last;       // empty window in the middle of the array
-    }
-    if (window_fits && w_hi < k) {
-        const int64_t j_last = w_hi - 1;                              // held by thread (j_last - w_lo) % THREADS, slot / THREADS
-        if (j_last >= w_lo && (j_last - w_lo) % RECOVER_THREADS == tid) {
-            bool short_of_end = false;
-#pragma unroll
-            for (int u = 0; u < WN; ++u)
-                if ((j_last - w_lo) / RECOVER_THREADS == u) short_of_end = int64_t(wi[u]) < last;
-            uncovered = uncovered || short_of_end;
-        }
-    }
-    if (__syncthreads_or(uncovered)) {                                // also orders the zero fill before the scatter
-        int64_t lo, hi;
-        block_lower_bound2<RECOVER_THREADS>(idx, first, last, 0, k, 0, k, lo, hi);
-        // eight pairs per thread at a time: their loads are all in flight before the first LDS store
-        constexpr int BATCH = 8;
-        for (int64_t j0 = lo + tid; j0 < hi; j0 += int64_t(BATCH) * RECOVER_THREADS) {
-            int32_t pi[BATCH];
-            uint32_t pv[BATCH];
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
-                if (j < hi) {
-                    pi[u] = idx[j];
-                    pv[u] = vals[j];
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u)
-                if (j0 + int64_t(u) * RECOVER_THREADS < hi) place(pi[u], pv[u]);
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < WN; ++u)
-            if (w_lo + int64_t(u) * RECOVER_THREADS + tid < w_hi) place(wi[u], wv[u]);
-    }
+    for_pairs_in_range<RECOVER_THREADS, RECOVER_WINDOW>(vals, idx, k, numel, first, last, margin, place, [&] {
+        for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
+    });
     __syncthreads();
     u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
     for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];

@@ -193,6 +193,29 @@ def test_conv3x3_matrix_core_paths_widths_and_image_groups(N, C, H, W, J, path):
     assert_close(got, ref, TOL["bf16"])
 
 
+@pytest.mark.parametrize("layout", ["dead_channels", "late_images", "one_image"])
+def test_conv3x3_gemm_form_uneven_density(layout):
+    """The im2col kernel guesses where a block's pairs sit from an even spread and verifies the guess:
+    tensors whose kept elements bunch up (dead channels, a few bright images) take its search instead."""
+    N, C, H, W, J = 32, 256, 7, 7, 128
+    print("wgrad conv gemm density", layout, flush=True)
+    rng = np.random.default_rng(len(layout))
+    xf = np.maximum(rng.standard_normal((N, C, H, W), dtype=np.float32), 0)
+    if layout == "dead_channels":
+        xf[:, (np.arange(C) // 24) % 2 == 0] *= 1e-3
+    elif layout == "late_images":
+        xf[: int(0.7 * N)] *= 1e-3
+    else:
+        xf[np.arange(N) != 5] *= 1e-3
+    x = f32_to_bf16_bits(xf)
+    dy = gradient((N, J, H, W), 0.02, 77, "bf16")
+    k = oracle.keep_count(x.size, 0.9)
+    assert dropit.weight_grad_path(x.shape, torch.bfloat16, k, J, conv=CONV3) == "conv_gemm"
+    got, _, _ = gpu_dw(x, dy, 0.9, J, conv=CONV3)
+    ref = oracle.dw_conv(ref_xhat(x, 0.9), oracle.widen(dy), 3, 3, (1, 1), (1, 1))
+    assert_close(got, ref, TOL["bf16"])
+
+
 def test_conv3x3_integer_values_are_exact():
     rng = np.random.default_rng(6)
     x = f32_to_bf16_bits(rng.integers(-3, 4, (2, 16, 28, 28)).astype(np.float32))
