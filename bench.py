@@ -208,7 +208,7 @@ def main():
     n_c = 2
     path = dropit.weight_grad_path(w.x_shape, xs[0].dtype, k, w.c_out, conv)      # which kernels the library runs
     fc_mfma = path == "fc_mfma"
-    conv_gemm = path == "conv_gemm"
+    conv_gemm = path in ("conv_gemm", "conv_im2col")      # operand preparation, then the fully-connected GEMM
     conv_mfma = path == "conv_bands"
     conv_padded = conv_mfma and w.x_shape[3] % 8 != 0       # one more kernel: the zero-padded copy of dY
     mfma = fc_mfma or conv_mfma or conv_gemm
@@ -220,7 +220,8 @@ def main():
     g_med = np.median(g_ms, axis=0)
     c_names = ["select_fused"]
     g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
-               ["im2col_recover_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if conv_gemm else
+               ["im2col_recover_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if path == "conv_gemm" else
+               ["im2col_rows_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if conv_gemm else
                ["row_starts", "pad_dY", "mfma_conv", "partial_reduce"] if conv_padded else
                ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())

@@ -101,6 +101,16 @@ EXTRA_WORKLOADS = {
                                   1008, 2008, conv=(3, 3, 1, 1)),
     "resnet_conv3x3_7": Workload("resnet_conv3x3_7", "bf16", (64, 512, 7, 7), "relu", 0.8, 512, 0.02,
                                  1009, 2009, conv=(3, 3, 1, 1)),
+    # other geometries of the same networks: a bottleneck's 1x1, the strided 3x3 that opens a stage,
+    # ResNet's first layer (on the normalised image), ViT's patch embedding
+    "resnet_conv1x1": Workload("resnet_conv1x1", "bf16", (64, 256, 56, 56), "relu", 0.8, 64, 0.02,
+                               1010, 2010, conv=(1, 1, 1, 0)),
+    "resnet_conv3x3_s2": Workload("resnet_conv3x3_s2", "bf16", (64, 128, 56, 56), "relu", 0.8, 128, 0.02,
+                                  1011, 2011, conv=(3, 3, 2, 1)),
+    "resnet_conv7x7_s2": Workload("resnet_conv7x7_s2", "bf16", (64, 3, 224, 224), "normal", 0.8, 64, 0.02,
+                                  1012, 2012, conv=(7, 7, 2, 3)),
+    "vit_patch_embed": Workload("vit_patch_embed", "bf16", (64, 3, 224, 224), "normal", 0.8, 768, 0.02,
+                                1013, 2013, conv=(16, 16, 16, 0)),
 }
 
 

@@ -133,7 +133,8 @@ typedef enum {
     DROPIT_PATH_FC_MFMA = 1,        /* recover + split-K bf16 MFMA GEMM */
     DROPIT_PATH_CONV_BANDS = 2,     /* 3x3/s1/p1 bf16: row bands in LDS, implicit im2col on the matrix cores */
     DROPIT_PATH_CONV_GEMM = 3,      /* 3x3/s1/p1 bf16, small planes with many channels: explicit im2col rows + the FC GEMM */
-    DROPIT_PATH_FMA = 4             /* exact fp32 multiply-add kernels (fp32 inputs, odd shapes, other geometries) */
+    DROPIT_PATH_FMA = 4,            /* exact fp32 multiply-add kernels (fp32 inputs, odd shapes) */
+    DROPIT_PATH_CONV_IM2COL = 5     /* bf16, any geometry and either layout: zero-filled im2col rows written from the pairs + the FC GEMM */
 } dropit_wgrad_path;
 dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,
                                           int64_t c_out, const dropit_conv2d *conv);
@@ -153,10 +154,11 @@ dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, drop
  *     OH = (H + 2*pad_h - dil_h*(kh-1) - 1)/stride_h + 1 (OW alike), type dt
  *     dW  [c_out, C, kh, kw] fp32:
  *     dW[j][c][u][v] = sum_{n,oy,ox} dY[n][j][oy][ox] * R(a^)[n][c][oy*sh-ph+u*dh][ox*sw-pw+v*dw]
- *     bf16 with kh = kw = 3, stride 1, pad 1, dilation 1 (and W <= 120)
- *     runs on the matrix cores (in one of two forms, see dropit_weight_grad_path);
- *     every other geometry (kernel extents up to 1024,
- *     stride / pad / dilation up to 65535) takes an exact but slow fp32 kernel.
+ *     bf16 with c_out % 8 == 0 and C*kh*kw <= 32768 runs on the matrix cores
+ *     (3x3 / stride 1 / pad 1 in forms of its own, every other geometry through
+ *     explicit im2col rows in the workspace, at most 1 GiB of them; see
+ *     dropit_weight_grad_path); fp32 and the remaining shapes (kernel extents up
+ *     to 1024, stride / pad / dilation up to 65535) take an exact but slow fp32 kernel.
  *     DROPIT_EINVAL if the window does not fit the padded input.
  *
  *   vals, idx [in]  device, the k pairs written by dropit_compress for a tensor
@@ -174,6 +176,23 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
                                  const void *dY, int64_t c_out, const dropit_conv2d *conv,
                                  float *dW, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
+
+/*
+ * The same weight gradient for channels-last tensors (Sec. 3.2, Eq. conv_backward_elem; the
+ * paper's method does not depend on the memory layout, the flat indices of dropit_compress
+ * simply index the NHWC tensor):
+ *     x_shape = [N, H, W, C] (4 extents),  dY [N, OH, OW, c_out],  conv != NULL
+ *     dW [c_out, kh, kw, C] fp32 (the channels-last layout of a [c_out, C, kh, kw] weight)
+ * Everything else (arguments, alignment, workspace, errors, arithmetic) as for
+ * dropit_weight_grad; bf16 with c_out % 8 == 0 runs on the matrix cores (DROPIT_PATH_CONV_IM2COL).
+ */
+dropit_wgrad_path dropit_weight_grad_nhwc_path(const int64_t *x_shape, dropit_dtype dt, int64_t k, int64_t c_out,
+                                               const dropit_conv2d *conv);
+size_t dropit_weight_grad_nhwc_workspace_bytes(const int64_t *x_shape, dropit_dtype dt, int64_t k, int64_t c_out,
+                                               const dropit_conv2d *conv);
+dropit_status dropit_weight_grad_nhwc(const void *vals, const int32_t *idx, int64_t k, const int64_t *x_shape,
+                                      dropit_dtype dt, const void *dY, int64_t c_out, const dropit_conv2d *conv,
+                                      float *dW, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Row form of the cache: cheaper indices (Sec. 5 counts the indices as the

@@ -73,6 +73,12 @@ def lib() -> ctypes.CDLL:
         L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
         L.dropit_weight_grad_path.restype = i32
         L.dropit_weight_grad_path.argtypes = [p64, i32, i32, i64, i64, pconv]
+        L.dropit_weight_grad_nhwc_path.restype = i32
+        L.dropit_weight_grad_nhwc_path.argtypes = [p64, i32, i64, i64, pconv]
+        L.dropit_weight_grad_nhwc_workspace_bytes.restype = sz
+        L.dropit_weight_grad_nhwc_workspace_bytes.argtypes = [p64, i32, i64, i64, pconv]
+        L.dropit_weight_grad_nhwc.restype = i32
+        L.dropit_weight_grad_nhwc.argtypes = [vp, vp, i64, p64, i32, vp, i64, pconv, vp, vp, sz, vp]
         L.dropit_set_select_mode.restype = i32
         L.dropit_set_select_mode.argtypes = [i32]
         L.dropit_trace_events.restype = None
@@ -187,53 +193,78 @@ def compress_random(x: torch.Tensor, gamma: float, seed: int, vals: Optional[tor
     return vals[:k], idx[:k]
 
 
+def _nhwc(layout: str, x_shape, cs) -> bool:
+    if layout not in ("nchw", "nhwc"):
+        raise ValueError("layout must be 'nchw' or 'nhwc'")
+    if layout == "nhwc" and (cs is None or len(x_shape) != 4):
+        raise ValueError("the channels-last layout is for convolutions: 4-d x_shape and conv=...")
+    return layout == "nhwc"
+
+
 def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int,
-                                conv=None) -> int:
+                                conv=None, layout: str = "nchw") -> int:
     cs = _conv_struct(conv)
+    pc = ctypes.byref(cs) if cs is not None else None
+    if _nhwc(layout, x_shape, cs):
+        return int(lib().dropit_weight_grad_nhwc_workspace_bytes(
+            _shape_array(x_shape), _dtype_code(dtype), int(k), int(c_out), pc))
     return int(lib().dropit_weight_grad_workspace_bytes(
-        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out),
-        ctypes.byref(cs) if cs is not None else None))
+        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out), pc))
 
 
-WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma"}
+WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma", 5: "conv_im2col"}
 
 
-def weight_grad_path(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int, conv=None) -> str:
+def weight_grad_path(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int, conv=None,
+                     layout: str = "nchw") -> str:
     """dropit_weight_grad_path: which kernels ``weight_grad`` runs for these arguments."""
     cs = _conv_struct(conv)
+    pc = ctypes.byref(cs) if cs is not None else None
+    if _nhwc(layout, x_shape, cs):
+        return WGRAD_PATHS[int(lib().dropit_weight_grad_nhwc_path(
+            _shape_array(x_shape), _dtype_code(dtype), int(k), int(c_out), pc))]
     return WGRAD_PATHS[int(lib().dropit_weight_grad_path(
-        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out),
-        ctypes.byref(cs) if cs is not None else None))]
+        _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out), pc))]
 
 
 def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], dY: torch.Tensor,
                 c_out: int, conv=None, dW: Optional[torch.Tensor] = None,
-                workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                workspace: Optional[torch.Tensor] = None, stream=None, layout: str = "nchw") -> torch.Tensor:
     """dropit_weight_grad: dW (fp32) from the (vals, idx) pair of a tensor of ``x_shape``.
     ``conv`` is None for a fully-connected layer, else (kh, kw, stride_h, stride_w, pad_h,
-    pad_w, dil_h, dil_w)."""
+    pad_w, dil_h, dil_w).  ``layout="nhwc"`` (dropit_weight_grad_nhwc): x_shape = [N, H, W, C],
+    dY [N, OH, OW, c_out], dW [c_out, kh, kw, C]."""
     _require_device(vals, idx, dY, dW, workspace)
     code = _dtype_code(dY.dtype)
     if vals.dtype != dY.dtype or idx.dtype != torch.int32:
         raise ValueError("vals must have dY's dtype and idx must be int32")
     cs = _conv_struct(conv)
     x_shape = [int(s) for s in x_shape]
+    nhwc = _nhwc(layout, x_shape, cs)
     if dW is None:
         if cs is None:
             dw_shape = (int(c_out), x_shape[-1])
+        elif nhwc:
+            dw_shape = (int(c_out), cs.kh, cs.kw, x_shape[3])
         else:
             dw_shape = (int(c_out), x_shape[1], cs.kh, cs.kw)
         dW = torch.empty(dw_shape, dtype=torch.float32, device=dY.device)
     k = int(vals.numel())
     if workspace is None:
-        workspace = torch.empty(max(weight_grad_workspace_bytes(x_shape, dY.dtype, k, c_out, cs), 1),
+        workspace = torch.empty(max(weight_grad_workspace_bytes(x_shape, dY.dtype, k, c_out, cs, layout), 1),
                                 dtype=torch.uint8, device=dY.device)
+    pc = ctypes.byref(cs) if cs is not None else None
     with torch.cuda.device(dY.device):
-        _check(lib().dropit_weight_grad(
-            vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
-            _shape_array(x_shape), len(x_shape), code, dY.data_ptr(), int(c_out),
-            ctypes.byref(cs) if cs is not None else None, dW.data_ptr(),
-            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+        if nhwc:
+            _check(lib().dropit_weight_grad_nhwc(
+                vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
+                _shape_array(x_shape), code, dY.data_ptr(), int(c_out), pc, dW.data_ptr(),
+                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+        else:
+            _check(lib().dropit_weight_grad(
+                vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
+                _shape_array(x_shape), len(x_shape), code, dY.data_ptr(), int(c_out), pc, dW.data_ptr(),
+                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dW
 
 

@@ -145,16 +145,21 @@ conv3x3_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int
 // the workgroup adds them up in a fixed tree, so the result is reproducible.  Slow (the data is
 // walked once per 16 taps) but exact, for the geometries the matrix-core kernel does not take.
 constexpr int TAP_CHUNK = 16;
+// Element strides of the two layouts: x and dY as (image, channel, row, column), dW as (filter, channel, tap).
+struct ConvStrides {
+    int64_t xn, xc, xh, xw, yn, yc, yh, yw, wj, wc, wt;
+};
+
 template <typename RAW>
 __global__ void __launch_bounds__(256)
 conv_general_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int N, int C, int H, int W, int cout,
                         int OH, int OW, int kh, int kw, int sh, int sw, int ph, int pw, int dh, int dw,
-                        float *__restrict__ dW)
+                        ConvStrides st, float *__restrict__ dW)
 {
     __shared__ float red[256][TAP_CHUNK + 1];
     const int j = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
     const int taps = kh * kw;
-    const int64_t oplane = int64_t(OH) * OW, iplane = int64_t(H) * W;
+    const int64_t oplane = int64_t(OH) * OW;
     const int64_t positions = int64_t(N) * oplane;
     for (int t0 = 0; t0 < taps; t0 += TAP_CHUNK) {
         float acc[TAP_CHUNK];
@@ -164,15 +169,16 @@ conv_general_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY
             const int n = int(p / oplane);
             const int r = int(p - int64_t(n) * oplane);
             const int oy = r / OW, ox = r - oy * OW;
-            const float g = to_f32(dY[(int64_t(n) * cout + j) * oplane + r]);
-            const RAW *xp = xhat + (int64_t(n) * C + c) * iplane;
+            const float g = to_f32(dY[n * st.yn + j * st.yc + oy * st.yh + ox * st.yw]);
+            const RAW *xp = xhat + n * st.xn + c * st.xc;
 #pragma unroll
             for (int q = 0; q < TAP_CHUNK; ++q) {
                 const int tap = t0 + q;                         // uniform
                 if (tap < taps) {
                     const int u = tap / kw, v = tap - u * kw;
                     const int64_t iy = int64_t(oy) * sh - ph + int64_t(u) * dh, ix = int64_t(ox) * sw - pw + int64_t(v) * dw;
-                    if (iy >= 0 && iy < H && ix >= 0 && ix < W) acc[q] = __builtin_fmaf(g, to_f32(xp[iy * W + ix]), acc[q]);
+                    if (iy >= 0 && iy < H && ix >= 0 && ix < W)
+                        acc[q] = __builtin_fmaf(g, to_f32(xp[iy * st.xh + ix * st.xw]), acc[q]);
                 }
             }
         }
@@ -185,7 +191,7 @@ conv_general_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY
                 for (int q = 0; q < TAP_CHUNK; ++q) red[tid][q] += red[tid + s][q];
             __syncthreads();
         }
-        if (tid < TAP_CHUNK && t0 + tid < taps) dW[(int64_t(j) * C + c) * taps + t0 + tid] = red[0][tid];
+        if (tid < TAP_CHUNK && t0 + tid < taps) dW[j * st.wj + c * st.wc + (t0 + tid) * st.wt] = red[0][tid];
         __syncthreads();
     }
 }
@@ -196,12 +202,14 @@ struct Problem {
     int64_t N, C, H, W, OH, OW;
     dropit_conv2d g;
     bool is_3x3_s1_p1;
+    bool nhwc;                                   // x [N][H][W][C], dY [N][OH][OW][J], dW [J][kh][kw][C]
 };
 
 // Validates shape arguments; returns DROPIT_OK and fills `p`.
 dropit_status describe(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t c_out,
-                       const dropit_conv2d *conv, Problem &p)
+                       const dropit_conv2d *conv, Problem &p, bool nhwc = false)
 {
+    p.nhwc = nhwc;
     if (dt != DROPIT_F32 && dt != DROPIT_BF16) return DROPIT_EINVAL;
     p.numel = checked_numel(x_shape, ndim);
     if (p.numel < 1 || c_out < 1 || c_out > INT32_MAX) return DROPIT_EINVAL;
@@ -223,7 +231,12 @@ dropit_status describe(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_
     p.g = *conv;
     p.is_3x3_s1_p1 = conv->kh == 3 && conv->kw == 3 && conv->stride_h == 1 && conv->stride_w == 1 && conv->pad_h == 1 &&
                      conv->pad_w == 1 && conv->dil_h == 1 && conv->dil_w == 1;
-    p.N = x_shape[0]; p.C = x_shape[1]; p.H = x_shape[2]; p.W = x_shape[3];
+    p.N = x_shape[0];
+    if (nhwc) {
+        p.H = x_shape[1]; p.W = x_shape[2]; p.C = x_shape[3];
+    } else {
+        p.C = x_shape[1]; p.H = x_shape[2]; p.W = x_shape[3];
+    }
     constexpr int64_t GEOM_MAX = 65535;              // keeps every index expression far inside 64 bits
     if (conv->kh > 1024 || conv->kw > 1024 || conv->pad_h > GEOM_MAX || conv->pad_w > GEOM_MAX ||
         conv->stride_h > GEOM_MAX || conv->stride_w > GEOM_MAX || conv->dil_h > GEOM_MAX || conv->dil_w > GEOM_MAX)
@@ -261,14 +274,18 @@ dropit_status run_generic(const Problem &p, const void *vals, const int32_t *idx
                                                       int(p.cout), dW);
     } else {
         const dim3 grid(p.C, p.cout);
-        if (p.is_3x3_s1_p1)
+        const int64_t taps = p.g.kh * p.g.kw;
+        const ConvStrides st = p.nhwc
+            ? ConvStrides{p.H * p.W * p.C, 1, p.W * p.C, p.C, p.OH * p.OW * p.cout, 1, p.OW * p.cout, p.cout, taps * p.C, 1, p.C}
+            : ConvStrides{p.C * p.H * p.W, p.H * p.W, p.W, 1, p.cout * p.OH * p.OW, p.OH * p.OW, p.OW, 1, p.C * taps, taps, 1};
+        if (p.is_3x3_s1_p1 && !p.nhwc)
             conv3x3_fma_kernel<RAW><<<grid, 256, 0, stream>>>(dense, static_cast<const RAW *>(dY), int(p.N), int(p.C),
                                                                int(p.H), int(p.W), int(p.cout), dW);
         else
             conv_general_fma_kernel<RAW><<<grid, 256, 0, stream>>>(
                 dense, static_cast<const RAW *>(dY), int(p.N), int(p.C), int(p.H), int(p.W), int(p.cout), int(p.OH),
                 int(p.OW), int(p.g.kh), int(p.g.kw), int(p.g.stride_h), int(p.g.stride_w), int(p.g.pad_h),
-                int(p.g.pad_w), int(p.g.dil_h), int(p.g.dil_w), dW);
+                int(p.g.pad_w), int(p.g.dil_h), int(p.g.dil_w), st, dW);
     }
     trace_mark(stream);
     return launch_status();
@@ -281,31 +298,74 @@ using namespace dropit;
 
 static bool use_fc_dense(const FcProblem &fp) { return fc_dense_supported(fp); }
 
-// which matrix-core path a 3x3/s1/p1 bf16 convolution takes: 2 im2col GEMM, 1 row-band kernel, 0 neither
-static int conv_path(const ConvProblem &cp)
+static ConvGeneral general_of(const Problem &p, int64_t k)
 {
-    bool gemm = conv_gemm_preferred(cp);
+    return ConvGeneral{p.N, p.C, p.H, p.W, p.OH, p.OW, p.cout, k, p.g, p.nhwc};
+}
+
+// Which kernels serve this problem.
+static dropit_wgrad_path choose_path(const Problem &p, dropit_dtype dt, int64_t k)
+{
+    if (dt != DROPIT_BF16) return DROPIT_PATH_FMA;
+    if (!p.conv) return use_fc_dense(FcProblem{p.ntok, p.cin, p.cout, k}) ? DROPIT_PATH_FC_MFMA : DROPIT_PATH_FMA;
+    if (p.is_3x3_s1_p1 && !p.nhwc) {
+        const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
+        bool gemm = conv_gemm_preferred(cp);
 #ifdef DROPIT_TUNING
-    if (const char *e = getenv("DROPIT_CONV_PATH")) gemm = e[0] == 'g' && conv_gemm_supported(cp);
+        if (const char *e = getenv("DROPIT_CONV_PATH")) gemm = e[0] == 'g' && conv_gemm_supported(cp);
 #endif
-    if (gemm) return 2;
-    return conv_mfma_supported(cp) ? 1 : 0;
+        if (gemm) return DROPIT_PATH_CONV_GEMM;
+        if (conv_mfma_supported(cp)) return DROPIT_PATH_CONV_BANDS;
+    }
+    return conv_im2col_supported(general_of(p, k)) ? DROPIT_PATH_CONV_IM2COL : DROPIT_PATH_FMA;
 }
 
 // Workspace need of the path dropit_weight_grad will take for this problem.
 static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
 {
-    if (!p.conv && dt == DROPIT_BF16) {
+    const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
+    switch (choose_path(p, dt, k)) {
+    case DROPIT_PATH_FC_MFMA: return fc_dense_plan(FcProblem{p.ntok, p.cin, p.cout, k}).total();
+    case DROPIT_PATH_CONV_GEMM: return conv_gemm_plan(cp).total();
+    case DROPIT_PATH_CONV_BANDS: return conv_mfma_plan(cp).total();
+    case DROPIT_PATH_CONV_IM2COL: return conv_im2col_plan(general_of(p, k)).total();
+    default: return dense_bytes(p, dt);
+    }
+}
+
+static dropit_status run(const Problem &p, const void *vals, const int32_t *idx, int64_t k, dropit_dtype dt,
+                         const void *dY, float *dW, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (k < 0 || k > p.numel) return DROPIT_EINVAL;
+    if (k > 0 && (vals == nullptr || idx == nullptr)) return DROPIT_EINVAL;
+    if (k > 0 && (!aligned(vals, dt == DROPIT_F32 ? 4 : 2) || !aligned(idx, 4))) return DROPIT_EINVAL;
+    if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
+    if (workspace == nullptr || !aligned(workspace, 256)) return DROPIT_EINVAL;
+    const size_t need = workspace_need(p, dt, k);
+    if (workspace_bytes < need) return DROPIT_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    if (k == 0) {                                  // everything was dropped: R(a^) = 0, so dW = 0
+        const int64_t n = p.conv ? p.cout * p.C * p.g.kh * p.g.kw : p.cout * p.cin;
+        zero_f32_kernel<<<int(std::min<int64_t>((n + 255) / 256, 2048)), 256, 0, stream>>>(dW, n);
+        return launch_status();
+    }
+    const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
+    switch (choose_path(p, dt, k)) {
+    case DROPIT_PATH_FC_MFMA: {
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
-        if (use_fc_dense(fp)) return fc_dense_plan(fp).total();
+        return fc_dense_run(fp, fc_dense_plan(fp), vals, idx, dY, dW, ws, stream);
     }
-    if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16) {
-        const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
-        const int path = conv_path(cp);
-        if (path == 2) return conv_gemm_plan(cp).total();
-        if (path == 1) return conv_mfma_plan(cp).total();
+    case DROPIT_PATH_CONV_GEMM: return conv_gemm_run(cp, conv_gemm_plan(cp), vals, idx, dY, dW, ws, stream);
+    case DROPIT_PATH_CONV_BANDS: return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
+    case DROPIT_PATH_CONV_IM2COL: {
+        const ConvGeneral cg = general_of(p, k);
+        return conv_im2col_run(cg, conv_im2col_plan(cg), vals, idx, dY, dW, ws, stream);
     }
-    return dense_bytes(p, dt);
+    default: break;
+    }
+    if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
+    return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);
 }
 
 extern "C" dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,
@@ -314,13 +374,7 @@ extern "C" dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int
     Problem p;
     if (describe(x_shape, ndim, dt, c_out, conv, p) != DROPIT_OK) return DROPIT_PATH_NONE;
     if (k < 0 || k > p.numel) return DROPIT_PATH_NONE;
-    if (!p.conv && dt == DROPIT_BF16 && use_fc_dense(FcProblem{p.ntok, p.cin, p.cout, k})) return DROPIT_PATH_FC_MFMA;
-    if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16) {
-        const int path = conv_path(ConvProblem{p.N, p.C, p.H, p.W, p.cout, k});
-        if (path == 2) return DROPIT_PATH_CONV_GEMM;
-        if (path == 1) return DROPIT_PATH_CONV_BANDS;
-    }
-    return DROPIT_PATH_FMA;
+    return choose_path(p, dt, k);
 }
 
 extern "C" size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
@@ -340,30 +394,36 @@ extern "C" dropit_status dropit_weight_grad(const void *vals, const int32_t *idx
     Problem p;
     const dropit_status st = describe(x_shape, ndim, dt, c_out, conv, p);
     if (st != DROPIT_OK) return st;
-    if (k < 0 || k > p.numel) return DROPIT_EINVAL;
-    if (k > 0 && (vals == nullptr || idx == nullptr)) return DROPIT_EINVAL;
-    if (k > 0 && (!aligned(vals, dt == DROPIT_F32 ? 4 : 2) || !aligned(idx, 4))) return DROPIT_EINVAL;
-    if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
-    if (workspace == nullptr || !aligned(workspace, 256)) return DROPIT_EINVAL;
-    const size_t need = workspace_need(p, dt, k);
-    if (workspace_bytes < need) return DROPIT_EWORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    char *ws = static_cast<char *>(workspace);
-    if (k == 0) {                                  // everything was dropped: R(a^) = 0, so dW = 0
-        const int64_t n = p.conv ? p.cout * p.C * p.g.kh * p.g.kw : p.cout * p.cin;
-        zero_f32_kernel<<<int(std::min<int64_t>((n + 255) / 256, 2048)), 256, 0, stream>>>(dW, n);
-        return launch_status();
-    }
-    if (!p.conv && dt == DROPIT_BF16 && k > 0) {
-        const FcProblem fp = {p.ntok, p.cin, p.cout, k};
-        if (use_fc_dense(fp)) return fc_dense_run(fp, fc_dense_plan(fp), vals, idx, dY, dW, ws, stream);
-    }
-    if (p.conv && p.is_3x3_s1_p1 && dt == DROPIT_BF16 && k > 0) {
-        const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
-        const int path = conv_path(cp);
-        if (path == 2) return conv_gemm_run(cp, conv_gemm_plan(cp), vals, idx, dY, dW, ws, stream);
-        if (path == 1) return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
-    }
-    if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
-    return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);
+    return run(p, vals, idx, k, dt, dY, dW, workspace, workspace_bytes, hip_stream);
+}
+
+// ---- channels-last convolutions ------------------------------------------------
+extern "C" dropit_wgrad_path dropit_weight_grad_nhwc_path(const int64_t *x_shape, dropit_dtype dt, int64_t k,
+                                                          int64_t c_out, const dropit_conv2d *conv)
+{
+    Problem p;
+    if (conv == nullptr || describe(x_shape, 4, dt, c_out, conv, p, true) != DROPIT_OK) return DROPIT_PATH_NONE;
+    if (k < 0 || k > p.numel) return DROPIT_PATH_NONE;
+    return choose_path(p, dt, k);
+}
+
+extern "C" size_t dropit_weight_grad_nhwc_workspace_bytes(const int64_t *x_shape, dropit_dtype dt, int64_t k,
+                                                          int64_t c_out, const dropit_conv2d *conv)
+{
+    Problem p;
+    if (conv == nullptr || describe(x_shape, 4, dt, c_out, conv, p, true) != DROPIT_OK) return 0;
+    if (k < 0 || k > p.numel) return 0;
+    return workspace_need(p, dt, k);
+}
+
+extern "C" dropit_status dropit_weight_grad_nhwc(const void *vals, const int32_t *idx, int64_t k,
+                                                 const int64_t *x_shape, dropit_dtype dt, const void *dY,
+                                                 int64_t c_out, const dropit_conv2d *conv, float *dW,
+                                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (conv == nullptr) return DROPIT_EINVAL;
+    Problem p;
+    const dropit_status st = describe(x_shape, 4, dt, c_out, conv, p, true);
+    if (st != DROPIT_OK) return st;
+    return run(p, vals, idx, k, dt, dY, dW, workspace, workspace_bytes, hip_stream);
 }

@@ -63,4 +63,25 @@ ConvGemmPlan conv_gemm_plan(const ConvProblem &p);
 dropit_status conv_gemm_run(const ConvProblem &p, const ConvGemmPlan &plan, const void *vals, const int32_t *idx,
                             const void *dY, float *dW, char *ws, hipStream_t stream);
 
+// Any geometry, NCHW or NHWC, bf16: zero-filled im2col rows written from the pairs + the FC GEMM
+// (wgrad_conv_im2col.hip)
+struct ConvGeneral {
+    int64_t N, C, H, W, OH, OW, J, k;
+    dropit_conv2d g;
+    bool nhwc;
+};
+struct ConvIm2colPlan {
+    FcProblem fp;                              // tokens = N*OH*OW, c_in = C*kh*kw, c_out = J
+    FcDensePlan gemm;
+    size_t dyt_bytes;                          // token-major copy of dY (NCHW only)
+    bool tiled;                                // im2col rows assembled in LDS tiles (else zero fill + scatter)
+    int nblocks, blk, bands, rb, rowlen;       // tiled form: column blocks, their width, row bands, rows per band, tile row length
+    size_t lds_bytes, rowptr_bytes;
+    size_t total() const { return gemm.dense_bytes + gemm.partial_bytes + dyt_bytes + rowptr_bytes; }
+};
+bool conv_im2col_supported(const ConvGeneral &p);
+ConvIm2colPlan conv_im2col_plan(const ConvGeneral &p);
+dropit_status conv_im2col_run(const ConvGeneral &p, const ConvIm2colPlan &plan, const void *vals, const int32_t *idx,
+                              const void *dY, float *dW, char *ws, hipStream_t stream);
+
 }  // namespace dropit

@@ -157,7 +157,10 @@ class _Conv2dFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, weight, bias, stride, padding, dilation, gamma, seed, rows):
         y = F.conv2d(x, weight, bias, stride, padding, dilation, 1)
-        ctx.save_for_backward(weight, *_compress_input(x, gamma, seed, rows))
+        # a channels-last input is cached as it lies in memory ([N, H, W, C]) instead of being copied to NCHW
+        ctx.nhwc = (not rows and x.dim() == 4 and not x.is_contiguous()
+                    and x.is_contiguous(memory_format=torch.channels_last))
+        ctx.save_for_backward(weight, *_compress_input(x.permute(0, 2, 3, 1) if ctx.nhwc else x, gamma, seed, rows))
         ctx.x_shape = tuple(x.shape)
         ctx.geometry = (stride, padding, dilation)
         ctx.has_bias = bias is not None
@@ -173,7 +176,13 @@ class _Conv2dFn(torch.autograd.Function):
             dx = torch.nn.grad.conv2d_input(ctx.x_shape, weight.to(dy.dtype), dy, stride, padding, dilation, 1)
         if ctx.needs_input_grad[1]:
             conv = (kh, kw, stride[0], stride[1], padding[0], padding[1], dilation[0], dilation[1])
-            dw = _weight_grad(cache, ctx.x_shape, dy, c_out, conv=conv).to(weight.dtype)
+            if ctx.nhwc:
+                n, c, h, w = ctx.x_shape
+                dyl = _match_dtype(dy.permute(0, 2, 3, 1), cache[0])
+                dw = binding.weight_grad(cache[0], cache[1], (n, h, w, c), dyl, c_out, conv=conv, layout="nhwc")
+                dw = dw.permute(0, 3, 1, 2).to(weight.dtype)        # [J, C, kh, kw] with channels-last strides
+            else:
+                dw = _weight_grad(cache, ctx.x_shape, dy, c_out, conv=conv).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy.sum((0, 2, 3))
         return dx, dw, db, None, None, None, None, None, None
@@ -182,9 +191,10 @@ class _Conv2dFn(torch.autograd.Function):
 def conv2d(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] = None,
            stride: _Int2 = 1, padding: _Int2 = 0, dilation: _Int2 = 1, gamma: float = 0.9,
            seed: Optional[int] = None, index_format: str = "flat") -> torch.Tensor:
-    """``F.conv2d`` (groups = 1, zero padding, NCHW) whose backward computes the weight gradient
+    """``F.conv2d`` (groups = 1, zero padding) whose backward computes the weight gradient
     from the min-k cache of ``x`` (from a random cache drawn with ``seed`` when one is given);
-    ``index_format`` as for ``linear``."""
+    ``index_format`` as for ``linear``.  A channels-last ``x`` is cached and multiplied in that
+    layout (flat index format)."""
     return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma), seed,
                            _check_format(index_format) == "rows")
 

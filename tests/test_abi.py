@@ -24,6 +24,7 @@ def test_header_declares_the_expected_entry_points():
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
         "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode",
         "dropit_weight_grad_path",
+        "dropit_weight_grad_nhwc_path", "dropit_weight_grad_nhwc_workspace_bytes", "dropit_weight_grad_nhwc",
         "dropit_compress_random_workspace_bytes", "dropit_compress_random",
         "dropit_compress_rows_workspace_bytes", "dropit_compress_rows",
         "dropit_weight_grad_rows_workspace_bytes", "dropit_weight_grad_rows"])
@@ -145,10 +146,39 @@ def test_weight_grad_path_of_the_benchmark_shapes():
     assert path((64, 64, 7, 7), bf, 1000, 64, conv=c3) == "conv_bands"  # few channels
     assert path((64, 516, 7, 7), bf, 1000, 512, conv=c3) == "conv_bands"  # channels not a multiple of 8
     assert path((64, 512, 7, 7), f32, 1000, 512, conv=c3) == "fma"
-    assert path((2, 3, 20, 22), bf, 100, 8, conv=(7, 7, 2, 2, 3, 3, 1, 1)) == "fma"
-    assert path((3, 16, 9, 1), bf, 10, 8, conv=c3) == "fma"             # a single column
+    assert path((2, 3, 20, 22), bf, 100, 8, conv=(7, 7, 2, 2, 3, 3, 1, 1)) == "conv_im2col"
+    assert path((2, 3, 20, 22), bf, 100, 5, conv=(7, 7, 2, 2, 3, 3, 1, 1)) == "fma"   # c_out not a multiple of 8
+    assert path((2, 3, 20, 22), f32, 100, 8, conv=(7, 7, 2, 2, 3, 3, 1, 1)) == "fma"
+    assert path((64, 3, 224, 224), bf, 1000, 768, conv=(16, 16, 16, 16, 0, 0, 1, 1)) == "conv_im2col"   # patch embedding
+    assert path((64, 256, 56, 56), bf, 1000, 64, conv=(1, 1, 1, 1, 0, 0, 1, 1)) == "conv_im2col"
+    assert path((64, 4096, 7, 7), bf, 1000, 64, conv=(3, 3, 2, 2, 1, 1, 1, 1)) == "fma"   # C*kh*kw > 32768
+    assert path((64, 56, 56, 64), bf, 1000, 64, conv=c3, layout="nhwc") == "conv_im2col"
+    assert path((64, 56, 56, 64), f32, 1000, 64, conv=c3, layout="nhwc") == "fma"
+    assert path((64, 56, 56, 64), bf, -1, 64, conv=c3, layout="nhwc") == "none"
+    assert path((3, 16, 9, 1), bf, 10, 8, conv=c3) == "conv_im2col"     # a single column: not the row-band kernel
     assert path((64, 512, 7, 7), bf, -1, 512, conv=c3) == "none"
     assert path((1, 2, 4, 4), bf, 4, 2, conv=(7, 7, 1, 1, 0, 0, 1, 1)) == "none"
+
+
+def test_nhwc_entry_points_validate_arguments():
+    L = dropit.lib()
+    fake = ctypes.c_void_p(0x1000)
+    dw = ctypes.c_void_p(0x2000)
+    ws = ctypes.c_void_p(0x4000)
+    geom = binding.Conv2d(3, 3, 1, 1, 1, 1, 1, 1)
+    g = ctypes.byref(geom)
+    call = L.dropit_weight_grad_nhwc
+    shape = _shape(2, 8, 8, 16)
+    assert L.dropit_weight_grad_nhwc_workspace_bytes(shape, binding.BF16, 4, 8, g) > 0
+    assert L.dropit_weight_grad_nhwc_workspace_bytes(shape, binding.BF16, 4, 8, None) == 0
+    assert L.dropit_weight_grad_nhwc_workspace_bytes(shape, binding.BF16, 2 * 8 * 8 * 16 + 1, 8, g) == 0
+    assert call(fake, fake, 4, shape, binding.BF16, fake, 8, None, dw, ws, 1 << 30, None) == binding.EINVAL
+    assert call(fake, fake, 4, None, binding.BF16, fake, 8, g, dw, ws, 1 << 30, None) == binding.EINVAL
+    assert call(fake, None, 4, shape, binding.BF16, fake, 8, g, dw, ws, 1 << 30, None) == binding.EINVAL
+    assert call(fake, fake, 4, shape, binding.BF16, None, 8, g, dw, ws, 1 << 30, None) == binding.EINVAL
+    assert call(fake, fake, 4, shape, binding.BF16, fake, 8, g, dw, ws, 16, None) == binding.EWORKSPACE
+    big = binding.Conv2d(17, 3, 1, 1, 0, 0, 1, 1)                      # window taller than the input
+    assert call(fake, fake, 4, shape, binding.BF16, fake, 8, ctypes.byref(big), dw, ws, 1 << 30, None) == binding.EINVAL
 
 
 def test_select_mode_switch_validates():

@@ -86,6 +86,27 @@ def test_conv_layer_gradients(geometry):
     _close(layer.weight.grad.float().cpu().numpy().astype(np.float64), ref, TOL["bf16"] + 2.0 ** -8)
 
 
+def test_conv_layer_channels_last():
+    """A channels-last model: the cache is taken from the NHWC memory, dW comes back channels-last."""
+    print("autograd conv channels_last", flush=True)
+    x_h = activation((3, 16, 24, 24), "relu", 43, "bf16")
+    torch.manual_seed(5)
+    layer = dnn.Conv2d(16, 24, 3, 1, 1, gamma=0.8, device="cuda:0", dtype=torch.bfloat16).to(memory_format=torch.channels_last)
+    x = to_device(x_h).contiguous(memory_format=torch.channels_last).requires_grad_(True)
+    with dnn.cache_meter() as meter:
+        y = layer(x)
+    assert meter.layers == 1
+    dy_h = gradient(tuple(y.shape), 0.02, 44, "bf16")
+    y.backward(to_device(dy_h))
+    torch.cuda.synchronize()
+    # the selection runs over the tensor as it lies in memory, [N, H, W, C]
+    x_nhwc = np.ascontiguousarray(x_h.transpose(0, 2, 3, 1))
+    xhat = np.ascontiguousarray(_oracle_xhat(x_nhwc, 0.8).transpose(0, 3, 1, 2))
+    ref = oracle.dw_conv(xhat, oracle.widen(dy_h), 3, 3, stride=(1, 1), pad=(1, 1), dil=(1, 1))
+    assert layer.weight.grad.shape == (24, 16, 3, 3)
+    _close(layer.weight.grad.float().cpu().numpy().astype(np.float64), ref, TOL["bf16"] + 2.0 ** -8)
+
+
 def test_gamma_zero_and_eval_run_the_plain_layer():
     layer = dnn.Linear(32, 16, gamma=0.0, device="cuda:0")
     x = torch.randn(8, 32, device="cuda:0", requires_grad=True)

@@ -178,7 +178,7 @@ def test_conv3x3_shapes(dtype, N, C, H, W, J):
     (600, 64, 7, 7, 64, "conv_bands"),     # few channels: more (image, block) units than compute units
                                            # -> several images per workgroup
     (778, 64, 7, 7, 64, "conv_bands"),     # ... with a ragged last image group
-    (3, 16, 9, 1, 8, "fma"),               # a single column with few channels: the exact fp32 kernel
+    (3, 16, 9, 1, 8, "conv_im2col"),       # a single column with few channels: the general im2col form
     (3, 16, 9, 2, 8, "conv_bands"),        # two columns: the narrowest plane of the row-band kernel
     (2, 24, 10, 119, 16, "conv_bands"),    # the widest padded row (120)
 ])
@@ -246,6 +246,85 @@ def test_conv_general_geometries(dtype, N, C, H, W, J, geom):
     ref = oracle.dw_conv(ref_xhat(x, 0.6), oracle.widen(dy), kh, kw, (sh, sw), (ph, pw), (dh, dw))
     assert got.shape == (J, C, kh, kw)
     assert_close(got, ref, TOL[dtype])
+
+
+GEOMETRIES = [
+    ((2, 16, 9, 11), 24, (1, 1, 1, 1, 0, 0, 1, 1)),        # 1x1 (most of a ResNet-50's convolutions)
+    ((2, 3, 40, 44), 16, (7, 7, 2, 2, 3, 3, 1, 1)),        # 7x7 / stride 2 / pad 3 (first ResNet layer's geometry)
+    ((3, 8, 15, 14), 8, (3, 3, 2, 2, 1, 1, 1, 1)),         # 3x3 / stride 2
+    ((2, 3, 32, 48), 40, (16, 16, 16, 16, 0, 0, 1, 1)),    # 16x16 / stride 16 (ViT patch embedding)
+    ((1, 4, 13, 17), 8, (3, 2, 1, 2, 2, 0, 2, 3)),         # asymmetric kernel, stride, pad, dilation
+    ((2, 5, 12, 10), 16, (3, 3, 1, 1, 1, 1, 2, 2)),        # dilated 3x3
+    ((5, 24, 20, 20), 72, (3, 3, 1, 1, 1, 1, 1, 1)),       # 3x3 / stride 1 / pad 1 (channels-last only: NCHW has kernels of its own)
+    ((3, 20, 37, 23), 136, (5, 5, 3, 2, 2, 1, 1, 1)),      # more than 256 output positions per image, three filter blocks
+    ((2, 8, 6, 6), 8, (3, 3, 1, 1, 4, 4, 1, 1)),           # padding wider than the window: whole rows of taps see only zeros
+    ((128, 8, 18, 18), 8, (3, 3, 1, 1, 0, 0, 1, 1)),       # many images: bands of several output rows per im2col tile
+    ((2, 256, 9, 32), 16, (3, 3, 2, 2, 1, 1, 1, 1)),       # a row of tokens beyond one tile: blocks of channels (NCHW) / taps (NHWC), ragged last block
+    ((2, 20, 9, 300), 8, (5, 5, 1, 1, 2, 2, 1, 1)),        # ... with channels not a multiple of 8: zero fill + scatter instead of tiles
+]
+
+
+def _out_extent(n, k, s, p, d):
+    return (n + 2 * p - d * (k - 1) - 1) // s + 1
+
+
+@pytest.mark.parametrize("x_shape,J,geom", GEOMETRIES)
+def test_conv_general_geometries_on_the_matrix_cores(x_shape, J, geom):
+    """bf16 with c_out a multiple of 8: im2col rows written from the pairs + the fully-connected GEMM."""
+    kh, kw, sh, sw, ph, pw, dh, dw = geom
+    N, C, H, W = x_shape
+    if geom == CONV3:
+        pytest.skip("NCHW 3x3/s1/p1 has kernels of its own")
+    OH, OW = _out_extent(H, kh, sh, ph, dh), _out_extent(W, kw, sw, pw, dw)
+    print("wgrad conv im2col nchw", x_shape, J, geom, flush=True)
+    x = activation(x_shape, "relu", 700 + H + kh, "bf16")
+    dy = gradient((N, J, OH, OW), 0.02, 750 + W + kw, "bf16")
+    k = oracle.keep_count(x.size, 0.6)
+    assert dropit.weight_grad_path(x_shape, torch.bfloat16, k, J, conv=geom) == "conv_im2col"
+    got, _, _ = gpu_dw(x, dy, 0.6, J, conv=geom)
+    ref = oracle.dw_conv(ref_xhat(x, 0.6), oracle.widen(dy), kh, kw, (sh, sw), (ph, pw), (dh, dw))
+    assert got.shape == (J, C, kh, kw)
+    assert_close(got, ref, TOL["bf16"])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("x_shape,J,geom", GEOMETRIES)
+def test_conv_channels_last(dtype, x_shape, J, geom):
+    """x [N,H,W,C], dY [N,OH,OW,J] -> dW [J,kh,kw,C]; the oracle (NCHW) sees the same tensors permuted."""
+    kh, kw, sh, sw, ph, pw, dh, dw = geom
+    N, C, H, W = x_shape
+    OH, OW = _out_extent(H, kh, sh, ph, dh), _out_extent(W, kw, sw, pw, dw)
+    print("wgrad conv nhwc", dtype, x_shape, J, geom, flush=True)
+    x = activation((N, H, W, C), "relu", 800 + H + kh, dtype)
+    dy = gradient((N, OH, OW, J), 0.02, 850 + W + kw, dtype)
+    k = oracle.keep_count(x.size, 0.6)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    assert dropit.weight_grad_path(x.shape, tdt, k, J, conv=geom, layout="nhwc") == \
+        ("conv_im2col" if dtype == "bf16" else "fma")
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, 0.6)
+    dW = dropit.weight_grad(vals, idx, x.shape, dyd, J, conv=geom, layout="nhwc")
+    torch.cuda.synchronize()
+    got = to_host(dW).astype(np.float64)
+    assert got.shape == (J, kh, kw, C)
+    xhat = np.ascontiguousarray(ref_xhat(x, 0.6).transpose(0, 3, 1, 2))          # selection on the NHWC tensor, then NCHW
+    dy_nchw = np.ascontiguousarray(oracle.widen(dy).transpose(0, 3, 1, 2))
+    ref = oracle.dw_conv(xhat, dy_nchw, kh, kw, (sh, sw), (ph, pw), (dh, dw)).transpose(0, 2, 3, 1)
+    assert_close(got, ref, TOL[dtype])
+
+
+def test_conv_channels_last_everything_dropped_and_bad_layout():
+    x = activation((2, 6, 6, 8), "relu", 1, "bf16")
+    dy = gradient((2, 6, 6, 8), 0.02, 2, "bf16")
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, 1.0)
+    dW = dropit.weight_grad(vals, idx, x.shape, dyd, 8, conv=CONV3, layout="nhwc")
+    torch.cuda.synchronize()
+    assert dW.shape == (8, 3, 3, 8) and not dW.any()
+    with pytest.raises(ValueError):
+        dropit.weight_grad(vals, idx, x.shape, dyd, 8, conv=None, layout="nhwc")
+    with pytest.raises(ValueError):
+        dropit.weight_grad(vals, idx, x.shape, dyd, 8, conv=CONV3, layout="chwn")
 
 
 def test_conv_window_larger_than_input_is_rejected():
