@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vitb_fc1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layout", choices=["nchw", "nhwc"], default="nchw",
+                    help="convolution workloads only: run on channels-last tensors (x [N,H,W,C], dY [N,OH,OW,J], "
+                         "dW [J,kh,kw,C]) through dropit_weight_grad_nhwc; the CPU baseline is skipped")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--vendor-gemm", action="store_true",
@@ -116,6 +119,16 @@ def main():
     torch.cuda.set_device(dev)
     w = {**WORKLOADS, **EXTRA_WORKLOADS}[args.workload]
     xh, dyh = make(w)
+    nhwc = args.layout == "nhwc"
+    if nhwc and w.conv is None:
+        print("bench.py: --layout nhwc is for the convolution workloads.", file=sys.stderr)
+        sys.exit(2)
+    x_shape, dw_shape = tuple(w.x_shape), tuple(w.dw_shape)
+    if nhwc:
+        xh = np.ascontiguousarray(xh.transpose(0, 2, 3, 1))
+        dyh = np.ascontiguousarray(dyh.transpose(0, 2, 3, 1))
+        x_shape = tuple(xh.shape)
+        dw_shape = (w.c_out, w.conv[0], w.conv[1], w.x_shape[1])
 
     def dev_tensor(a):
         if a.dtype == np.uint16:
@@ -133,15 +146,16 @@ def main():
     k = dropit.keep_count(w.numel, w.gamma)
     vals = torch.empty(k, dtype=xs[0].dtype, device=dev)
     idx = torch.empty(k, dtype=torch.int32, device=dev)
-    dW = torch.empty(w.dw_shape, dtype=torch.float32, device=dev)
+    dW = torch.empty(dw_shape, dtype=torch.float32, device=dev)
     ws_c = torch.empty(dropit.compress_workspace_bytes(w.numel, xs[0].dtype), dtype=torch.uint8, device=dev)
-    ws_g = torch.empty(max(1, dropit.weight_grad_workspace_bytes(w.x_shape, xs[0].dtype, k, w.c_out, conv)),
+    ws_g = torch.empty(max(1, dropit.weight_grad_workspace_bytes(x_shape, xs[0].dtype, k, w.c_out, conv,
+                                                                       layout=args.layout)),
                        dtype=torch.uint8, device=dev)
 
     def step(i):
         x, dy = xs[i % copies], dys[i % copies]
         dropit.compress(x, w.gamma, vals=vals, idx=idx, workspace=ws_c)
-        dropit.weight_grad(vals, idx, w.x_shape, dy, w.c_out, conv=conv, dW=dW, workspace=ws_g)
+        dropit.weight_grad(vals, idx, x_shape, dy, w.c_out, conv=conv, dW=dW, workspace=ws_g, layout=args.layout)
 
     for i in range(args.warmup):
         step(i)
@@ -200,13 +214,13 @@ def main():
         dropit.trace_events(ce[i])
         dropit.compress(x, w.gamma, vals=vals, idx=idx, workspace=ws_c)
         dropit.trace_events(ge[i])
-        dropit.weight_grad(vals, idx, w.x_shape, dy, w.c_out, conv=conv, dW=dW, workspace=ws_g)
+        dropit.weight_grad(vals, idx, x_shape, dy, w.c_out, conv=conv, dW=dW, workspace=ws_g, layout=args.layout)
         dropit.trace_events(None)
     torch.cuda.synchronize()
     bf16 = w.dtype == "bf16"
     # marks recorded per compress call: before and after the one persistent select kernel
     n_c = 2
-    path = dropit.weight_grad_path(w.x_shape, xs[0].dtype, k, w.c_out, conv)      # which kernels the library runs
+    path = dropit.weight_grad_path(x_shape, xs[0].dtype, k, w.c_out, conv, layout=args.layout)   # which kernels the library runs
     fc_mfma = path == "fc_mfma"
     conv_gemm = path in ("conv_gemm", "conv_im2col")      # operand preparation, then the fully-connected GEMM
     conv_mfma = path == "conv_bands"
@@ -250,7 +264,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": "%s: x %s %s gamma=%.2f, dY %s, dW %s fp32%s" % (
-            w.name, w.dtype, list(w.x_shape), w.gamma, list(w.dy_shape), list(w.dw_shape),
+            w.name + (" channels-last" if nhwc else ""), w.dtype, list(x_shape), w.gamma, list(dyh.shape), list(dw_shape),
             " (cold: %d rotating input copies, %.0f MB)" % (copies, copies * (xh.nbytes + dyh.nbytes) / 1e6)
             if copies > 1 else " (inputs warm in Infinity Cache)")},
         "warm": {"ms_per_step": warm_ms_per_step, "value": flops / (warm_ms_per_step * 1e-3) * 1e-12,
@@ -294,6 +308,8 @@ def main():
             x, dy = xs[i % copies], dys[i % copies]
             if w.conv is None:
                 return torch.mm(dy.reshape(-1, w.c_out).t(), x.reshape(-1, w.x_shape[-1]))
+            if nhwc:       # the same tensors as channels-last views of NCHW shapes
+                x, dy = x.permute(0, 3, 1, 2), dy.permute(0, 3, 1, 2)
             return torch.nn.grad.conv2d_weight(x, w.dw_shape, dy, stride=w.conv[2], padding=w.conv[3])
         for i in range(10):
             vendor(i)
@@ -309,7 +325,7 @@ def main():
                               "pct_mfma_peak": 100.0 * flops / (v_ms * 1e-3) * 1e-12 / MFMA_BF16_PEAK_TFLOPS,
                               "note": "dense dW of the same layer by torch (vendor GEMM / convolution library), "
                                       "bf16 output; this library's recover + GEMM + reduce take dw_ms"}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not nhwc:
         out["cpu_baseline"] = cpu_baseline(w, flops)
     print(json.dumps(out))
 

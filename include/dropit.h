@@ -184,7 +184,9 @@ dropit_status dropit_weight_grad(const void *vals, const int32_t *idx, int64_t k
  *     x_shape = [N, H, W, C] (4 extents),  dY [N, OH, OW, c_out],  conv != NULL
  *     dW [c_out, kh, kw, C] fp32 (the channels-last layout of a [c_out, C, kh, kw] weight)
  * Everything else (arguments, alignment, workspace, errors, arithmetic) as for
- * dropit_weight_grad; bf16 with c_out % 8 == 0 runs on the matrix cores (DROPIT_PATH_CONV_IM2COL).
+ * dropit_weight_grad; bf16 with c_out % 8 == 0 runs on the matrix cores (DROPIT_PATH_CONV_IM2COL; a
+ * 1x1 / stride 1 / unpadded convolution is a fully-connected layer over the N*H*W positions in this
+ * layout and takes those kernels, DROPIT_PATH_FC_MFMA).
  */
 dropit_wgrad_path dropit_weight_grad_nhwc_path(const int64_t *x_shape, dropit_dtype dt, int64_t k, int64_t c_out,
                                                const dropit_conv2d *conv);

@@ -248,6 +248,14 @@ dropit_status describe(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_
     p.OW = ew / conv->stride_w + 1;
     if (p.N * c_out * p.OH * p.OW > INT32_MAX * int64_t(16)) return DROPIT_EINVAL;
     if (c_out * p.C * conv->kh * conv->kw > INT32_MAX) return DROPIT_EINVAL;
+    // A channels-last 1x1 / stride 1 / unpadded convolution IS a fully-connected layer over the N*H*W
+    // positions: x [N*H*W][C], dY [N*H*W][J], dW [J][1][1][C] = [J][C].  It takes the FC kernels.
+    if (nhwc && conv->kh == 1 && conv->kw == 1 && conv->stride_h == 1 && conv->stride_w == 1 && conv->pad_h == 0 &&
+        conv->pad_w == 0) {
+        p.conv = false;
+        p.cin = p.C;
+        p.ntok = p.numel / p.C;
+    }
     return DROPIT_OK;
 }
 

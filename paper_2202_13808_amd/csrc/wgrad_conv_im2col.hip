@@ -190,7 +190,37 @@ im2col_tiled_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict
                 if (j + q * step < j1) decode(pi[q], pv[q]);
         }
     };
-    if (ih_lo <= ih_hi) {
+    if (NHWC && ts.nblocks > 1) {
+        // Blocks of taps: a tap (u, v) takes, for output row oy, exactly the input row oy*sh - ph + u*dh,
+        // which is one run of the pairs (all its columns and channels).  The (tap, output row) runs of the
+        // tile are dealt to groups of threads, so all of them are read at the same time and no workgroup
+        // reads rows its taps do not use.
+        const int nruns = bw * rb;
+        int rpow = 1;
+        while (rpow < nruns && rpow < 256) rpow <<= 1;
+        const int T = 256 / rpow;
+        const int grp = tid / T, sub = tid - grp * T;
+        const uint32_t row_elems = uint32_t(g.W * g.C);
+        for (int r = grp; r < nruns; r += 256 / T) {
+            const int tapi = r / rb, oyi = r - tapi * rb;
+            const int tap = b0 + tapi, u = tap / g.kw, v = tap - u * g.kw;
+            const int ih = (oy0 + oyi) * g.sh - g.ph + u * g.dh;
+            if (ih < 0 || ih >= g.H) continue;
+            const int64_t r0 = int64_t(n) * g.H + ih;
+            const uint32_t base = uint32_t(r0) * row_elems;
+            uint16_t *out_row = tile + oyi * g.OW * rowlen + tapi * g.C;
+            walk(row_ptr[r0], row_ptr[r0 + 1], sub, T, [&](uint32_t flat, uint32_t v16) {
+                const uint32_t rel = flat - base;
+                if (rel >= row_elems) return;                              // unsorted input must not write outside the tile
+                const uint32_t iw = rel / uint32_t(g.C), c = rel - iw * uint32_t(g.C);
+                const int nx = int(iw) + g.pw - v * g.dw;
+                if (nx < 0) return;
+                const int ox = g.sw == 1 ? nx : int(uint32_t(nx) / uint32_t(g.sw));
+                if (ox * g.sw != nx || ox >= g.OW) return;
+                out_row[ox * rowlen + int(c)] = uint16_t(v16);
+            });
+        }
+    } else if (ih_lo <= ih_hi) {
         if (NHWC) {
             const int64_t r0 = int64_t(n) * g.H + ih_lo;
             const uint32_t base = uint32_t(r0) * uint32_t(g.W * g.C);      // flat index of (n, ih_lo, 0, 0)

@@ -154,6 +154,8 @@ def test_weight_grad_path_of_the_benchmark_shapes():
     assert path((64, 4096, 7, 7), bf, 1000, 64, conv=(3, 3, 2, 2, 1, 1, 1, 1)) == "fma"   # C*kh*kw > 32768
     assert path((64, 56, 56, 64), bf, 1000, 64, conv=c3, layout="nhwc") == "conv_im2col"
     assert path((64, 56, 56, 64), f32, 1000, 64, conv=c3, layout="nhwc") == "fma"
+    assert path((64, 56, 56, 256), bf, 1000, 64, conv=(1, 1, 1, 1, 0, 0, 1, 1), layout="nhwc") == "fc_mfma"
+    assert path((64, 56, 56, 256), bf, 1000, 64, conv=(1, 1, 2, 2, 0, 0, 1, 1), layout="nhwc") == "conv_im2col"
     assert path((64, 56, 56, 64), bf, -1, 64, conv=c3, layout="nhwc") == "none"
     assert path((3, 16, 9, 1), bf, 10, 8, conv=c3) == "conv_im2col"     # a single column: not the row-band kernel
     assert path((64, 512, 7, 7), bf, -1, 512, conv=c3) == "none"

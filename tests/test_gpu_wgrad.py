@@ -250,6 +250,7 @@ def test_conv_general_geometries(dtype, N, C, H, W, J, geom):
 
 GEOMETRIES = [
     ((2, 16, 9, 11), 24, (1, 1, 1, 1, 0, 0, 1, 1)),        # 1x1 (most of a ResNet-50's convolutions)
+    ((3, 40, 7, 9), 16, (1, 1, 2, 2, 0, 0, 1, 1)),         # 1x1 / stride 2 (a ResNet downsampling shortcut)
     ((2, 3, 40, 44), 16, (7, 7, 2, 2, 3, 3, 1, 1)),        # 7x7 / stride 2 / pad 3 (first ResNet layer's geometry)
     ((3, 8, 15, 14), 8, (3, 3, 2, 2, 1, 1, 1, 1)),         # 3x3 / stride 2
     ((2, 3, 32, 48), 40, (16, 16, 16, 16, 0, 0, 1, 1)),    # 16x16 / stride 16 (ViT patch embedding)
@@ -299,8 +300,9 @@ def test_conv_channels_last(dtype, x_shape, J, geom):
     dy = gradient((N, OH, OW, J), 0.02, 850 + W + kw, dtype)
     k = oracle.keep_count(x.size, 0.6)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    pointwise = geom[:6] == (1, 1, 1, 1, 0, 0)         # a fully-connected layer over the positions in this layout
     assert dropit.weight_grad_path(x.shape, tdt, k, J, conv=geom, layout="nhwc") == \
-        ("conv_im2col" if dtype == "bf16" else "fma")
+        ("fma" if dtype == "f32" else "fc_mfma" if pointwise else "conv_im2col")
     xd, dyd = to_device(x), to_device(dy)
     vals, idx = dropit.compress(xd, 0.6)
     dW = dropit.weight_grad(vals, idx, x.shape, dyd, J, conv=geom, layout="nhwc")
