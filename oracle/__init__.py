@@ -59,6 +59,10 @@ def _load():
         lib.oracle_rows_from_pairs.argtypes = [vp, i64, i64, i64, vp, vp]
         lib.oracle_pairs_from_rows.restype = i32
         lib.oracle_pairs_from_rows.argtypes = [vp, vp, i64, i64, vp]
+        lib.oracle_mask_from_pairs.restype = i32
+        lib.oracle_mask_from_pairs.argtypes = [vp, i64, i64, i64, vp, vp]
+        lib.oracle_pairs_from_mask.restype = i64
+        lib.oracle_pairs_from_mask.argtypes = [vp, vp, i64, i64, vp]
         lib.oracle_widen.restype = None
         lib.oracle_widen.argtypes = [vp, i64, i32, vp]
         lib.oracle_densify.restype = i32
@@ -157,6 +161,31 @@ def pairs_from_rows(col: np.ndarray, rowptr: np.ndarray, shape) -> np.ndarray:
     if _load().oracle_pairs_from_rows(_ptr(col), _ptr(rowptr), rowptr.size - 1, int(shape[-1]), _ptr(idx)) != 0:
         raise ValueError("oracle_pairs_from_rows rejected its arguments")
     return idx
+
+
+MASK_BLOCK = 1024      # elements per entry of the block-offset table of the bit-mask form
+
+
+def mask_from_pairs(idx: np.ndarray, numel: int, block: int = MASK_BLOCK):
+    """Bit-mask form of a retained index set: (mask uint32 [ceil(numel/32)], blockptr int32
+    [ceil(numel/block)+1])  [Sec. 5, index memory]."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    mask = np.empty((numel + 31) // 32, dtype=np.uint32)
+    blockptr = np.empty((numel + block - 1) // block + 1, dtype=np.int32)
+    if _load().oracle_mask_from_pairs(_ptr(idx), idx.size, int(numel), int(block), _ptr(mask), _ptr(blockptr)) != 0:
+        raise ValueError("oracle_mask_from_pairs rejected its arguments")
+    return mask, blockptr
+
+
+def pairs_from_mask(mask: np.ndarray, blockptr: np.ndarray, numel: int, block: int = MASK_BLOCK) -> np.ndarray:
+    """Inverse of mask_from_pairs: the ascending int32 flat indices."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint32)
+    blockptr = np.ascontiguousarray(blockptr, dtype=np.int32)
+    idx = np.empty(int(numel), dtype=np.int32)
+    n = _load().oracle_pairs_from_mask(_ptr(mask), _ptr(blockptr), int(numel), int(block), _ptr(idx))
+    if n < 0:
+        raise ValueError("oracle_pairs_from_mask: the block offsets do not match the mask")
+    return idx[:n].copy()
 
 
 def widen(a: np.ndarray) -> np.ndarray:

@@ -214,6 +214,48 @@ int oracle_pairs_from_rows(const uint16_t *col, const int32_t *rowptr, int64_t r
     return 0;
 }
 
+/* ---- bit-mask form of the retained index set --------------------------- */
+/* One bit per element of the tensor (bit i%32 of word i/32 set iff element i is
+ * retained; the bits past numel in the last word are 0), plus, for every block of
+ * `block` consecutive elements (a multiple of 32), the number of retained elements
+ * before it: blockptr[b], b = 0..ceil(numel/block).  numel/8 bytes of mask against
+ * 4 bytes per retained int32 index: smaller whenever more than 1/32 of the tensor
+ * is kept (Sec. 5 counts the index bytes as part of the method's memory; the
+ * appendix on choosing gamma prices an int32 index at one fp32 activation).
+ * Returns 0, or -1 on bad arguments (an index outside the tensor or out of order). */
+int oracle_mask_from_pairs(const int32_t *idx, int64_t k, int64_t numel, int64_t block,
+                           uint32_t *mask, int32_t *blockptr)
+{
+    if (k < 0 || numel < 1 || block < 32 || block % 32 != 0) return -1;
+    const int64_t words = (numel + 31) / 32, blocks = (numel + block - 1) / block;
+    for (int64_t w = 0; w < words; ++w) mask[w] = 0;
+    for (int64_t b = 0; b <= blocks; ++b) blockptr[b] = 0;
+    for (int64_t j = 0; j < k; ++j) {
+        int64_t i = idx[j];
+        if (i < 0 || i >= numel) return -1;
+        if (j > 0 && idx[j - 1] >= idx[j]) return -1;
+        mask[i / 32] |= (uint32_t)1 << (i % 32);
+        blockptr[i / block + 1] += 1;           /* count per block ... */
+    }
+    for (int64_t b = 0; b < blocks; ++b) blockptr[b + 1] += blockptr[b];   /* ... then running sum */
+    return 0;
+}
+
+/* Inverse: the ascending flat indices of the set bits.  Returns their number, or -1 if
+ * blockptr does not match the mask. */
+int64_t oracle_pairs_from_mask(const uint32_t *mask, const int32_t *blockptr, int64_t numel, int64_t block,
+                               int32_t *idx)
+{
+    if (numel < 1 || block < 32 || block % 32 != 0) return -1;
+    int64_t j = 0;
+    for (int64_t i = 0; i < numel; ++i) {
+        if (i % block == 0 && blockptr[i / block] != j) return -1;
+        if ((mask[i / 32] >> (i % 32)) & 1u) idx[j++] = (int32_t)i;
+    }
+    if (blockptr[(numel + block - 1) / block] != j) return -1;
+    return j;
+}
+
 /* ---- exact widening to double ----------------------------------------- */
 static double widen(const void *v, int64_t i, int dtype)
 {
