@@ -231,6 +231,32 @@ dropit_status dropit_weight_grad_rows(const void *vals, const uint16_t *col, con
                                       void *hip_stream);
 
 /*
+ * Bit-mask form of the cache (Sec. 5 counts the index bytes as part of the method's memory;
+ * the appendix on choosing gamma prices an int32 index at one fp32 activation).  Instead of idx:
+ *     mask[ceil(numel/32)]  uint32, bit (i mod 32) of word (i div 32) set iff element i is retained
+ *                           (bits past numel are 0);
+ *     blockptr[ceil(numel/DROPIT_MASK_BLOCK) + 1]  int32, the number of retained elements before
+ *                           element b * DROPIT_MASK_BLOCK (the last entry is k).
+ * numel/8 bytes whatever k: smaller than int32 indices when more than 1/32 of the tensor is kept.
+ * vals is what dropit_compress writes (ascending flat index).  The encoding is lossless:
+ * dropit_weight_grad_mask gives bit for bit what dropit_weight_grad gives on the flat indices.
+ * Arguments not named here, alignment and error behaviour as for dropit_compress /
+ * dropit_weight_grad; mask and blockptr are device pointers, 4-byte aligned; each workspace also
+ * holds the flat indices (the *_mask_workspace_bytes queries say how much).
+ */
+#define DROPIT_MASK_BLOCK 1024
+size_t dropit_compress_mask_workspace_bytes(int64_t numel, int64_t k, dropit_dtype dt);
+dropit_status dropit_compress_mask(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                                   double gamma, void *vals, uint32_t *mask, int32_t *blockptr,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t dropit_weight_grad_mask_workspace_bytes(const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                               int64_t k, int64_t c_out, const dropit_conv2d *conv);
+dropit_status dropit_weight_grad_mask(const void *vals, const uint32_t *mask, const int32_t *blockptr,
+                                      int64_t k, const int64_t *x_shape, int ndim, dropit_dtype dt,
+                                      const void *dY, int64_t c_out, const dropit_conv2d *conv,
+                                      float *dW, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * How dropit_compress runs its select (per host thread):
  *   0 (default)  one persistent kernel (it also clears its own exchange area), one workgroup per
  *                compute unit, grid barriers between its phases, launched as an ordinary kernel

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     compress,
     compress_random,
     compress_random_workspace_bytes,
+    compress_mask,
     compress_rows,
     compress_workspace_bytes,
     keep_count,
@@ -20,6 +21,7 @@ from .binding import (  # noqa: F401
     set_select_mode,
     trace_events,
     weight_grad,
+    weight_grad_mask,
     weight_grad_rows,
     weight_grad_workspace_bytes,
     weight_grad_path,

@@ -69,6 +69,14 @@ def lib() -> ctypes.CDLL:
         L.dropit_weight_grad_rows_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
         L.dropit_weight_grad_rows.restype = i32
         L.dropit_weight_grad_rows.argtypes = [vp, vp, vp, i64, p64, i32, i32, vp, i64, pconv, vp, vp, sz, vp]
+        L.dropit_compress_mask_workspace_bytes.restype = sz
+        L.dropit_compress_mask_workspace_bytes.argtypes = [i64, i64, i32]
+        L.dropit_compress_mask.restype = i32
+        L.dropit_compress_mask.argtypes = [vp, p64, i32, i32, ctypes.c_double, vp, vp, vp, vp, sz, vp]
+        L.dropit_weight_grad_mask_workspace_bytes.restype = sz
+        L.dropit_weight_grad_mask_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
+        L.dropit_weight_grad_mask.restype = i32
+        L.dropit_weight_grad_mask.argtypes = [vp, vp, vp, i64, p64, i32, i32, vp, i64, pconv, vp, vp, sz, vp]
         L.dropit_weight_grad_workspace_bytes.restype = sz
         L.dropit_weight_grad_workspace_bytes.argtypes = [p64, i32, i32, i64, i64, pconv]
         L.dropit_weight_grad_path.restype = i32
@@ -314,6 +322,59 @@ def weight_grad_rows(vals: torch.Tensor, col: torch.Tensor, rowptr: torch.Tensor
     with torch.cuda.device(dY.device):
         _check(lib().dropit_weight_grad_rows(
             vals.data_ptr() if k else None, col.data_ptr() if k else None, rowptr.data_ptr(), k,
+            shape, len(x_shape), code, dY.data_ptr(), int(c_out), ref, dW.data_ptr(),
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dW
+
+
+MASK_BLOCK = 1024      # DROPIT_MASK_BLOCK: elements per entry of the block-offset table
+
+
+def compress_mask(x: torch.Tensor, gamma: float, workspace: Optional[torch.Tensor] = None,
+                  stream=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """dropit_compress_mask: (vals[k], mask[ceil(numel/32)] int32 holding the uint32 words,
+    blockptr[ceil(numel/1024)+1] int32)."""
+    _require_device(x, workspace)
+    code = _dtype_code(x.dtype)
+    numel = x.numel()
+    k = keep_count(numel, gamma)
+    if k < 0:
+        _check(EINVAL)
+    vals = torch.empty(k, dtype=x.dtype, device=x.device)
+    mask = torch.empty((numel + 31) // 32, dtype=torch.int32, device=x.device)      # bits are uint32
+    blockptr = torch.empty((numel + MASK_BLOCK - 1) // MASK_BLOCK + 1, dtype=torch.int32, device=x.device)
+    if workspace is None:
+        need = int(lib().dropit_compress_mask_workspace_bytes(numel, k, code))
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(lib().dropit_compress_mask(x.data_ptr(), _shape_array(x.shape), x.dim(), code, float(gamma),
+                                          vals.data_ptr() if k else None, mask.data_ptr(), blockptr.data_ptr(),
+                                          workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return vals, mask, blockptr
+
+
+def weight_grad_mask(vals: torch.Tensor, mask: torch.Tensor, blockptr: torch.Tensor, x_shape: Sequence[int],
+                     dY: torch.Tensor, c_out: int, conv=None, dW: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """dropit_weight_grad_mask: ``weight_grad`` from the bit-mask form of the cache."""
+    _require_device(vals, mask, blockptr, dY, dW, workspace)
+    code = _dtype_code(dY.dtype)
+    if vals.dtype != dY.dtype or mask.dtype != torch.int32 or blockptr.dtype != torch.int32:
+        raise ValueError("vals must have dY's dtype, mask int32 (uint32 bits), blockptr int32")
+    cs = _conv_struct(conv)
+    x_shape = [int(s) for s in x_shape]
+    if dW is None:
+        dw_shape = (int(c_out), x_shape[-1]) if cs is None else (int(c_out), x_shape[1], cs.kh, cs.kw)
+        dW = torch.empty(dw_shape, dtype=torch.float32, device=dY.device)
+    k = int(vals.numel())
+    shape = _shape_array(x_shape)
+    ref = ctypes.byref(cs) if cs is not None else None
+    if workspace is None:
+        need = int(lib().dropit_weight_grad_mask_workspace_bytes(shape, len(x_shape), code, k, int(c_out), ref))
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dY.device)
+    with torch.cuda.device(dY.device):
+        _check(lib().dropit_weight_grad_mask(
+            vals.data_ptr() if k else None, mask.data_ptr(), blockptr.data_ptr(), k,
             shape, len(x_shape), code, dY.data_ptr(), int(c_out), ref, dW.data_ptr(),
             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dW

@@ -93,8 +93,9 @@ def main() -> None:
     ap.add_argument("--depth", type=int, default=12)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--index", choices=["flat", "rows"], default="flat",
-                    help="cached index form: int32 flat indices, or 16-bit in-row positions + row offsets")
+    ap.add_argument("--index", choices=["flat", "rows", "mask"], default="flat",
+                    help="cached index form: int32 flat indices, 16-bit in-row positions + row offsets, or one "
+                         "bit per element + block offsets")
     ap.add_argument("--gammas", type=float, nargs="*", default=[0.0, 0.6, 0.7, 0.8, 0.9])
     args = ap.parse_args()
     if not torch.cuda.is_available():

@@ -30,8 +30,8 @@ _Int2 = Union[int, Sequence[int]]
 
 
 def _check_format(index_format: str) -> str:
-    if index_format not in ("flat", "rows"):
-        raise ValueError("index_format must be 'flat' or 'rows'")
+    if index_format not in ("flat", "rows", "mask"):
+        raise ValueError("index_format must be 'flat', 'rows' or 'mask'")
     return index_format
 
 
@@ -83,18 +83,19 @@ def _account(x: torch.Tensor, cache: Sequence[torch.Tensor]) -> None:
         meter._add(x, cache)
 
 
-def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int], rows: bool) -> Tuple[torch.Tensor, ...]:
+def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int], fmt: str) -> Tuple[torch.Tensor, ...]:
     """Min-k dropping, or (seed given) the random strategy of Sec. 3.3 with that seed.  Returns the
-    cache: (vals, idx), or with ``rows`` the cheaper (vals, col, rowptr) form."""
+    cache: (vals, idx), or one of the cheaper index forms: "rows" (vals, col, rowptr), "mask"
+    (vals, mask, blockptr)."""
     if not x.is_cuda:
         raise RuntimeError("DropIT layers train on device tensors only: there is no CPU path")
     xc = x.detach()
     if not xc.is_contiguous():
         xc = xc.contiguous()
-    if rows:
+    if fmt != "flat":
         if seed is not None:
             raise ValueError("the random strategy keeps flat indices (index_format='flat')")
-        cache = binding.compress_rows(xc, gamma)
+        cache = binding.compress_rows(xc, gamma) if fmt == "rows" else binding.compress_mask(xc, gamma)
     elif seed is None:
         cache = binding.compress(xc, gamma)
     else:
@@ -103,10 +104,12 @@ def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int], rows: bo
     return tuple(cache)
 
 
-def _weight_grad(cache: Sequence[torch.Tensor], x_shape, dy: torch.Tensor, c_out: int, conv=None) -> torch.Tensor:
+def _weight_grad(cache: Sequence[torch.Tensor], fmt: str, x_shape, dy: torch.Tensor, c_out: int, conv=None) -> torch.Tensor:
     dy = _match_dtype(dy, cache[0])
-    if len(cache) == 3:
+    if fmt == "rows":
         return binding.weight_grad_rows(cache[0], cache[1], cache[2], x_shape, dy, c_out, conv=conv)
+    if fmt == "mask":
+        return binding.weight_grad_mask(cache[0], cache[1], cache[2], x_shape, dy, c_out, conv=conv)
     return binding.weight_grad(cache[0], cache[1], x_shape, dy, c_out, conv=conv)
 
 
@@ -120,9 +123,10 @@ def _match_dtype(dy: torch.Tensor, vals: torch.Tensor) -> torch.Tensor:
 # ---------------------------------------------------------------------------------------------
 class _LinearFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, gamma, seed, rows):
+    def forward(ctx, x, weight, bias, gamma, seed, fmt):
         y = F.linear(x, weight, bias)
-        ctx.save_for_backward(weight, *_compress_input(x, gamma, seed, rows))
+        ctx.save_for_backward(weight, *_compress_input(x, gamma, seed, fmt))
+        ctx.fmt = fmt
         ctx.x_shape = tuple(x.shape)
         ctx.has_bias = bias is not None
         return y
@@ -136,7 +140,7 @@ class _LinearFn(torch.autograd.Function):
         if ctx.needs_input_grad[0]:
             dx = (dy2 @ weight.to(dy.dtype)).reshape(ctx.x_shape)
         if ctx.needs_input_grad[1]:
-            dw = _weight_grad(cache, ctx.x_shape, dy2, c_out).to(weight.dtype)
+            dw = _weight_grad(cache, ctx.fmt, ctx.x_shape, dy2, c_out).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy2.sum(0)
         return dx, dw, db, None, None, None
@@ -146,8 +150,9 @@ def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] =
            gamma: float = 0.9, seed: Optional[int] = None, index_format: str = "flat") -> torch.Tensor:
     """``F.linear`` whose backward computes the weight gradient from the min-k cache of ``x``
     (from a random cache drawn with ``seed`` when one is given).  ``index_format`` "rows" caches
-    16-bit in-row positions and row offsets instead of int32 flat indices."""
-    return _LinearFn.apply(x, weight, bias, float(gamma), seed, _check_format(index_format) == "rows")
+    16-bit in-row positions and row offsets instead of int32 flat indices, "mask" one bit per
+    element and block offsets."""
+    return _LinearFn.apply(x, weight, bias, float(gamma), seed, _check_format(index_format))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -155,12 +160,13 @@ def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] =
 # ---------------------------------------------------------------------------------------------
 class _Conv2dFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma, seed, rows):
+    def forward(ctx, x, weight, bias, stride, padding, dilation, gamma, seed, fmt):
         y = F.conv2d(x, weight, bias, stride, padding, dilation, 1)
         # a channels-last input is cached as it lies in memory ([N, H, W, C]) instead of being copied to NCHW
-        ctx.nhwc = (not rows and x.dim() == 4 and not x.is_contiguous()
+        ctx.fmt = fmt
+        ctx.nhwc = (fmt == "flat" and x.dim() == 4 and not x.is_contiguous()
                     and x.is_contiguous(memory_format=torch.channels_last))
-        ctx.save_for_backward(weight, *_compress_input(x.permute(0, 2, 3, 1) if ctx.nhwc else x, gamma, seed, rows))
+        ctx.save_for_backward(weight, *_compress_input(x.permute(0, 2, 3, 1) if ctx.nhwc else x, gamma, seed, fmt))
         ctx.x_shape = tuple(x.shape)
         ctx.geometry = (stride, padding, dilation)
         ctx.has_bias = bias is not None
@@ -182,7 +188,7 @@ class _Conv2dFn(torch.autograd.Function):
                 dw = binding.weight_grad(cache[0], cache[1], (n, h, w, c), dyl, c_out, conv=conv, layout="nhwc")
                 dw = dw.permute(0, 3, 1, 2).to(weight.dtype)        # [J, C, kh, kw] with channels-last strides
             else:
-                dw = _weight_grad(cache, ctx.x_shape, dy, c_out, conv=conv).to(weight.dtype)
+                dw = _weight_grad(cache, ctx.fmt, ctx.x_shape, dy, c_out, conv=conv).to(weight.dtype)
         if ctx.has_bias and ctx.needs_input_grad[2]:
             db = dy.sum((0, 2, 3))
         return dx, dw, db, None, None, None, None, None, None
@@ -196,7 +202,7 @@ def conv2d(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] =
     ``index_format`` as for ``linear``.  A channels-last ``x`` is cached and multiplied in that
     layout (flat index format)."""
     return _Conv2dFn.apply(x, weight, bias, _pair(stride), _pair(padding), _pair(dilation), float(gamma), seed,
-                           _check_format(index_format) == "rows")
+                           _check_format(index_format))
 
 
 # ---------------------------------------------------------------------------------------------

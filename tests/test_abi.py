@@ -27,7 +27,9 @@ def test_header_declares_the_expected_entry_points():
         "dropit_weight_grad_nhwc_path", "dropit_weight_grad_nhwc_workspace_bytes", "dropit_weight_grad_nhwc",
         "dropit_compress_random_workspace_bytes", "dropit_compress_random",
         "dropit_compress_rows_workspace_bytes", "dropit_compress_rows",
-        "dropit_weight_grad_rows_workspace_bytes", "dropit_weight_grad_rows"])
+        "dropit_weight_grad_rows_workspace_bytes", "dropit_weight_grad_rows",
+        "dropit_compress_mask_workspace_bytes", "dropit_compress_mask",
+        "dropit_weight_grad_mask_workspace_bytes", "dropit_weight_grad_mask"])
 
 
 def test_library_exports_every_declared_symbol():
@@ -160,6 +162,28 @@ def test_weight_grad_path_of_the_benchmark_shapes():
     assert path((3, 16, 9, 1), bf, 10, 8, conv=c3) == "conv_im2col"     # a single column: not the row-band kernel
     assert path((64, 512, 7, 7), bf, -1, 512, conv=c3) == "none"
     assert path((1, 2, 4, 4), bf, 4, 2, conv=(7, 7, 1, 1, 0, 0, 1, 1)) == "none"
+
+
+def test_mask_entry_points_validate_arguments():
+    L = dropit.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ws = ctypes.c_void_p(0x4000)
+    dw = ctypes.c_void_p(0x2000)
+    big = 1 << 30
+    call = L.dropit_compress_mask
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, None, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, None, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 2.0, fake, fake, fake, ws, big, None) == binding.EINVAL
+    assert call(fake, _shape(4, 4), 2, binding.BF16, 0.5, fake, fake, fake, ws, 64, None) == binding.EWORKSPACE
+    assert L.dropit_compress_mask_workspace_bytes(1 << 20, 1 << 18, binding.BF16) >= \
+        L.dropit_compress_workspace_bytes(1 << 20, binding.BF16) + 4 * (1 << 18)
+    assert L.dropit_compress_mask_workspace_bytes(16, 17, binding.BF16) == 0
+    wg = L.dropit_weight_grad_mask
+    assert wg(fake, None, fake, 4, _shape(4, 8), 2, binding.BF16, fake, 8, None, dw, ws, big, None) == binding.EINVAL
+    assert wg(fake, fake, fake, 33, _shape(4, 8), 2, binding.BF16, fake, 8, None, dw, ws, big, None) == binding.EINVAL
+    assert wg(fake, fake, fake, 4, _shape(4, 8), 2, binding.BF16, fake, 8, None, dw, ws, 16, None) == binding.EWORKSPACE
+    assert L.dropit_weight_grad_mask_workspace_bytes(_shape(4, 8), 2, binding.BF16, 4, 8, None) > \
+        L.dropit_weight_grad_workspace_bytes(_shape(4, 8), 2, binding.BF16, 4, 8, None)
 
 
 def test_nhwc_entry_points_validate_arguments():
