@@ -587,8 +587,17 @@ splitk_sum_kernel(const f32x4 *__restrict__ partial, int splits, int M, int N, i
 #ifndef DROPIT_GEMM_CFG
 #define DROPIT_GEMM_CFG 256, 256, 32, 4, 2, 4, 2, 1
 #endif
+// For layers with at most 128 output channels: half the rows, wavefronts 2 x 4 of 64 x 64 each.  A 128-row
+// tile multiplies at ~0.7 of the wide tile's rate per flop (more LDS bytes per flop), but the wide one
+// would spend half its rows or more on padding there.
+#ifndef DROPIT_GEMM_CFG_NARROW
+#define DROPIT_GEMM_CFG_NARROW 128, 256, 32, 2, 4, 4, 2, 1
+#endif
 using Cfg = GemmCfg<DROPIT_GEMM_CFG>;
+using CfgNarrow = GemmCfg<DROPIT_GEMM_CFG_NARROW>;
+static_assert(Cfg::BK == CfgNarrow::BK && Cfg::BN == CfgNarrow::BN, "the recovered operand is laid out once for both");
 
+template <typename C>
 int tuned_splits(int tiles, int nkb)
 {
     // as many K-slices as fill the 256 compute units (one or two resident workgroups each)
@@ -596,7 +605,7 @@ int tuned_splits(int tiles, int nkb)
     // writes a whole partial tile however little it summed, and below that depth the partial
     // traffic costs more than the idle compute units (measured on 3136 and 12544 tokens:
     // the best slice count was the one with 19.6 blocks per slice both times)
-    int splits = std::min(256 * Cfg::WGS_PER_CU / tiles, std::max(1, (nkb + 10) / 20));
+    int splits = std::min(256 * C::WGS_PER_CU / tiles, std::max(1, (nkb + 10) / 20));
 #ifdef DROPIT_TUNING
     if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
 #endif
@@ -604,6 +613,24 @@ int tuned_splits(int tiles, int nkb)
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     return splits;
+}
+
+bool use_narrow(const FcProblem &p)
+{
+#ifdef DROPIT_TUNING
+    if (const char *e = getenv("DROPIT_GEMM_NARROW")) return e[0] == '1';
+#endif
+    return p.cout <= CfgNarrow::BM;
+}
+
+template <typename C>
+void plan_tiles(const FcProblem &p, FcDensePlan &plan)
+{
+    plan.nb_count = int((p.cin + C::BN - 1) / C::BN);
+    plan.mb_count = int((p.cout + C::BM - 1) / C::BM);
+    plan.splits = tuned_splits<C>(plan.nb_count * plan.mb_count, plan.nkb);
+    // K-slice partials are whole tiles (ragged edge tiles included) in accumulator order
+    plan.partial_bytes = plan.splits > 1 ? size_t(plan.splits) * plan.nb_count * plan.mb_count * C::BM * C::BN * 4 : 0;
 }
 
 }  // namespace
@@ -621,15 +648,15 @@ FcDensePlan fc_dense_plan(const FcProblem &p)
 {
     FcDensePlan plan;
     plan.nkb = int((p.ntok + Cfg::BK - 1) / Cfg::BK);
-    plan.nb_count = int((p.cin + Cfg::BN - 1) / Cfg::BN);
-    plan.mb_count = int((p.cout + Cfg::BM - 1) / Cfg::BM);
-    plan.splits = tuned_splits(plan.nb_count * plan.mb_count, plan.nkb);
+    plan.narrow = use_narrow(p);
+    if (plan.narrow)
+        plan_tiles<CfgNarrow>(p, plan);
+    else
+        plan_tiles<Cfg>(p, plan);
     plan.pitch = int((p.cin + 7) / 8 * 8);
     plan.rows_per_wg = std::max(1, (plan.pitch <= RECOVER_ELEMS ? RECOVER_ELEMS : RECOVER_ELEMS_MAX) / plan.pitch);
     plan.ntok_pad = int64_t(plan.nkb) * Cfg::BK;
     plan.dense_bytes = round_up(size_t(plan.ntok_pad) * plan.pitch * 2, 256);
-    // K-slice partials are whole tiles (ragged edge tiles included) in accumulator order
-    plan.partial_bytes = plan.splits > 1 ? size_t(plan.splits) * plan.nb_count * plan.mb_count * Cfg::BM * Cfg::BN * 4 : 0;
     return plan;
 }
 
@@ -644,30 +671,40 @@ static bool fc_dense_attributes()
                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                    RECOVER_ELEMS_MAX * 2) == hipSuccess &&
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<CfgNarrow>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, CfgNarrow::LDS_BYTES) == hipSuccess;
     });
+}
+
+template <typename C>
+static dropit_status launch_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
+                                 float *partial, float *dW, hipStream_t stream)
+{
+    const int total = plan.nb_count * plan.mb_count * plan.splits;
+    const int grid = (total + 7) / 8 * 8;
+    float *out = plan.splits > 1 ? partial : dW;
+    fc_dense_kernel<C><<<grid, C::NTHREADS, C::LDS_BYTES, stream>>>(
+        static_cast<const uint16_t *>(dY), dense, p.ntok, int(p.cout), int(p.cin), plan.pitch, plan.nb_count,
+        plan.mb_count, plan.nkb, plan.splits, out);
+
+    trace_mark(stream);
+    if (plan.splits > 1) {
+        const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (C::BM * C::BN / 4);
+        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
+        splitk_sum_kernel<C><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
+                                                         int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
+    }
+    trace_mark(stream);
+    return launch_status();
 }
 
 dropit_status fc_dense_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
                             float *partial, float *dW, hipStream_t stream)
 {
     if (!fc_dense_attributes()) return DROPIT_EHIP;
-    const int total = plan.nb_count * plan.mb_count * plan.splits;
-    const int grid = (total + 7) / 8 * 8;
-    float *out = plan.splits > 1 ? partial : dW;
-    fc_dense_kernel<Cfg><<<grid, Cfg::NTHREADS, Cfg::LDS_BYTES, stream>>>(
-        static_cast<const uint16_t *>(dY), dense, p.ntok, int(p.cout), int(p.cin), plan.pitch, plan.nb_count,
-        plan.mb_count, plan.nkb, plan.splits, out);
-
-    trace_mark(stream);
-    if (plan.splits > 1) {
-        const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (Cfg::BM * Cfg::BN / 4);
-        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
-        splitk_sum_kernel<Cfg><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
-                                                           int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
-    }
-    trace_mark(stream);
-    return launch_status();
+    return plan.narrow ? launch_gemm<CfgNarrow>(p, plan, dY, dense, partial, dW, stream)
+                       : launch_gemm<Cfg>(p, plan, dY, dense, partial, dW, stream);
 }
 
 dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,

@@ -13,6 +13,7 @@ struct FcProblem {
 
 struct FcDensePlan {
     int nkb, nb_count, mb_count, splits, pitch, rows_per_wg;
+    bool narrow;                               // the 128-row tile configuration (layers with few output channels)
     int64_t ntok_pad;                          // rows of the dense operand: the tokens rounded up to whole token blocks
     size_t dense_bytes, partial_bytes;
     size_t total() const { return dense_bytes + partial_bytes; }
