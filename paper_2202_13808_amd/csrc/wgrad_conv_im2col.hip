@@ -79,19 +79,6 @@ im2col_scatter_kernel(const uint16_t *__restrict__ vals, const int32_t *__restri
     }
 }
 
-// Row starts for the tiled form: row_ptr[r] = number of pairs whose flat index lies before row r
-// of `row_len` elements (row_ptr[R] = k).  One pass over idx: thread j looks at pairs j - 1 and j
-// and fills the row starts that fall between them.
-__global__ void __launch_bounds__(256)
-row_starts_kernel(const int32_t *__restrict__ idx, int64_t k, uint32_t row_len, int64_t R, uint32_t *__restrict__ row_ptr)
-{
-    for (int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; j <= k; j += int64_t(gridDim.x) * blockDim.x) {
-        const int64_t before = (j == 0) ? -1 : min<int64_t>(uint32_t(idx[j - 1]) / row_len, R);
-        const int64_t here = (j == k) ? R : min<int64_t>(uint32_t(idx[j]) / row_len, R);
-        for (int64_t r = max<int64_t>(before, -1) + 1; r <= here; ++r) row_ptr[r] = uint32_t(j);
-    }
-}
-
 // The im2col rows assembled in LDS tiles and written once, in full lines, with no zero-fill pass.
 // Workgroup = (image n, column block, band of RB output rows).  A column block is a block of input
 // channels in NCHW (columns (c, u, v)) and a block of taps in NHWC (columns (u, v, c)), so that its
@@ -388,8 +375,7 @@ dropit_status conv_im2col_run(const ConvGeneral &p, const ConvIm2colPlan &plan, 
         uint32_t *row_ptr = reinterpret_cast<uint32_t *>(ws + plan.gemm.dense_bytes + plan.gemm.partial_bytes + plan.dyt_bytes);
         const int64_t rows = p.nhwc ? p.N * p.H : p.N * p.C * p.H;
         const uint32_t row_len = uint32_t(p.nhwc ? p.W * p.C : p.W);
-        row_starts_kernel<<<int(std::min<int64_t>((p.k + 1 + 255) / 256, 4096)), 256, 0, stream>>>(idx, p.k, row_len, rows,
-                                                                                                 row_ptr);
+        launch_row_starts(idx, p.k, row_len, rows, row_ptr, stream);
         static std::atomic<uint64_t> attr_set{0};
         if (!once_per_device(attr_set, [] {
                 return hipFuncSetAttribute(reinterpret_cast<const void *>(im2col_tiled_kernel<true>),

@@ -36,19 +36,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int CT = 512;            // threads per GEMM workgroup: 2 K-groups x (2 j-halves x 2 c-halves) wavefronts
 constexpr int BJ = 64, BC = 64;    // output-channel / input-channel block of a workgroup
 
-// Prep: row_ptr[r] = number of pairs whose flat index lies before row r, for every row
-// r = (n * C + c) * H + h of W elements (row_ptr[R] = k).  One pass over idx: thread j looks at
-// pairs j - 1 and j and fills the row starts that fall between them.
-__global__ void __launch_bounds__(256)
-conv_rowptr_kernel(const int32_t *__restrict__ idx, int64_t k, int W, int64_t R, uint32_t *__restrict__ row_ptr)
-{
-    for (int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; j <= k; j += int64_t(gridDim.x) * blockDim.x) {
-        // indices are below 2^31: 32-bit unsigned division (a 64-bit one is several times the instructions)
-        const int64_t before = (j == 0) ? -1 : min<int64_t>(uint32_t(idx[j - 1]) / uint32_t(W), R);
-        const int64_t here = (j == k) ? R : min<int64_t>(uint32_t(idx[j]) / uint32_t(W), R);
-        for (int64_t r = max<int64_t>(before, -1) + 1; r <= here; ++r) row_ptr[r] = uint32_t(j);
-    }
-}
+// Prep (row_starts_kernel): row_ptr[r] = number of pairs whose flat index lies before row r, for every
+// row r = (n * C + c) * H + h of W elements (row_ptr[R] = k).
 
 // GEMM: workgroup = (image n, band of RB output rows, 64 x 64 block of (j, c)).
 // AG = column groups (of 8) multiplied per step; the host picks the instantiation that wastes the
@@ -394,8 +383,7 @@ dropit_status conv_mfma_run(const ConvProblem &p, const ConvPlan &plan, const vo
 
     trace_mark(stream);
     const int64_t R = p.N * p.C * p.H;
-    const int prep_blocks = int(std::min<int64_t>((p.k + 1 + 255) / 256, 4096));
-    conv_rowptr_kernel<<<prep_blocks, 256, 0, stream>>>(idx, p.k, int(p.W), R, row_ptr);
+    launch_row_starts(idx, p.k, uint32_t(p.W), R, row_ptr, stream);
     trace_mark(stream);
     const uint16_t *dy_rows = static_cast<const uint16_t *>(dY);
     if (plan.wp != p.W) {

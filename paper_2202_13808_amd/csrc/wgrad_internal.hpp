@@ -30,6 +30,48 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
 dropit_status fc_dense_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
                             float *partial, float *dW, hipStream_t stream);
 
+// Row starts of the index-sorted pairs: row_ptr[r] = number of pairs whose flat index lies before row r
+// of `row_len` consecutive elements, r = 0..R (row_ptr[R] = k).  One pass over idx: every pair is compared
+// with its predecessor and fills the row starts that fall between them; the entry j == k closes the table.
+// A thread takes four consecutive pairs (one 16-byte load when idx is 16-byte aligned) and divides each
+// index once.  Indices are below 2^31: 32-bit unsigned division (a 64-bit one is several times the instructions).
+template <bool VEC>
+static __global__ void __launch_bounds__(256)
+row_starts_kernel(const int32_t *__restrict__ idx, int64_t k, uint32_t row_len, int64_t R, uint32_t *__restrict__ row_ptr)
+{
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x * 4;
+    for (int64_t j0 = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) * 4; j0 <= k; j0 += stride) {
+        int64_t before = (j0 == 0) ? -1 : min<int64_t>(uint32_t(idx[j0 - 1]) / row_len, R);
+        int32_t v[4];
+        if (VEC && j0 + 4 <= k) {
+            const i32x4 q = *reinterpret_cast<const i32x4 *>(idx + j0);
+            v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = j0 + e < k ? idx[j0 + e] : 0;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t j = j0 + e;
+            if (j > k) break;
+            const int64_t here = (j == k) ? R : min<int64_t>(uint32_t(v[e]) / row_len, R);
+            for (int64_t r = before + 1; r <= here; ++r) row_ptr[r] = uint32_t(j);
+            before = here;
+        }
+    }
+}
+
+inline void launch_row_starts(const int32_t *idx, int64_t k, uint32_t row_len, int64_t R, uint32_t *row_ptr,
+                              hipStream_t stream)
+{
+    const int blocks = int(std::min<int64_t>((k / 4 + 1 + 255) / 256, 4096));
+    if (aligned(idx, 16))
+        row_starts_kernel<true><<<blocks, 256, 0, stream>>>(idx, k, row_len, R, row_ptr);
+    else
+        row_starts_kernel<false><<<blocks, 256, 0, stream>>>(idx, k, row_len, R, row_ptr);
+}
+
 struct ConvProblem {
     int64_t N, C, H, W, J, k;
 };

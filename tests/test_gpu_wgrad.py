@@ -216,6 +216,25 @@ def test_conv3x3_gemm_form_uneven_density(layout):
     assert_close(got, ref, TOL["bf16"])
 
 
+@pytest.mark.parametrize("conv", [CONV3, (3, 3, 2, 2, 1, 1, 1, 1)])
+def test_conv_pairs_at_a_4_byte_aligned_address_only(conv):
+    """The pair arrays need only their natural alignment: views one element into a buffer give the same dW."""
+    x = activation((3, 16, 21, 24), "relu", 61, "bf16")
+    OH, OW = (21, 24) if conv == CONV3 else (11, 12)
+    dy = gradient((3, 16, OH, OW), 0.02, 62, "bf16")
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, 0.7)
+    want = dropit.weight_grad(vals, idx, x.shape, dyd, 16, conv=conv)
+    vbuf = torch.empty(vals.numel() + 1, dtype=vals.dtype, device=vals.device)
+    ibuf = torch.empty(idx.numel() + 1, dtype=idx.dtype, device=idx.device)
+    vbuf[1:] = vals
+    ibuf[1:] = idx
+    assert ibuf[1:].data_ptr() % 16 == 4
+    got = dropit.weight_grad(vbuf[1:], ibuf[1:], x.shape, dyd, 16, conv=conv)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+
+
 def test_conv3x3_integer_values_are_exact():
     rng = np.random.default_rng(6)
     x = f32_to_bf16_bits(rng.integers(-3, 4, (2, 16, 28, 28)).astype(np.float32))
