@@ -255,39 +255,68 @@ im2col_tiled_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict
 }
 
 // dY [N][J][P] -> dYt [N * P][J]  (P = OH * OW): workgroup (n, 64 output channels, 256 positions)
-// through an LDS slab; loads run along the positions, stores along the channels (in pairs).  The odd
-// slab pitch keeps the transposed reads off each other's banks (a variant with 16-byte loads and
-// stores needs an aligned pitch and was 40 % slower for that reason).
+// through an LDS slab; loads run along the positions, stores along the channels.  PAIRS (P even):
+// a lane loads two positions (4 bytes) and stores four channels (8 bytes); the slab pitch of 129
+// words keeps both the 4-byte stores aligned and the transposed reads off each other's banks.
+// (A variant with 16-byte loads and stores needs a pitch that is a multiple of 8 and was 40 % slower
+// for the bank conflicts.)  Otherwise 2-byte loads and channel-pair stores.
 constexpr int TJ = 64, TP = 256;
+template <bool PAIRS>
 __global__ void __launch_bounds__(256)
 dy_tokens_tiled_kernel(const uint16_t *__restrict__ dY, int J, int64_t P, int jblocks, int pblocks,
                        uint16_t *__restrict__ dYt)
 {
-    __shared__ uint16_t slab[TJ][TP + 1];
+    constexpr int PITCH = PAIRS ? TP + 2 : TP + 1;
+    __shared__ __attribute__((aligned(4))) uint16_t slab[TJ][PITCH];
     const int tid = threadIdx.x;
     const int pb = blockIdx.x % pblocks;
     const int jb = (blockIdx.x / pblocks) % jblocks;
     const int64_t n = blockIdx.x / (int64_t(pblocks) * jblocks);
-    const int j0 = jb * TJ, jw = min(TJ, J - j0);
+    const int j0 = jb * TJ, jw = min(TJ, J - j0);                 // jw is a multiple of 8
     const int64_t p0 = int64_t(pb) * TP;
-    const int pw = int(min<int64_t>(TP, P - p0));
-    // thread tid reads position tid of every channel: eight loads in flight, each in a full register
+    const int pw = int(min<int64_t>(TP, P - p0));                 // even when PAIRS
     constexpr int BATCH = 8;
-    for (int jj0 = 0; jj0 < jw; jj0 += BATCH) {
-        uint32_t v[BATCH];
+    if (PAIRS) {
+        // 128 lanes cover the 256 positions of a channel; the two halves of the workgroup take alternate channels
+        const int half = tid >> 7, pp = (tid & 127) * 2;
+        for (int jj0 = half; jj0 < jw; jj0 += 2 * BATCH) {
+            uint32_t v[BATCH];
 #pragma unroll
-        for (int q = 0; q < BATCH; ++q)
-            if (jj0 + q < jw && tid < pw) v[q] = dY[(n * J + j0 + jj0 + q) * P + p0 + tid];
+            for (int q = 0; q < BATCH; ++q)
+                if (jj0 + 2 * q < jw && pp < pw)
+                    v[q] = *reinterpret_cast<const uint32_t *>(dY + (n * J + j0 + jj0 + 2 * q) * P + p0 + pp);
 #pragma unroll
-        for (int q = 0; q < BATCH; ++q)
-            if (jj0 + q < jw && tid < pw) slab[jj0 + q][tid] = uint16_t(v[q]);
-    }
-    __syncthreads();
-    uint32_t *dst = reinterpret_cast<uint32_t *>(dYt);           // J is even: a channel pair is one aligned word
-    for (int i = tid; i < TP * (TJ / 2); i += 256) {
-        const int pp = i / (TJ / 2), jj = (i % (TJ / 2)) * 2;
-        if (pp < pw && jj < jw)
-            dst[((n * P + p0 + pp) * J + j0 + jj) / 2] = uint32_t(slab[jj][pp]) | (uint32_t(slab[jj + 1][pp]) << 16);
+            for (int q = 0; q < BATCH; ++q)
+                if (jj0 + 2 * q < jw && pp < pw) *reinterpret_cast<uint32_t *>(&slab[jj0 + 2 * q][pp]) = v[q];
+        }
+        __syncthreads();
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        for (int i = tid; i < TP * (TJ / 4); i += 256) {
+            const int t = i / (TJ / 4), jj = (i % (TJ / 4)) * 4;
+            if (t < pw && jj < jw) {
+                const u32x2 o = {uint32_t(slab[jj][t]) | (uint32_t(slab[jj + 1][t]) << 16),
+                                 uint32_t(slab[jj + 2][t]) | (uint32_t(slab[jj + 3][t]) << 16)};
+                *reinterpret_cast<u32x2 *>(dYt + ((n * P + p0 + t) * J + j0 + jj)) = o;
+            }
+        }
+    } else {
+        // thread tid reads position tid of every channel: eight loads in flight, each in a full register
+        for (int jj0 = 0; jj0 < jw; jj0 += BATCH) {
+            uint32_t v[BATCH];
+#pragma unroll
+            for (int q = 0; q < BATCH; ++q)
+                if (jj0 + q < jw && tid < pw) v[q] = dY[(n * J + j0 + jj0 + q) * P + p0 + tid];
+#pragma unroll
+            for (int q = 0; q < BATCH; ++q)
+                if (jj0 + q < jw && tid < pw) slab[jj0 + q][tid] = uint16_t(v[q]);
+        }
+        __syncthreads();
+        uint32_t *dst = reinterpret_cast<uint32_t *>(dYt);       // J is even: a channel pair is one aligned word
+        for (int i = tid; i < TP * (TJ / 2); i += 256) {
+            const int t = i / (TJ / 2), jj = (i % (TJ / 2)) * 2;
+            if (t < pw && jj < jw)
+                dst[((n * P + p0 + t) * J + j0 + jj) / 2] = uint32_t(slab[jj][t]) | (uint32_t(slab[jj + 1][t]) << 16);
+        }
     }
 }
 
@@ -415,8 +444,12 @@ dropit_status conv_im2col_run(const ConvGeneral &p, const ConvIm2colPlan &plan, 
         const int64_t pblocks = (P + TP - 1) / TP;
         const int64_t grid = p.N * jblocks * pblocks;
         if (grid > INT32_MAX) return DROPIT_EINVAL;
-        dy_tokens_tiled_kernel<<<int(grid), 256, 0, stream>>>(static_cast<const uint16_t *>(dY), int(p.J), P, jblocks,
-                                                              int(pblocks), dYt);
+        if (P % 2 == 0)
+            dy_tokens_tiled_kernel<true><<<int(grid), 256, 0, stream>>>(static_cast<const uint16_t *>(dY), int(p.J), P,
+                                                                        jblocks, int(pblocks), dYt);
+        else
+            dy_tokens_tiled_kernel<false><<<int(grid), 256, 0, stream>>>(static_cast<const uint16_t *>(dY), int(p.J), P,
+                                                                         jblocks, int(pblocks), dYt);
         tokens = dYt;
     }
     trace_mark(stream);
