@@ -5,8 +5,8 @@
  * DNN Training" (arXiv 2202.13808):
  *
  *   forward  : a^ = D(a) = {a_Xr, Xr}   min-k dropping of a layer's cached
- *              input (Sec. 3.2; Sec. 3.3 "Min-K Elements"; Sec. 4.1
- *              "Implementation Details")                    -> dropit_compress
+ *              input (Sec. 3.2; Sec. 3.3, min-k strategy; Sec. 4.1,
+ *              implementation details)                      -> dropit_compress
  *   backward : grad(theta) ~= grad(z) * dl(R(a^), theta)/dtheta, the weight
  *              gradient taken on the zero-filled recovered tensor R(a^)
  *              (Sec. 3.2, Eq. conv_backward_elem / Eq. fc_backward_elem_save)
@@ -53,9 +53,9 @@ typedef enum {
 const char *dropit_status_string(dropit_status s);
 
 /*
- * Number of retained elements for dropping rate gamma (Sec. 3.3: "drop the
- * smallest gamma fraction"; Sec. 4.1: top-k "based on a proportion of
- * 1 - gamma"):  k = floor((1 - gamma) * numel), evaluated in IEEE double as
+ * Number of retained elements for dropping rate gamma (Sec. 3.3, min-k strategy: the
+ * gamma fraction of smallest magnitude is dropped; Sec. 4.1: the top-k keeps a
+ * share of 1 - gamma):  k = floor((1 - gamma) * numel), evaluated in IEEE double as
  * numel - ceil(gamma * numel).  gamma = 0 keeps everything (the baseline row of
  * Table 2), gamma = 1 keeps nothing.
  * Returns -1 if numel < 0, numel > 2^31-1, or gamma is NaN / outside [0,1].
@@ -67,7 +67,7 @@ int64_t dropit_keep_count(int64_t numel, double gamma);
 size_t dropit_compress_workspace_bytes(int64_t numel, dropit_dtype dt);
 
 /*
- * Min-k dropping D(a) (Sec. 3.2, Sec. 3.3 "Min-K Elements", Sec. 4.1).
+ * Min-k dropping D(a) (Sec. 3.2; Sec. 3.3, min-k strategy; Sec. 4.1).
  *
  * Keeps the k = dropit_keep_count(numel, gamma) elements of x with the largest
  * absolute magnitude, ranked over the whole tensor (one ranking per call, i.e.
@@ -94,7 +94,7 @@ dropit_status dropit_compress(const void *x, const int64_t *shape, int ndim, dro
 size_t dropit_compress_random_workspace_bytes(int64_t numel, dropit_dtype dt);
 
 /*
- * Random dropping D(a) (Sec. 3.3 "Random Elements": a gamma fraction of the
+ * Random dropping D(a) (Sec. 3.3, random strategy: a gamma fraction of the
  * elements of the mini-batch tensor is dropped at random; the paper's baseline
  * strategy beside min-k).
  *

@@ -7,7 +7,7 @@
  * only from the tests, the smoke check and the benchmark's cpu_baseline leg.
  *
  * What it states (paper passages in brackets):
- *   - keep count        k = floor((1-gamma)*numel)        [Sec. 4.1, "proportion of 1-gamma";
+ *   - keep count        k = floor((1-gamma)*numel)        [Sec. 4.1, a share of 1-gamma is kept;
  *                                                          Sec. 3.3 Min-K; Table 4]
  *   - min-k dropping    D(a) = {a_Xr, Xr}: keep the k elements of largest
  *                       absolute magnitude, with their indices

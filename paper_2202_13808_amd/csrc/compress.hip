@@ -1,4 +1,4 @@
-// Min-k dropping D(a) = {a_Xr, Xr} (Sec. 3.2, Sec. 3.3 "Min-K Elements", Sec. 4.1)
+// Min-k dropping D(a) = {a_Xr, Xr} (Sec. 3.2; Sec. 3.3, min-k strategy; Sec. 4.1)
 // as a bandwidth-bound radix select + ordered stream compaction for gfx950.
 //
 // The magnitude key of an element is its bit pattern with the sign cleared

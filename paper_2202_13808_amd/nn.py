@@ -1,6 +1,6 @@
 """torch.autograd integration of the DropIT hot path.
 
-The paper's implementation note (Sec. 4, "Implementation") describes the layer-level mechanism: in
+The paper's implementation note (Sec. 4, implementation paragraph) describes the layer-level mechanism: in
 the forward pass the layer's input is converted to (value, index) form and the dense input is left
 to be released; in the backward pass the sparse form is recovered for the weight gradient only
 (Sec. 3.2, 3.3).  The forward output and the gradient with respect to the input never touch the
