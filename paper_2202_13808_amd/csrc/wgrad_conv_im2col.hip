@@ -92,6 +92,7 @@ im2col_scatter_kernel(const uint16_t *__restrict__ vals, const int32_t *__restri
 #endif
 struct TileShape {
     int nblocks, blk, bands, rb, rowlen;      // column blocks, their width (channels or taps), bands, rows per band, tile row length
+    int tmin;                                 // NCHW: at least this many threads share a channel's run (a power of two)
 };
 
 template <bool NHWC>
@@ -221,12 +222,12 @@ im2col_tiled_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict
             });
         } else {
             // Each channel's pairs are a run of their own.  The 256 threads are dealt to the channels of the
-            // block in groups of T = 256 / (channels rounded up to a power of two), at most a wavefront:
-            // many channels with short runs get a thread each, a few channels with long runs a wavefront
-            // each, and in both cases every run is being read at the same time.
+            // block in groups of T = 256 / (channels rounded up to a power of two), between ts.tmin and a
+            // wavefront: a few channels with long runs get a wavefront each and are all read at the same
+            // time; many channels with short runs are taken 256 / tmin at a time.
             int cpow = 1;
             while (cpow < bw && cpow < 256) cpow <<= 1;
-            const int T = min(64, 256 / cpow);
+            const int T = min(64, max(256 / cpow, ts.tmin));
             const int grp = tid / T, sub = tid - grp * T;
             for (int c = b0 + grp; c < b0 + bw; c += 256 / T) {
                 const int64_t r0 = (int64_t(n) * g.C + c) * g.H + ih_lo;
@@ -413,7 +414,13 @@ dropit_status conv_im2col_run(const ConvGeneral &p, const ConvIm2colPlan &plan, 
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) == hipSuccess;
             }))
             return DROPIT_EHIP;
-        const TileShape ts = {plan.nblocks, plan.blk, plan.bands, plan.rb, plan.rowlen};
+        // at least 8 threads per channel run: neighbouring lanes then read neighbouring pairs (with one or two
+        // threads per run every lane of a load asks for a line of its own: 1x1 over 256 channels 144 -> 126 us)
+        int tmin = 8;
+#ifdef DROPIT_TUNING
+        if (const char *e = getenv("DROPIT_IM2COL_TMIN")) tmin = atoi(e);
+#endif
+        const TileShape ts = {plan.nblocks, plan.blk, plan.bands, plan.rb, plan.rowlen, tmin};
         const int64_t pad_chunks = (plan.gemm.ntok_pad - plan.fp.ntok) * plan.gemm.pitch / 8;
         const int pad_wgs = int(std::min<int64_t>((pad_chunks + 255) / 256, 64));
         const int grid = int(p.N * plan.nblocks * plan.bands) + pad_wgs;
