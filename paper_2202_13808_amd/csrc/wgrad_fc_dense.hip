@@ -584,6 +584,53 @@ splitk_sum_kernel(const f32x4 *__restrict__ partial, int splits, int M, int N, i
     }
 }
 
+// The same sum for many slices of few tiles (a result of one or two tiles is cut into up to 256 slices, one
+// per compute unit): 16 threads share an output group, thread p of them adds the slices p, p + 16, ... in
+// ascending order, and the 16 sums are added in ascending p through LDS -- a fixed order again, with 16
+// times the loads in flight (one thread per group took 20 us for 256 slices of a single tile).
+template <typename C>
+__global__ void __launch_bounds__(256)
+splitk_sum_wide_kernel(const f32x4 *__restrict__ partial, int splits, int M, int N, int nb_count, int mb_count,
+                       float *__restrict__ dW)
+{
+    constexpr int PARTS = 16, GPB = 16;                // slice lanes per group, groups per workgroup
+    constexpr int TILE4 = C::BM * C::BN / 4;
+    __shared__ f32x4 red[PARTS][GPB];
+    const int64_t total = int64_t(nb_count) * mb_count * TILE4;
+    const int part = threadIdx.x / GPB, gi = threadIdx.x % GPB;
+    const int64_t g = int64_t(blockIdx.x) * GPB + gi;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (g < total) {
+        for (int p0 = part; p0 < splits; p0 += 4 * PARTS) {
+            f32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (p0 + u * PARTS < splits) v[u] = partial[(p0 + u * PARTS) * total + g];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (p0 + u * PARTS < splits) s += v[u];
+        }
+    }
+    red[part][gi] = s;
+    __syncthreads();
+    if (part != 0 || g >= total) return;
+#pragma unroll
+    for (int q = 1; q < PARTS; ++q) s += red[q][gi];
+    const int tile = int(g / TILE4), r = int(g % TILE4);
+    const int tid = r % C::NTHREADS, slot = r / C::NTHREADS;   // slot = (i * FN + j) * 4 + q
+    const int q = slot & 3, j = (slot >> 2) % C::FN, i = (slot >> 2) / C::FN;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const int mb = tile / nb_count, nb = tile % nb_count;
+    const int m = mb * C::BM + wm * C::WM + i * 32 + q * 8 + (lane >> 5) * 4;
+    const int n = nb * C::BN + wn * C::WN + j * 32 + (lane & 31);
+    if (n < N) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (m + e < M) dW[int64_t(m + e) * N + n] = s[e];
+    }
+}
+
 #ifndef DROPIT_GEMM_CFG
 #define DROPIT_GEMM_CFG 256, 256, 32, 4, 2, 4, 2, 1
 #endif
@@ -611,7 +658,7 @@ int tuned_splits(int tiles, int nkb)
 #endif
     if (splits > nkb) splits = nkb;
     if (splits < 1) splits = 1;
-    if (splits > 64) splits = 64;
+    if (splits > 256) splits = 256;      // one slice per compute unit when the whole result is a single tile
     return splits;
 }
 
@@ -691,9 +738,15 @@ static dropit_status launch_gemm(const FcProblem &p, const FcDensePlan &plan, co
     trace_mark(stream);
     if (plan.splits > 1) {
         const int64_t groups = int64_t(plan.nb_count) * plan.mb_count * (C::BM * C::BN / 4);
-        const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
-        splitk_sum_kernel<C><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
-                                                         int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
+        if (plan.splits > 16) {
+            splitk_sum_wide_kernel<C><<<int((groups + 15) / 16), 256, 0, stream>>>(
+                reinterpret_cast<const f32x4 *>(partial), plan.splits, int(p.cout), int(p.cin), plan.nb_count,
+                plan.mb_count, dW);
+        } else {
+            const int blocks = int(std::min<int64_t>((groups + 255) / 256, 1 << 20));   // one group per thread
+            splitk_sum_kernel<C><<<blocks, 256, 0, stream>>>(reinterpret_cast<const f32x4 *>(partial), plan.splits,
+                                                             int(p.cout), int(p.cin), plan.nb_count, plan.mb_count, dW);
+        }
     }
     trace_mark(stream);
     return launch_status();
