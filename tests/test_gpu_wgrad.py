@@ -70,6 +70,9 @@ def test_fc_shapes(dtype, ntok, cin, cout, gamma):
     (2000, 3000, 8, 0.95),    # many column tiles, one narrow row tile
     (9000, 512, 512, 0.9),    # several K-slices per tile
     (640, 40000, 8, 0.9),     # c_in beyond what the recover kernel holds in LDS: generic path
+    (20000, 200, 64, 0.9),    # the whole result is one 128-row tile: 31 K-slices, added by the many-slice kernel
+    (70000, 64, 8, 0.8),      # ... 109 slices of a nearly empty tile
+    (6000, 300, 136, 0.9),    # just over 128 output channels: the wide tile, two column tiles
 ])
 def test_fc_bf16_tile_edges(ntok, cin, cout, gamma):
     print("wgrad fc edges", ntok, cin, cout, gamma, flush=True)
