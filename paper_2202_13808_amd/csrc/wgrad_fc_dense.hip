@@ -97,6 +97,60 @@ fc_recover_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__
     for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
 }
 
+// Recover from the row form of the cache (16-bit positions within rows + row offsets): the offsets say
+// where a workgroup's rows start among the pairs, so there is nothing to guess or search, and a pair's
+// place in its row is its 16-bit position as it stands.  Which row a pair belongs to follows from the
+// offsets of the workgroup's rows, kept in LDS behind the tile.
+__global__ void __launch_bounds__(RECOVER_THREADS)
+fc_recover_rows_kernel(const uint16_t *__restrict__ vals, const uint16_t *__restrict__ col,
+                       const int32_t *__restrict__ rowptr, int64_t k, int64_t ntok, int64_t ntok_pad, int cin,
+                       int pitch, int rows_per_wg, uint16_t *__restrict__ dense)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [rows_per_wg][pitch], then rows_per_wg + 1 offsets
+    const int tid = threadIdx.x;
+    const int64_t r0 = int64_t(blockIdx.x) * rows_per_wg;
+    const int64_t r1 = min(r0 + rows_per_wg, ntok_pad);
+    const int rows = int(r1 - r0);
+    const int chunks = rows * (pitch / 8);                            // 16-byte units
+    u32x4 *tile16 = reinterpret_cast<u32x4 *>(tile);
+    int32_t *starts = reinterpret_cast<int32_t *>(tile + size_t(rows_per_wg) * pitch);
+    const int64_t q0 = min(r0, ntok);
+    const int real = int(min(r1, ntok) - q0);                         // rows that exist in the tensor (the rest is padding)
+    for (int i = tid; i <= real; i += RECOVER_THREADS)
+        starts[i] = int32_t(min<int64_t>(max<int64_t>(rowptr[q0 + i], 0), k));   // a malformed table must not read outside the pairs
+    for (int i = tid; i < chunks; i += RECOVER_THREADS) tile16[i] = u32x4{0, 0, 0, 0};
+    __syncthreads();
+    if (real > 0) {
+        const int64_t jb = starts[0], je = starts[real];
+        constexpr int BATCH = 8;
+        for (int64_t j0 = jb + tid; j0 < je; j0 += int64_t(BATCH) * RECOVER_THREADS) {
+            uint32_t pc[BATCH], pv[BATCH];                            // full registers: 16-bit destinations get packed in pairs
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
+                if (j < je) {
+                    pc[u] = col[j];
+                    pv[u] = vals[j];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int64_t j = j0 + int64_t(u) * RECOVER_THREADS;
+                if (j >= je) continue;
+                int lo = 0, hi = real - 1;                            // the last row i with starts[i] <= j
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (int64_t(starts[mid]) <= j) lo = mid; else hi = mid - 1;
+                }
+                if (pc[u] < uint32_t(cin)) tile[size_t(lo) * pitch + pc[u]] = static_cast<uint16_t>(pv[u]);
+            }
+        }
+    }
+    __syncthreads();
+    u32x4 *out16 = reinterpret_cast<u32x4 *>(dense + r0 * pitch);
+    for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
+}
+
 // Recover for large k: the error of the interpolated guess grows with sqrt(k) (and with the ties at
 // the threshold, which are all kept at the low-index end of the tensor), the pairs of a tile do not, so
 // a window per tile would be mostly overlap -- and an exact search per tile costs ~500 scattered probes
@@ -717,6 +771,9 @@ static bool fc_dense_attributes()
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_stream_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                    RECOVER_ELEMS_MAX * 2) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_rows_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   RECOVER_ELEMS_MAX * 2 + (RECOVER_ELEMS_MAX / 8 + 1) * 4) == hipSuccess &&
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess &&
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<CfgNarrow>),
@@ -792,6 +849,22 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
             tiles_per_wg, dense);
     }
 
+    trace_mark(stream);
+    return fc_dense_gemm(p, plan, dY, dense, partial, dW, stream);
+}
+
+dropit_status fc_dense_run_rows(const FcProblem &p, const FcDensePlan &plan, const void *vals, const uint16_t *col,
+                                const int32_t *rowptr, const void *dY, float *dW, char *ws, hipStream_t stream)
+{
+    uint16_t *dense = reinterpret_cast<uint16_t *>(ws);
+    float *partial = reinterpret_cast<float *>(ws + plan.dense_bytes);
+    if (!fc_dense_attributes()) return DROPIT_EHIP;
+    trace_mark(stream);
+    const int grid = int((plan.ntok_pad + plan.rows_per_wg - 1) / plan.rows_per_wg);
+    const size_t lds = size_t(plan.rows_per_wg) * plan.pitch * 2 + size_t(plan.rows_per_wg + 1) * 4;
+    fc_recover_rows_kernel<<<grid, RECOVER_THREADS, lds, stream>>>(
+        static_cast<const uint16_t *>(vals), col, rowptr, p.k, p.ntok, plan.ntok_pad, int(p.cin), plan.pitch,
+        plan.rows_per_wg, dense);
     trace_mark(stream);
     return fc_dense_gemm(p, plan, dY, dense, partial, dW, stream);
 }

@@ -25,6 +25,10 @@ FcDensePlan fc_dense_plan(const FcProblem &p);
 dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
                            const void *dY, float *dW, char *ws, hipStream_t stream);
 
+// the same from the row form of the cache (col = position in the row, rowptr = pairs before each row)
+dropit_status fc_dense_run_rows(const FcProblem &p, const FcDensePlan &plan, const void *vals, const uint16_t *col,
+                                const int32_t *rowptr, const void *dY, float *dW, char *ws, hipStream_t stream);
+
 // the GEMM and the K-slice sum alone, on operands that are already dense: dY [ntok][cout], dense [plan.ntok_pad][plan.pitch]
 // (rows past ntok zero); `partial` holds plan.partial_bytes
 dropit_status fc_dense_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
