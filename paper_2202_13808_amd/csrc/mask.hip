@@ -12,6 +12,7 @@
 #include <algorithm>
 
 #include "common.hpp"
+#include "wgrad_internal.hpp"
 
 namespace dropit {
 namespace {
@@ -153,6 +154,19 @@ extern "C" dropit_status dropit_weight_grad_mask(const void *vals, const uint32_
         return DROPIT_EWORKSPACE;
     int32_t *idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + round_up(inner, 256));
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // A bf16 fully-connected layer on the matrix cores recovers straight from the mask (c_in % 8 == 0: the
+    // recovered matrix has the tensor's own layout).  Everything else expands the flat indices first.
+    if (conv == nullptr && dt == DROPIT_BF16 && k > 0 && c_out >= 1) {
+        const int64_t cin = x_shape[ndim - 1];
+        const FcProblem fp = {numel / cin, cin, c_out, k};
+        if (fc_dense_mask_native(fp)) {
+            if (vals == nullptr || !aligned(vals, 2)) return DROPIT_EINVAL;
+            if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
+            const FcDensePlan plan = fc_dense_plan(fp);
+            if (plan.total() > inner) return DROPIT_EWORKSPACE;
+            return fc_dense_run_mask(fp, plan, vals, mask, blockptr, dY, dW, static_cast<char *>(workspace), stream);
+        }
+    }
     if (k > 0) {
         trace_mark(stream);
         const int64_t blocks = mask_blocks(numel);

@@ -151,6 +151,47 @@ fc_recover_rows_kernel(const uint16_t *__restrict__ vals, const uint16_t *__rest
     for (int i = tid; i < chunks; i += RECOVER_THREADS) out16[i] = tile16[i];
 }
 
+// Recover from the bit-mask form of the cache (one bit per element + the number of retained elements
+// before every block of 1024): pure streaming.  A thread takes 8 consecutive elements, i.e. one byte of
+// the mask; the retained ones among them are the next popcount(byte) values after the block's offset
+// plus the bits set before the byte within the block (a prefix sum over the block's 128 threads).
+// Needs pitch == c_in (c_in % 8 == 0): the recovered matrix then has the tensor's own flat layout.
+__global__ void __launch_bounds__(256)
+fc_recover_mask_kernel(const uint16_t *__restrict__ vals, const uint32_t *__restrict__ mask,
+                       const int32_t *__restrict__ blockptr, int64_t k, int64_t numel, int64_t dense_elems,
+                       uint16_t *__restrict__ dense)
+{
+    static_assert(DROPIT_MASK_BLOCK == 1024, "a block is the 8 x 128 elements of half a workgroup");
+    __shared__ uint32_t first_wave_total[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t e0 = (int64_t(blockIdx.x) * 256 + tid) * 8;
+    const int64_t block = e0 / DROPIT_MASK_BLOCK;
+    const uint32_t byte = e0 < numel ? (mask[e0 >> 5] >> (e0 & 31)) & 0xFFu : 0u;
+    const uint32_t c = __builtin_popcount(byte);
+    const uint32_t inc = wave_inclusive_scan(c);
+    if ((wave & 1) == 0 && lane == 63) first_wave_total[wave >> 1] = inc;
+    __syncthreads();
+    const uint32_t before = inc - c + ((wave & 1) ? first_wave_total[wave >> 1] : 0u);
+    if (e0 >= dense_elems) return;
+    const int64_t base = (e0 < numel ? int64_t(blockptr[block]) : 0) + before;
+    uint32_t v[8];                                                    // full registers: 16-bit destinations get packed in pairs
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (uint32_t(i) < c && base + i >= 0 && base + i < k) ? vals[base + i] : 0u;
+    uint32_t out[8];
+    int taken = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bool set = (byte >> e) & 1u;
+        uint32_t val = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val = (set && taken == i) ? v[i] : val;
+        out[e] = val;
+        taken += set ? 1 : 0;
+    }
+    const u32x4 o = {out[0] | (out[1] << 16), out[2] | (out[3] << 16), out[4] | (out[5] << 16), out[6] | (out[7] << 16)};
+    *reinterpret_cast<u32x4 *>(dense + e0) = o;
+}
+
 // Recover for large k: the error of the interpolated guess grows with sqrt(k) (and with the ties at
 // the threshold, which are all kept at the low-index end of the tensor), the pairs of a tile do not, so
 // a window per tile would be mostly overlap -- and an exact search per tile costs ~500 scattered probes
@@ -849,6 +890,22 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
             tiles_per_wg, dense);
     }
 
+    trace_mark(stream);
+    return fc_dense_gemm(p, plan, dY, dense, partial, dW, stream);
+}
+
+bool fc_dense_mask_native(const FcProblem &p) { return fc_dense_supported(p) && p.cin % 8 == 0; }
+
+dropit_status fc_dense_run_mask(const FcProblem &p, const FcDensePlan &plan, const void *vals, const uint32_t *mask,
+                                const int32_t *blockptr, const void *dY, float *dW, char *ws, hipStream_t stream)
+{
+    uint16_t *dense = reinterpret_cast<uint16_t *>(ws);
+    float *partial = reinterpret_cast<float *>(ws + plan.dense_bytes);
+    if (!fc_dense_attributes() || plan.pitch != p.cin) return DROPIT_EHIP;
+    trace_mark(stream);
+    const int64_t dense_elems = plan.ntok_pad * plan.pitch;          // a multiple of 8
+    fc_recover_mask_kernel<<<int((dense_elems + 2047) / 2048), 256, 0, stream>>>(
+        static_cast<const uint16_t *>(vals), mask, blockptr, p.k, p.ntok * p.cin, dense_elems, dense);
     trace_mark(stream);
     return fc_dense_gemm(p, plan, dY, dense, partial, dW, stream);
 }

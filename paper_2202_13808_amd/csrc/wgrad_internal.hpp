@@ -29,6 +29,12 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
 dropit_status fc_dense_run_rows(const FcProblem &p, const FcDensePlan &plan, const void *vals, const uint16_t *col,
                                 const int32_t *rowptr, const void *dY, float *dW, char *ws, hipStream_t stream);
 
+// ... and from the bit-mask form (mask bit per element, blockptr = pairs before each block of DROPIT_MASK_BLOCK);
+// only when fc_dense_mask_native(p): c_in % 8 == 0
+bool fc_dense_mask_native(const FcProblem &p);
+dropit_status fc_dense_run_mask(const FcProblem &p, const FcDensePlan &plan, const void *vals, const uint32_t *mask,
+                                const int32_t *blockptr, const void *dY, float *dW, char *ws, hipStream_t stream);
+
 // the GEMM and the K-slice sum alone, on operands that are already dense: dY [ntok][cout], dense [plan.ntok_pad][plan.pitch]
 // (rows past ntok zero); `partial` holds plan.partial_bytes
 dropit_status fc_dense_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
