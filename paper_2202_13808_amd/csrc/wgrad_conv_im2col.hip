@@ -10,8 +10,10 @@
 //   NCHW: x [N][C][H][W], dY [N][J][OH][OW];  col = (c*kh + u)*kw + v   ->  dW [J][C][kh][kw]
 //   NHWC: x [N][H][W][C], dY [N][OH][OW][J];  col = (u*kw + v)*C + c    ->  dW [J][kh][kw][C]
 //
-// B is zero-filled and then written straight from the (value, index) pairs: a retained element
-// lands in every (token, tap) whose window covers it, at most ceil(kh/sh) * ceil(kw/sw) places.
+// B is written straight from the (value, index) pairs: a retained element lands in every
+// (token, tap) whose window covers it, at most ceil(kh/sh) * ceil(kw/sw) places.  Normally B is
+// assembled in LDS tiles and written once in full lines (im2col_tiled_kernel); where no aligned
+// tiling exists it is zero-filled and scattered into (im2col_scatter_kernel).
 // In NHWC dY is token-major already; in NCHW a tiled transposition makes it so.  The 3x3 / stride 1
 // / pad 1 NCHW case has kernels of its own (wgrad_conv_mfma.hip, wgrad_conv_gemm.hip) that never
 // materialise the nine-fold B; this path serves everything else: 1x1, strided, dilated, large-window
