@@ -53,8 +53,11 @@ struct SelState {
     uint32_t error;      // hint: some workgroup ran out of patience at a grid barrier (the others stop waiting)
     uint32_t exited;     // fused kernel: low 16 bits = workgroups done, high 16 bits = how many of them gave up
     uint32_t path;       // fused kernel, for the tests: 0 exact digit histograms, 1 sampled bracket confirmed, 2 sampled bracket missed (exact retry)
-    unsigned long long ready;    // == the call's generation number once workgroup 0 has cleared the words above and the histograms
-    uint32_t pad[50];
+    unsigned long long ready;    // == the call's generation number once workgroup 0 has cleared the words above and the histograms;
+                                 // the last workgroup to leave puts 0 back (no generation is 0), so a launch replayed with
+                                 // the same number (a captured graph) waits for its own workgroup 0 again
+    uint32_t redo;       // fused kernel, for callers and tests: 1 if the grid barriers gave up and the last workgroup redid the selection alone
+    uint32_t pad[49];
 };
 static_assert(sizeof(SelState) == 256, "state block is 256 bytes");
 
@@ -418,7 +421,13 @@ compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vp
 // device-wide fence is needed: on this 8-XCD part such a fence writes back and
 // invalidates a whole L2 and was measured at 5-8 us per grid barrier.
 constexpr int FUSED_RES = 6;             // 16-byte vectors per thread parked in LDS
-constexpr uint32_t SPIN_LIMIT = 1u << 22;   // grid-barrier patience in polls (~0.1 us each); every wave exits even if it runs out
+// Patience in polls (~0.25 us each); every wave exits even if it runs out.  A resident grid meets at a barrier within
+// microseconds (a millisecond for the largest tensors), so the barriers give up after ~15 ms: a grid that is not
+// resident all at once then costs those milliseconds plus the serial redo, not a second.  Waiting for workgroup 0's
+// clearing pass is another matter: it is dispatched first and needs a few microseconds, and a workgroup that stops
+// waiting for it leaves the exit count short (nobody then puts `ready` back to 0), so that wait is long.
+constexpr uint32_t SPIN_LIMIT = 1u << 16;
+constexpr uint32_t READY_SPIN_LIMIT = 1u << 26;
 
 __device__ inline uint32_t dev_load(const uint32_t *p)
 {
@@ -662,6 +671,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                 dev_store(&st->barrier, 0u);
                 dev_store(&st->error, 0u);
                 dev_store(&st->exited, 0u);
+                dev_store(&st->redo, 0u);
             }
             if (tid < 8)
                 dev_store(reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(st) + SelWorkspace::xbar_off) + tid * 64, 0u);
@@ -737,7 +747,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         if (tid == 0) {
             uint32_t spins = 0, ok = 1;
             while (dev_load64(&st->ready) != gen) {
-                if (++spins > SPIN_LIMIT) {      // workgroup 0 never ran: not this workgroup's patience setting
+                if (++spins > READY_SPIN_LIMIT) {      // workgroup 0 never ran: not this workgroup's patience setting
                     ok = 0;
                     break;
                 }
@@ -1218,7 +1228,14 @@ select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64
         if (outcome != SEL_NEVER_READY) {
             const uint32_t mine = outcome == SEL_DONE ? 1u : 0x10001u;
             const uint32_t seen = __hip_atomic_fetch_add(&st->exited, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
-            s_redo = ((seen & 0xFFFFu) == gridDim.x && (seen >> 16) != 0) ? 1u : 0u;
+            const bool last = (seen & 0xFFFFu) == gridDim.x;
+            s_redo = (last && (seen >> 16) != 0) ? 1u : 0u;
+            if (last) {
+                // Nobody looks at the exchange area any more: un-publish it, so that the next launch that carries the
+                // same generation number (a replay of a captured graph) cannot take this call's leftovers for its own.
+                dev_store64(&st->ready, 0ull);
+                if (s_redo) dev_store(&st->redo, 1u);
+            }
         }
     }
     __syncthreads();

@@ -343,3 +343,58 @@ def test_select_in_a_hip_graph(mode):
             assert to_host(vals).tobytes() == want_v.tobytes(), replay
     finally:
         dropit.set_select_mode(0)
+
+
+@pytest.mark.parametrize("numel", [123457, (1 << 21) + 4099])
+def test_graph_replays_over_changing_inputs_with_an_untouched_workspace(numel):
+    """The real use of a captured training step: the same graph (hence the same kernel arguments, the persistent
+    kernel's per-call number included) replayed while the activations change in place and nobody touches the
+    workspace in between.  Every replay must give the oracle's bytes for the input it saw; the larger size takes
+    the sampled form."""
+    dists = ["gelu", "normal", "relu", "gelu"]
+    xs = [activation((numel,), d, 90 + i, "bf16") for i, d in enumerate(dists)]
+    xs[3] = f32_to_bf16_bits(np.random.default_rng(5).standard_normal(numel, dtype=np.float32) * 1000.0)   # the threshold moves far away
+    k = dropit.keep_count(numel, 0.9)
+    want = [oracle.compress(x, k) for x in xs]
+    xd = to_device(xs[0])
+    vals = torch.zeros(k, dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.zeros(k, dtype=torch.int32, device="cuda:0")
+    ws = torch.empty(dropit.compress_workspace_bytes(numel, xd.dtype), dtype=torch.uint8, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dropit.compress(xd, 0.9, vals=vals, idx=idx, workspace=ws)           # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        dropit.compress(xd, 0.9, vals=vals, idx=idx, workspace=ws)
+    for replay in range(8):
+        which = replay % len(xs)
+        xd.copy_(to_device(xs[which]))                                       # new activations, in place
+        vals.zero_()
+        idx.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(idx), want[which][1]), (replay, which)
+        assert to_host(vals).tobytes() == want[which][0].tobytes(), (replay, which)
+
+
+def test_forced_redo_is_reported():
+    """White box: word 14 of the state block says whether the grid barriers gave up and the last workgroup redid
+    the selection alone (mode 3 forces that); an ordinary call reports 0."""
+    x = activation((300003,), "gelu", 17, "bf16")
+    xd = to_device(x)
+    k = oracle.keep_count(x.size, 0.9)
+    want_v, want_i = oracle.compress(x, k)
+    for mode, expect in ((0, 0), (3, 1), (0, 0)):
+        ws = torch.full((dropit.compress_workspace_bytes(x.size, xd.dtype),), 0xA5, dtype=torch.uint8, device="cuda:0")
+        dropit.set_select_mode(mode)
+        try:
+            vals, idx = dropit.compress(xd, 0.9, workspace=ws)
+            torch.cuda.synchronize()
+        finally:
+            dropit.set_select_mode(0)
+        assert np.array_equal(to_host(idx), want_i) and to_host(vals).tobytes() == want_v.tobytes()
+        assert int(ws[:64].cpu().numpy().view(np.uint32)[14]) == expect, mode
