@@ -29,6 +29,7 @@
 // barriers.  Nothing here synchronises with the host; counts are integer, so the
 // result does not depend on the order in which workgroups run.
 #include "common.hpp"
+#include "dev_hooks.hpp"
 #include <atomic>
 #include <cstdlib>
 #include <random>
@@ -57,7 +58,8 @@ struct SelState {
                                  // the last workgroup to leave puts 0 back (no generation is 0), so a launch replayed with
                                  // the same number (a captured graph) waits for its own workgroup 0 again
     uint32_t redo;       // fused kernel, for callers and tests: 1 if the grid barriers gave up and the last workgroup redid the selection alone
-    uint32_t pad[49];
+    uint32_t staged;     // fused kernel, for the tests: how many workgroups compacted from candidates staged in LDS (one read of x)
+    uint32_t pad[48];
 };
 static_assert(sizeof(SelState) == 256, "state block is 256 bytes");
 
@@ -461,9 +463,15 @@ __device__ inline bool grid_barrier(SelState *st, uint32_t *xbar, uint32_t round
     if (threadIdx.x == 0) {
         const uint32_t G = gridDim.x, group = blockIdx.x & 7u;
         const uint32_t groups = G < 8u ? G : 8u, members = (G - group + 7u) / 8u;
+#ifdef DROPIT_RELACQ
+        const uint32_t before = __hip_atomic_fetch_add(&xbar[group * 64], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (before + 1 == round * members)
+            __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+#else
         const uint32_t before = __hip_atomic_fetch_add(&xbar[group * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (before + 1 == round * members)
             __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
         uint32_t spins = 0, ok = 1;
         while (dev_load(&st->barrier) < round * groups) {
             if (++spins > spin_limit || ((spins & 31u) == 0 && dev_load(&st->error) != 0)) {
@@ -473,6 +481,9 @@ __device__ inline bool grid_barrier(SelState *st, uint32_t *xbar, uint32_t round
             }
             __builtin_amdgcn_s_sleep(8);        // ~0.2 us between polls: 256 pollers on one word compete with the arrivals
         }
+#ifdef DROPIT_RELACQ
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
         *ok_slot = ok;
     }
     __syncthreads();
@@ -592,6 +603,56 @@ __device__ inline bool sample_bracket(const uint32_t *hist, uint32_t k, int64_t 
     return ok;
 }
 
+// ---- one read of x: candidates staged in LDS (16-bit element types, sampled bracket) ----------------
+// With the bracket [key_lo, key_lo + nf) known BEFORE the pass over the chunk, everything that can still
+// be kept is known too: the elements with key >= key_lo, a share of (1 - gamma) plus the bracket's width
+// (11-15 % at gamma = 0.9).  The pass therefore stages them in LDS, in flat-index order, as one word each
+// (value << 16 | position), and both the exact counts and the compaction then walk the staged words
+// instead of reading x again -- x is read from memory exactly once, whatever the tensor size.
+// Each wavefront owns a contiguous 1/16 of the chunk and a staging segment of its own, so the pass needs
+// no workgroup barrier: a wavefront loads ST_U x 64 vectors (coalesced), turns them through a private
+// LDS buffer so that every lane holds ST_U CONSECUTIVE vectors (flat order = lane order: one wavefront
+// scan of the per-lane candidate counts gives every candidate its slot), and copies the candidates out
+// of that buffer.  The buffer is padded by 16 bytes per 128 so that both the coalesced writes and the
+// 32-byte-per-lane reads are free of bank conflicts.
+// A chunk with more candidates than a segment holds (values that bunch up along the tensor; tensors
+// beyond ~110 MB) takes the two-read form below for that workgroup; the bytes written are the same.
+constexpr int ST_U = 2;                                    // vectors per lane per block
+constexpr int ST_BLKV = ST_U * WAVE;                       // vectors per block (1024 16-bit elements)
+constexpr int ST_EPL = ST_U * 8;                           // elements per lane per block
+constexpr int ST_TRANS_BYTES = ST_BLKV * 16 + (ST_BLKV / 8) * 16;
+constexpr int ST_LH_OFF = (SEL_THREADS / WAVE) * ST_TRANS_BYTES;
+constexpr int ST_STAGE_OFF = ST_LH_OFF + 256;
+constexpr size_t FUSED_SMEM_BYTES = 156 * 1024;            // of the 160 KB of a compute unit; the rest is static
+constexpr int ST_SEGCAP = int((FUSED_SMEM_BYTES - ST_STAGE_OFF) / 4 / (SEL_THREADS / WAVE));   // staged words per wavefront
+static_assert(ST_STAGE_OFF + 4 * ((1 << 11) + 2 * WAVE) <= int(FUSED_SMEM_BYTES), "the exact retry's histogram fits behind ST_LH_OFF");
+static_assert(ST_STAGE_OFF % 16 == 0 && ST_SEGCAP % 4 == 0, "staged words are read four at a time");
+
+// bit b of the result: element b of the ST_EPL consecutive 16-bit elements in r[] has key >= key_lo.
+// Per 32-bit word: one AND clears both signs, one unsigned compare per half (the upper half against
+// key_lo << 16: the lower half cannot change the outcome), and an add-with-carry shifts each outcome
+// into the mask; the elements are taken last to first so that element 0 ends in bit 0.
+__device__ inline uint32_t candidate_mask(const u32x4 (&r)[ST_U], uint32_t key_lo)
+{
+    uint32_t mask = 0, k;
+    const uint32_t lo = key_lo, hi = key_lo << 16;
+#pragma unroll
+    for (int u = ST_U - 1; u >= 0; --u)
+#pragma unroll
+        for (int w = 3; w >= 0; --w) {
+            const uint32_t word = r[u][w];
+            asm("v_and_b32 %1, 0x7fff7fff, %2\n\t"
+                "v_cmp_le_u32 vcc, %4, %1\n\t"
+                "v_addc_co_u32 %0, vcc, %0, %0, vcc\n\t"
+                "v_cmp_le_u16 vcc, %3, %1\n\t"
+                "v_addc_co_u32 %0, vcc, %0, %0, vcc"
+                : "+v"(mask), "=&v"(k)
+                : "v"(word), "s"(lo), "s"(hi)
+                : "vcc");
+        }
+    return mask;
+}
+
 // The parallel selection.  Returns (the same in every thread) SEL_DONE, or SEL_GAVE_UP if a grid
 // barrier ran out of patience, or SEL_NEVER_READY if the exchange area was never published; in the
 // last two cases the outputs are incomplete (whatever was written is correct, nothing is out of bounds).
@@ -616,7 +677,6 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     extern __shared__ __attribute__((aligned(16))) u32x4 dyn_smem[];
     u32x4 *res = dyn_smem;                                            // [FUSED_RES][SEL_THREADS]
     uint32_t *smem = reinterpret_cast<uint32_t *>(dyn_smem + FUSED_RES * SEL_THREADS);
-    uint32_t *lh = smem;
     int32_t *stage_idx = reinterpret_cast<int32_t *>(smem);
     RAW *stage_val = reinterpret_cast<RAW *>(smem + TILE);
     __shared__ uint32_t bcast[4];
@@ -629,25 +689,58 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
     const int64_t v0 = static_cast<int64_t>(blockIdx.x) * vpc;
     const int64_t v1 = min(v0 + vpc, nvf);
 
-#ifdef DROPIT_TUNING
-    int stamp_i = 0;
-#define STAMP() do { if (tid == 0 && blockIdx.x == gridDim.x / 2) reinterpret_cast<unsigned long long *>(st->pad + 6)[stamp_i] = wall_clock64(); ++stamp_i; } while (0)
-#else
-#define STAMP() do { } while (0)
-#endif
-    STAMP();
+    // development builds only: phase time stamps of one workgroup into the state block's spare words
+    [[maybe_unused]] unsigned long long *stamps = reinterpret_cast<unsigned long long *>(st->pad + 6);
+#define STAMP(i) DROPIT_DEV_STAMP(stamps, i, tid == 0 && blockIdx.x == gridDim.x / 2)
+    STAMP(0);
 
-    // ---- park the head of the chunk in LDS (each thread only ever reads its own slots) --
-    const int nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
     const bool sampling = !F32 && numel >= SAMPLE_MIN_NUMEL;       // uniform over the grid
     // The threshold lies in the key range [key_lo, key_lo + nf): predicted from the sample here (16-bit
     // types, large tensors), else (or if the prediction fails) exactly known after the digit histograms.
     uint32_t key_lo = 0, nf = LB;
     bool predicted = false;
+
+    // ---- the staged form's geometry: wavefront `wave` owns vectors [wv0, wv1) of the chunk --------------
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    const int64_t vpw = ((vpc + NW - 1) / NW + 7) / 8 * 8;          // wavefront ranges start on 128-byte lines
+    const int64_t wv0 = min(v0 + int64_t(wave) * vpw, v1), wv1 = min(wv0 + vpw, v1);
+    const int nblk = static_cast<int>((wv1 - wv0 + ST_BLKV - 1) / ST_BLKV);
+    // uniform over the grid: a position within a wavefront's range must fit the 16 bits of a staged word
+    bool staged = !F32 && sampling && vpw * VEC <= 65536;
+    char *dyn_bytes = reinterpret_cast<char *>(dyn_smem);
+    uint32_t *lh = staged ? reinterpret_cast<uint32_t *>(dyn_bytes + ST_LH_OFF) : smem;
+    uint32_t *seg = reinterpret_cast<uint32_t *>(dyn_bytes + ST_STAGE_OFF) + wave * ST_SEGCAP;
+    __shared__ uint32_t wcount[NW];                                  // staged words per wavefront
+    __shared__ uint32_t whist[F32 ? 1 : NW][MAX_LAST_BINS + 1];      // per wavefront: staged keys on each key of the range, and above it
+    __shared__ uint32_t overflow;                                    // some wavefront's segment was too small
+    u32x4 qa[ST_U], qb[ST_U];                                        // two blocks of the wavefront's range in flight
+    auto issue_block = [&](u32x4 (&q)[ST_U], int blk) {
+#pragma unroll
+        for (int u = 0; u < ST_U; ++u)
+            q[u] = xv[min(wv0 + int64_t(blk) * ST_BLKV + u * WAVE + lane, nvf - 1)];
+    };
+
+    // ---- park the head of the chunk in LDS (each thread only ever reads its own slots) --
+    int nres = 0;
+    auto park = [&]() {
+        nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
+        if (nvf > 0) {
+            u32x4 q[FUSED_RES];
+#pragma unroll
+            for (int i = 0; i < FUSED_RES; ++i)     // unconditional, clamped: all loads in flight at once
+                q[i] = xv[min(v0 + int64_t(i) * SEL_THREADS + tid, nvf - 1)];
+#pragma unroll
+            for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
+        }
+    };
     {
         u32x4 q[FUSED_RES];
         u32x4 sq[SAMPLE_VECTORS_PER_THREAD];
-        if (nvf > 0) {
+        if (staged) {
+            if (nblk > 0) issue_block(qa, 0);
+            if (nblk > 1) issue_block(qb, 1);
+        } else if (nvf > 0) {
+            nres = static_cast<int>(min<int64_t>(FUSED_RES, (max<int64_t>(v1 - v0, 0) + SEL_THREADS - 1) / SEL_THREADS));
 #pragma unroll
             for (int i = 0; i < FUSED_RES; ++i)     // unconditional, clamped: all loads in flight at once
                 q[i] = xv[min(v0 + int64_t(i) * SEL_THREADS + tid, nvf - 1)];
@@ -672,19 +765,22 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                 dev_store(&st->error, 0u);
                 dev_store(&st->exited, 0u);
                 dev_store(&st->redo, 0u);
+                dev_store(&st->staged, 0u);
             }
             if (tid < 8)
                 dev_store(reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(st) + SelWorkspace::xbar_off) + tid * 64, 0u);
             __syncthreads();                    // every wave has waited for its stores
             if (tid == 0) dev_store64(&st->ready, gen);
         }
-        if (nvf > 0) {
+        if (!staged && nvf > 0) {
 #pragma unroll
             for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = q[i];
         }
-        STAMP();
+        STAMP(8);
         if (sampling) {
             constexpr int NB = 1 << BITS1;
+            // the sample's histogram: where the digit histograms live, which in the staged form lies behind
+            // the transposition buffers and reaches into the (still empty) staging segments
             for (int i = tid; i < NB + WAVE; i += SEL_THREADS) lh[i] = 0;
             __syncthreads();
 #pragma unroll
@@ -694,6 +790,7 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                     atomicAdd(&lh[dgt ? dgt : NB + lane], 1u);          // exact zeros go to per-lane slots
                 });
             __syncthreads();
+            STAMP(9);
             if (tid < WAVE) {
                 const uint32_t z = wave_sum(lh[NB + tid]);
                 if (tid == 0) lh[0] += z;
@@ -705,6 +802,11 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
                 key_lo = b_lo << SHIFT1;                                // a first-digit bin is 2^SHIFT1 = 2^LAST_BITS keys
                 nf = (b_hi - b_lo + 1) << SHIFT1;
             }
+        }
+        if (staged && !predicted) {     // no usable bracket (uniform over the grid): the exact form, with the head parked after all
+            staged = false;
+            lh = smem;
+            park();
         }
     }
     const int64_t v_stream = v0 + int64_t(nres) * SEL_THREADS;        // first vector that is not parked
@@ -787,14 +889,13 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             const uint32_t c = lh[i];
             if (c) atomicAdd(&ghist[i], c);
         }
-        STAMP();
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
-        STAMP();
         return SEL_DONE;
     };
 
     bool missed = false;
-    if (sampling) STAMP();
+    bool use_staged = false;     // this workgroup's candidates are all staged in LDS (uniform over the workgroup)
+    STAMP(1);
     uint32_t t = 0, m = 0;
     for (;;) {
         if (!predicted) {
@@ -813,13 +914,111 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             }
             key_lo = prefix << LAST_BITS;
             nf = LB;
-            STAMP();
+            STAMP(2);
         }
 
         // ---- exact counts over the range and above it, per chunk ----------------------
         for (int i = tid; i <= static_cast<int>(nf); i += SEL_THREADS) lh[i] = 0;
+        if (tid == 0) overflow = 0;
         __syncthreads();
-        {
+        bool counted = false;
+        if constexpr (!F32) {
+            if (staged && predicted) {
+                // One pass over the wavefront's range: candidates (key >= key_lo) staged in flat-index order.
+                const uint32_t key_lo_s = __builtin_amdgcn_readfirstlane(key_lo);
+                char *tb = dyn_bytes + wave * ST_TRANS_BYTES;                   // this wavefront's transposition buffer
+                char *mine = tb + lane * (ST_U * 16) + ((lane * ST_U) >> 3) * 16;   // this lane's ST_U consecutive vectors in it
+                uint32_t n_w = 0;
+                bool full = false;
+                auto process = [&](u32x4 (&q)[ST_U], int blk) {
+#pragma unroll
+                    for (int u = 0; u < ST_U; ++u) {
+                        const int vi = u * WAVE + lane;                        // as loaded: lane after lane
+                        *reinterpret_cast<u32x4 *>(tb + vi * 16 + (vi >> 3) * 16) = q[u];
+                    }
+                    if (blk + 2 < nblk) issue_block(q, blk + 2);               // the registers are free again
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // a wavefront's LDS accesses execute in order
+                    u32x4 r[ST_U];
+#pragma unroll
+                    for (int u = 0; u < ST_U; ++u) r[u] = *reinterpret_cast<const u32x4 *>(mine + u * 16);
+                    uint32_t mask = candidate_mask(r, key_lo_s);
+                    // whole vectors past the end of the wavefront's range are not there
+                    const int64_t left = (wv1 - wv0 - int64_t(blk) * ST_BLKV) - int64_t(lane) * ST_U;
+                    if (left < ST_U) mask &= left <= 0 ? 0u : (1u << (static_cast<int>(left) * VEC)) - 1u;
+                    const uint32_t cnt = __builtin_popcount(mask);
+                    const uint32_t incl = wave_inclusive_scan(cnt);
+                    const uint32_t total = uint32_t(__builtin_amdgcn_readlane(int(incl), WAVE - 1));
+                    if (n_w + total > uint32_t(ST_SEGCAP)) {
+                        full = true;
+                        return;
+                    }
+                    uint32_t slot = n_w + incl - cnt;
+                    const uint32_t pos0 = static_cast<uint32_t>(blk) * (ST_BLKV * VEC) + lane * ST_EPL;
+                    while (mask) {
+                        const int b = __builtin_ctz(mask);
+                        mask &= mask - 1;
+                        const uint32_t raw = *reinterpret_cast<const uint16_t *>(mine + 2 * b);
+                        seg[slot++] = (raw << 16) | (pos0 + b);
+                    }
+                    n_w += total;
+                };
+                for (int blk = 0; blk < nblk && !full; blk += 2) {
+                    process(qa, blk);
+                    if (blk + 1 < nblk && !full) process(qb, blk + 1);
+                }
+                if (lane == 0) {
+                    wcount[wave] = n_w;
+                    if (full) overflow = 1u;
+                }
+                __syncthreads();
+                STAMP(3);
+                if (overflow == 0) {
+                    // Exact counts from the staged words, per wavefront (whist[wave]: one counter per key of the
+                    // range, the last one for the keys above it); four words per lane and read, the segment's
+                    // capacity is a multiple of four.
+                    const uint32_t key_end = key_lo + nf;
+                    uint32_t *wh = whist[wave];
+                    if (lane <= static_cast<int>(nf)) wh[lane] = 0;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    uint32_t above = 0;
+                    for (uint32_t q0 = 0; q0 < n_w; q0 += 4 * WAVE) {
+                        const uint32_t q = q0 + lane * 4;
+                        if (q < n_w) {
+                            const u32x4 w4 = *reinterpret_cast<const u32x4 *>(seg + q);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const uint32_t key = (w4[j] >> 16) & MASK;
+                                const bool there = q + j < n_w;
+                                above += (there && key >= key_end) ? 1u : 0u;
+                                const uint32_t rel = key - key_lo;
+                                if (there && rel < nf) atomicAdd(&wh[rel], 1u);
+                            }
+                        }
+                    }
+                    above = wave_sum(above);
+                    if (lane == 0) atomicAdd(&wh[nf], above);
+                    __syncthreads();
+                    if (tid <= static_cast<int>(nf)) {        // the workgroup's row of the table: the wavefronts' counts added up
+                        uint32_t sum = 0;
+#pragma unroll
+                        for (int w2 = 0; w2 < NW; ++w2) sum += whist[w2][tid];
+                        lh[tid] = sum;
+                    }
+                    if (last_chunk) {                          // the tensor's ragged end belongs to the chunk, but to no wavefront's range
+                        __syncthreads();
+                        if (tid == 0)
+                            for (int64_t i = nvf * VEC; i < numel; ++i) {
+                                const uint32_t key = x[i] & MASK;
+                                if (key >= key_end) lh[nf] += 1u;
+                                else if (key - key_lo < nf) lh[key - key_lo] += 1u;
+                            }
+                    }
+                    use_staged = true;
+                    counted = true;
+                }
+            }
+        }
+        if (!counted) {
             // Few keys fall into the range, so unlike the digit histograms this pass branches: a
             // wavefront with no such key among its lanes skips the LDS atomic altogether (an LDS
             // atomic costs its issue cycles whatever the number of active lanes).
@@ -865,9 +1064,9 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         __syncthreads();
         if (!wait_ready()) return SEL_NEVER_READY;      // (already seen, unless the range was predicted)
         if (tid <= static_cast<int>(nf)) dev_store(&table[tid * G + blockIdx.x], lh[tid]);
-        STAMP();
+        STAMP(4);
         if (!grid_barrier(st, xbar, ++barriers, spin_limit, &bcast[3])) return SEL_GAVE_UP;
-        STAMP();
+        STAMP(5);
 
         // Per row of the table (a key of the range; the last row = the keys above the range): the total
         // over all chunks and the part in the chunks before this one, one wavefront per row.
@@ -925,13 +1124,14 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
         if (!predicted) return SEL_GAVE_UP;     // cannot happen with exact digits; the serial path would still answer
         predicted = false;                       // the sample misled: once more with the exact histogram
         missed = true;
+        use_staged = false;
         __syncthreads();                         // everybody has read the verdict before it is written again
     }
     t = bcast[0];
     m = bcast[1];
     if (blockIdx.x == 0 && tid == 0) dev_store(&st->path, missed ? 2u : predicted ? 1u : 0u);
     uint32_t run_gt = offs[0], run_eq = offs[1];   // #{key > t}, #{key == t} before this chunk
-    STAMP();
+    STAMP(6);
 
     // ---- ordered compaction -------------------------------------------------------
     // The kept elements of a tile occupy consecutive output slots; they are gathered in
@@ -989,103 +1189,160 @@ __device__ inline SelOutcome select_fused_body(const RAW *__restrict__ x, int64_
             }
         // the next tile's scan starts with a barrier, which also protects the staging buffers
     };
-    __syncthreads();                       // histogram storage becomes staging storage
-    // The chunk is compacted in super-tiles of FUSED_RES x 1024 vectors that sit in the parking
-    // area: the first one is the parked head itself, the following ones are fetched (coalesced,
-    // one super-tile ahead, through registers) into the same area.  Inside a super-tile each thread
-    // takes `rows` CONSECUTIVE vectors (the other phases take every 1024th), so flat-index order is
-    // thread order and one block scan serves the whole super-tile: two barriers + a gather + a
-    // write-out per 49152 elements.  Bit (i * VEC + e) of the masks stands for element e of the
-    // thread's i-th vector.  A super-tile that keeps more than the staging buffers hold (only when
-    // most of the tensor is kept) falls back to one scan per 1024-vector row.
-    constexpr int64_t SUPER = int64_t(FUSED_RES) * SEL_THREADS;
-    auto fetch = [&](u32x4 (&pre)[FUSED_RES], int64_t sb) {       // vectors [sb, sb + SUPER) n [.., v1), clamped loads
+    bool compacted = false;
+    if constexpr (!F32) {
+        if (use_staged) {
+            // ---- compaction from the staged candidates: x is not read again ----
+            const uint32_t n_w = wcount[wave];
+            // #{key > t}, #{key == t} in the wavefronts' ranges, from their histograms: lane l adds up wavefront l's
+            const uint32_t trel = t - key_lo;
+            uint32_t g = 0, e = 0;
+            if (lane < NW) {
+                g = whist[lane][nf];
+                for (uint32_t r = trel + 1; r < nf; ++r) g += whist[lane][r];
+                e = whist[lane][trel];
+            }
+            const uint32_t gi = wave_inclusive_scan(g), ei = wave_inclusive_scan(e);
+            uint32_t my_gt = run_gt + uint32_t(__builtin_amdgcn_readlane(int(gi - g), wave));
+            uint32_t my_eq = run_eq + uint32_t(__builtin_amdgcn_readlane(int(ei - e), wave));
+            run_gt += uint32_t(__builtin_amdgcn_readlane(int(gi), NW - 1));
+            run_eq += uint32_t(__builtin_amdgcn_readlane(int(ei), NW - 1));
+            const uint32_t flat0 = static_cast<uint32_t>(wv0 * VEC);
+            for (uint32_t q0 = 0; q0 < n_w; q0 += 4 * WAVE) {
+                const uint32_t q = q0 + lane * 4;
+                u32x4 w4 = {0u, 0u, 0u, 0u};
+                if (q < n_w) w4 = *reinterpret_cast<const u32x4 *>(seg + q);
+                uint32_t gtm = 0, eqm = 0;                 // bit j: word j of this lane has key > t / key == t
 #pragma unroll
-        for (int i = 0; i < FUSED_RES; ++i)
-            pre[i] = (sb < v1) ? xv[min(sb + int64_t(i) * SEL_THREADS + tid, v1 - 1)] : u32x4{0, 0, 0, 0};
-    };
-    u32x4 pre[FUSED_RES];
-    for (int64_t sb = v0; sb < v1; sb += SUPER) {
-        const int64_t count = min<int64_t>(v1 - sb, SUPER);          // vectors of this super-tile, all in `res`
-        const int rows = static_cast<int>((count + SEL_THREADS - 1) / SEL_THREADS);
-        const bool more = sb + SUPER < v1;
-        if (more) fetch(pre, sb + SUPER);
-        const int64_t mine0 = int64_t(tid) * rows;                    // first vector of this thread
-        unsigned long long gtm = 0, eqm = 0;
-#pragma nounroll
-        for (int i = 0; i < rows; ++i) {
-            if (mine0 + i < count) {
-                uint32_t g = 0, q = 0;
-                for_each_raw(RAW(0), res[mine0 + i], [&](uint32_t raw, int e) {
-                    const uint32_t key = raw & MASK;
-                    g |= (key > t ? 1u : 0u) << e;
-                    q |= (key == t ? 1u : 0u) << e;
-                });
-                gtm |= static_cast<unsigned long long>(g) << (i * VEC);
-                eqm |= static_cast<unsigned long long>(q) << (i * VEC);
-            }
-        }
-        uint32_t ex_gt, ex_eq, tot_gt, tot_eq;
-        block_exclusive_scan2<SEL_THREADS>(__builtin_popcountll(gtm), __builtin_popcountll(eqm), wave_tot2, ex_gt, ex_eq,
-                                           tot_gt, tot_eq);
-        const uint32_t part_first = run_gt + min(run_eq, m);
-        const uint32_t part_kept = (run_gt + tot_gt) + min(run_eq + tot_eq, m) - part_first;
-        // 16-bit elements are staged as ONE word each, value << 16 | position within the super-tile,
-        // so the staging area holds half as many again (a super-tile that keeps a fifth of its
-        // elements still fits) and the scatter issues one LDS store per kept element.
-        constexpr bool PACKED = !F32;
-        static_assert(F32 || SUPER * VEC <= 65536, "a position within a super-tile fits 16 bits");
-        constexpr uint32_t STAGE_CAP = PACKED ? uint32_t(TILE + TILE / 2) : uint32_t(TILE);
-        if (part_kept <= STAGE_CAP) {                                  // uniform over the workgroup
-            uint32_t my_gt = run_gt + ex_gt, my_eq = run_eq + ex_eq;
-            const RAW *res_raw = reinterpret_cast<const RAW *>(res);
-            uint32_t *stage_pk = smem;
-            unsigned long long todo = gtm | eqm;
-            while (todo) {
-                const int b = __builtin_ctzll(todo);
-                todo &= todo - 1;
-                const bool gt = (gtm >> b) & 1ull;
-                if (gt || my_eq < m) {
-                    const uint32_t slot = my_gt + min(my_eq, m) - part_first;
-                    const uint32_t off = static_cast<uint32_t>(mine0) * VEC + b;
-                    if constexpr (PACKED) {
-                        stage_pk[slot] = (static_cast<uint32_t>(res_raw[off]) << 16) | off;
-                    } else {
-                        stage_val[slot] = res_raw[off];
-                        stage_idx[slot] = static_cast<int32_t>(sb * VEC + off);
-                    }
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = (w4[j] >> 16) & MASK;
+                    const bool there = q + j < n_w;
+                    gtm |= (there && key > t) ? (1u << j) : 0u;
+                    eqm |= (there && key == t) ? (1u << j) : 0u;
                 }
-                my_gt += gt ? 1u : 0u;
-                my_eq += gt ? 0u : 1u;
-            }
-            run_gt += tot_gt;
-            run_eq += tot_eq;
-            __syncthreads();
-            for (uint32_t q = tid; q < part_kept; q += SEL_THREADS)
-                if (part_first + q < k) {          // always true for consistent counts
-                    if constexpr (PACKED) {
-                        const uint32_t w = stage_pk[q];
-                        vals[part_first + q] = static_cast<RAW>(w >> 16);
-                        idx[part_first + q] = static_cast<int32_t>(sb * VEC + (w & 0xFFFFu));
-                    } else {
-                        vals[part_first + q] = stage_val[q];
-                        idx[part_first + q] = stage_idx[q];
-                    }
-                }
-        } else {
-            for (int i = 0; i < rows; ++i) {       // row by row; a row's scan starts with a barrier, which frees the staging buffers
-                const int64_t v = sb + int64_t(i) * SEL_THREADS + tid;
-                emit_tile(res[i * SEL_THREADS + tid], v, v < v1);
-            }
-        }
-        if (more) {
-            __syncthreads();                       // everybody is done with this super-tile's vectors and staging
+                const uint32_t both = __builtin_popcount(gtm) | (__builtin_popcount(eqm) << 16);
+                const uint32_t incl = wave_inclusive_scan(both);
+                const uint32_t tot = uint32_t(__builtin_amdgcn_readlane(int(incl), WAVE - 1));
+                uint32_t gb = my_gt + ((incl - both) & 0xFFFFu), eb = my_eq + ((incl - both) >> 16);
 #pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool gt = (gtm >> j) & 1u, eq = (eqm >> j) & 1u;
+                    if (gt || (eq && eb < m)) keep(gb + min(eb, m), w4[j] >> 16, int64_t(flat0) + (w4[j] & 0xFFFFu));
+                    gb += gt ? 1u : 0u;
+                    eb += eq ? 1u : 0u;
+                }
+                my_gt += tot & 0xFFFFu;
+                my_eq += tot >> 16;
+            }
+            if (tid == 0) __hip_atomic_fetch_add(&st->staged, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            compacted = true;
+        }
+    }
+    if (!compacted) {
+        __syncthreads();                       // histogram storage becomes staging storage
+        // The chunk is compacted in super-tiles of FUSED_RES x 1024 vectors that sit in the parking
+        // area: the first one is the parked head itself, the following ones are fetched (coalesced,
+        // one super-tile ahead, through registers) into the same area.  Inside a super-tile each thread
+        // takes `rows` CONSECUTIVE vectors (the other phases take every 1024th), so flat-index order is
+        // thread order and one block scan serves the whole super-tile: two barriers + a gather + a
+        // write-out per 49152 elements.  Bit (i * VEC + e) of the masks stands for element e of the
+        // thread's i-th vector.  A super-tile that keeps more than the staging buffers hold (only when
+        // most of the tensor is kept) falls back to one scan per 1024-vector row.
+        constexpr int64_t SUPER = int64_t(FUSED_RES) * SEL_THREADS;
+        auto fetch = [&](u32x4 (&pre)[FUSED_RES], int64_t sb) {       // vectors [sb, sb + SUPER) n [.., v1), clamped loads
+    #pragma unroll
+            for (int i = 0; i < FUSED_RES; ++i)
+                pre[i] = (sb < v1) ? xv[min(sb + int64_t(i) * SEL_THREADS + tid, v1 - 1)] : u32x4{0, 0, 0, 0};
+        };
+        u32x4 pre[FUSED_RES];
+        if (nres == 0 && v0 < v1) {            // nothing was parked (the staged form was abandoned): fetch the first super-tile now
+            fetch(pre, v0);
+    #pragma unroll
             for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = pre[i];
             __syncthreads();
         }
+        for (int64_t sb = v0; sb < v1; sb += SUPER) {
+            const int64_t count = min<int64_t>(v1 - sb, SUPER);          // vectors of this super-tile, all in `res`
+            const int rows = static_cast<int>((count + SEL_THREADS - 1) / SEL_THREADS);
+            const bool more = sb + SUPER < v1;
+            if (more) fetch(pre, sb + SUPER);
+            const int64_t mine0 = int64_t(tid) * rows;                    // first vector of this thread
+            unsigned long long gtm = 0, eqm = 0;
+    #pragma nounroll
+            for (int i = 0; i < rows; ++i) {
+                if (mine0 + i < count) {
+                    uint32_t g = 0, q = 0;
+                    for_each_raw(RAW(0), res[mine0 + i], [&](uint32_t raw, int e) {
+                        const uint32_t key = raw & MASK;
+                        g |= (key > t ? 1u : 0u) << e;
+                        q |= (key == t ? 1u : 0u) << e;
+                    });
+                    gtm |= static_cast<unsigned long long>(g) << (i * VEC);
+                    eqm |= static_cast<unsigned long long>(q) << (i * VEC);
+                }
+            }
+            uint32_t ex_gt, ex_eq, tot_gt, tot_eq;
+            block_exclusive_scan2<SEL_THREADS>(__builtin_popcountll(gtm), __builtin_popcountll(eqm), wave_tot2, ex_gt, ex_eq,
+                                               tot_gt, tot_eq);
+            const uint32_t part_first = run_gt + min(run_eq, m);
+            const uint32_t part_kept = (run_gt + tot_gt) + min(run_eq + tot_eq, m) - part_first;
+            // 16-bit elements are staged as ONE word each, value << 16 | position within the super-tile,
+            // so the staging area holds half as many again (a super-tile that keeps a fifth of its
+            // elements still fits) and the scatter issues one LDS store per kept element.
+            constexpr bool PACKED = !F32;
+            static_assert(F32 || SUPER * VEC <= 65536, "a position within a super-tile fits 16 bits");
+            constexpr uint32_t STAGE_CAP = PACKED ? uint32_t(TILE + TILE / 2) : uint32_t(TILE);
+            if (part_kept <= STAGE_CAP) {                                  // uniform over the workgroup
+                uint32_t my_gt = run_gt + ex_gt, my_eq = run_eq + ex_eq;
+                const RAW *res_raw = reinterpret_cast<const RAW *>(res);
+                uint32_t *stage_pk = smem;
+                unsigned long long todo = gtm | eqm;
+                while (todo) {
+                    const int b = __builtin_ctzll(todo);
+                    todo &= todo - 1;
+                    const bool gt = (gtm >> b) & 1ull;
+                    if (gt || my_eq < m) {
+                        const uint32_t slot = my_gt + min(my_eq, m) - part_first;
+                        const uint32_t off = static_cast<uint32_t>(mine0) * VEC + b;
+                        if constexpr (PACKED) {
+                            stage_pk[slot] = (static_cast<uint32_t>(res_raw[off]) << 16) | off;
+                        } else {
+                            stage_val[slot] = res_raw[off];
+                            stage_idx[slot] = static_cast<int32_t>(sb * VEC + off);
+                        }
+                    }
+                    my_gt += gt ? 1u : 0u;
+                    my_eq += gt ? 0u : 1u;
+                }
+                run_gt += tot_gt;
+                run_eq += tot_eq;
+                __syncthreads();
+                for (uint32_t q = tid; q < part_kept; q += SEL_THREADS)
+                    if (part_first + q < k) {          // always true for consistent counts
+                        if constexpr (PACKED) {
+                            const uint32_t w = stage_pk[q];
+                            vals[part_first + q] = static_cast<RAW>(w >> 16);
+                            idx[part_first + q] = static_cast<int32_t>(sb * VEC + (w & 0xFFFFu));
+                        } else {
+                            vals[part_first + q] = stage_val[q];
+                            idx[part_first + q] = stage_idx[q];
+                        }
+                    }
+            } else {
+                for (int i = 0; i < rows; ++i) {       // row by row; a row's scan starts with a barrier, which frees the staging buffers
+                    const int64_t v = sb + int64_t(i) * SEL_THREADS + tid;
+                    emit_tile(res[i * SEL_THREADS + tid], v, v < v1);
+                }
+            }
+            if (more) {
+                __syncthreads();                       // everybody is done with this super-tile's vectors and staging
+    #pragma unroll
+                for (int i = 0; i < FUSED_RES; ++i) res[i * SEL_THREADS + tid] = pre[i];
+                __syncthreads();
+            }
+        }
     }
-    STAMP();
+    STAMP(7);
     if (last_chunk && tid == 0) {
         for (int64_t i = nvf * VEC; i < numel; ++i) {
             const RAW raw = x[i];
@@ -1360,8 +1617,11 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
         constexpr int VEC = KeyTraits<RAW>::VEC;
         constexpr int TILE_WORDS = SEL_THREADS * VEC + SEL_THREADS * VEC * int(sizeof(RAW)) / 4;
         constexpr int HIST_WORDS = (sizeof(RAW) == 4 ? (1 << 13) : (1 << 11)) + 2 * WAVE;
-        constexpr size_t smem_bytes = size_t(FUSED_RES) * SEL_THREADS * 16 +
-                                      4 * size_t(TILE_WORDS > HIST_WORDS ? TILE_WORDS : HIST_WORDS);
+        constexpr size_t parked_bytes = size_t(FUSED_RES) * SEL_THREADS * 16 +
+                                        4 * size_t(TILE_WORDS > HIST_WORDS ? TILE_WORDS : HIST_WORDS);
+        static_assert(parked_bytes <= FUSED_SMEM_BYTES, "both LDS layouts fit");
+        // 16-bit types: everything the compute unit has, the staged form's segments take what the layouts leave
+        constexpr size_t smem_bytes = sizeof(RAW) == 2 ? FUSED_SMEM_BYTES : parked_bytes;
         static_assert(size_t(FUSED_RES) * SEL_THREADS * 16 >= 4 * ((size_t(1) << 13) + 2 * WAVE),
                       "the serial fallback keeps its histogram where the chunk head was parked");
         // how many workgroups of this kernel each device holds at once (asked once per element type and device)

@@ -398,3 +398,61 @@ def test_forced_redo_is_reported():
             dropit.set_select_mode(0)
         assert np.array_equal(to_host(idx), want_i) and to_host(vals).tobytes() == want_v.tobytes()
         assert int(ws[:64].cpu().numpy().view(np.uint32)[14]) == expect, mode
+
+
+def _state_words(ws: torch.Tensor) -> np.ndarray:
+    return ws[:64].cpu().numpy().view(np.uint32)
+
+
+def _run_with_state(x, gamma):
+    xd = to_device(x)
+    ws = torch.zeros(dropit.compress_workspace_bytes(x.size, xd.dtype), dtype=torch.uint8, device="cuda:0")
+    k = oracle.keep_count(x.size, gamma)
+    want_v, want_i = oracle.compress(x, k)
+    vals, idx = dropit.compress(xd, gamma, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(idx), want_i) and to_host(vals).tobytes() == want_v.tobytes()
+    st = _state_words(ws)
+    return dict(path=int(st[11]), groups=int(st[10] & 0xFFFF), redo=int(st[14]), staged=int(st[15]))
+
+
+@pytest.mark.parametrize("name", ["vitb_fc1", "vitb_fc2", "vitdet_fc2", "resnet_conv3x3"])
+def test_benchmark_tensors_are_read_once(name):
+    """White box: on the benchmark tensors the sampled bracket is confirmed and EVERY workgroup compacts from the
+    candidates it staged in LDS during its one pass over x (word 15 of the state block counts them, the low half
+    of word 10 the workgroups)."""
+    w = WORKLOADS[name]
+    s = _run_with_state(activation(w.x_shape, w.x_dist, w.x_seed, w.dtype), w.gamma)
+    print("staged", name, s, flush=True)
+    assert s["path"] == 1 and s["redo"] == 0
+    assert s["groups"] > 1 and s["staged"] == s["groups"]
+
+
+@pytest.mark.parametrize("numel,gamma", [((9 << 20) + 1234, 0.9), (3 * (1 << 22) + 8 * 77, 0.8), (20000011, 0.95)])
+def test_staging_overflow_falls_back_per_workgroup(numel, gamma):
+    """Values that bunch up along the tensor: the largest eighth of a normal sample sits (shuffled) in the first
+    eighth of the tensor, so the value histogram is the ordinary one (the sampled bracket is usable) but the
+    workgroups that own that stretch find most of their elements candidates, more than their LDS segments hold, and
+    take the two-read form, while the others stage theirs.  Same bytes either way."""
+    rng = np.random.default_rng(numel % 1000)
+    base = rng.standard_normal(numel, dtype=np.float32)
+    order = np.argsort(-np.abs(base), kind="stable")
+    head = numel // 8
+    out = np.empty_like(base)
+    out[:head] = base[rng.permutation(order[:head])]
+    out[head:] = base[rng.permutation(order[head:])]
+    s = _run_with_state(f32_to_bf16_bits(out), gamma)
+    print("overflow", numel, gamma, s, flush=True)
+    assert s["path"] == 1 and s["redo"] == 0
+    assert 0 < s["staged"] < s["groups"]
+
+
+@pytest.mark.parametrize("numel", [(1 << 21), (1 << 21) + 8 * 1000 + 3, 2500000, 7 * (1 << 20) + 5])
+@pytest.mark.parametrize("dist", ["normal", "relu", "gelu"])
+def test_staged_form_sizes_and_ragged_ends(numel, dist):
+    """Chunk and wavefront ranges that end inside a block, inside a lane's pair of vectors, and with a ragged
+    (numel % 8) tail, for the three activation shapes and three gammas."""
+    x = activation((numel,), dist, 40 + numel % 97, "bf16")
+    for gamma in (0.9, 0.8, 0.6):
+        s = _run_with_state(x, gamma)
+        print("staged sizes", numel, dist, gamma, s, flush=True)
