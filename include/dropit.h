@@ -90,6 +90,24 @@ dropit_status dropit_compress(const void *x, const int64_t *shape, int ndim, dro
                               double gamma, void *vals, int32_t *idx,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * dropit_compress without a workspace argument, for callers that cannot allocate device memory
+ * and have none to spare: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The select's exchange area (about 170 KB, independent of the tensor size)
+ * is a static device array inside the library, one copy per GPU, held until the process ends.
+ * The call itself allocates and frees nothing, on the device or through any library.
+ *
+ * Arguments, outputs, alignment and error behaviour as for dropit_compress; tensors of up to
+ * DROPIT_STATIC_MAX_NUMEL elements (the limit of the int32 index; larger shapes give
+ * DROPIT_EINVAL), DROPIT_EHIP if the runtime cannot give the array's device address.
+ * All calls on one GPU share the one array (it keeps the last call's contents; the kernels clear
+ * what they need): calls that overlap in time on the same GPU, from any stream or thread, race
+ * with each other -- order them, or give the others a workspace through dropit_compress.
+ */
+#define DROPIT_STATIC_MAX_NUMEL 2147483647
+dropit_status dropit_compress_static(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                                     double gamma, void *vals, int32_t *idx, void *hip_stream);
+
 /* Bytes of device workspace dropit_compress_random needs (0 on invalid arguments). */
 size_t dropit_compress_random_workspace_bytes(int64_t numel, dropit_dtype dt);
 

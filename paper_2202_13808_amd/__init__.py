@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     compress_random_workspace_bytes,
     compress_mask,
     compress_rows,
+    compress_static,
     compress_workspace_bytes,
     keep_count,
     lib,

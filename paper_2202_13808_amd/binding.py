@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.dropit_compress_workspace_bytes.argtypes = [i64, i32]
         L.dropit_compress.restype = i32
         L.dropit_compress.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp, sz, vp]
+        L.dropit_compress_static.restype = i32
+        L.dropit_compress_static.argtypes = [vp, p64, i32, i32, dbl, vp, vp, vp]
         L.dropit_compress_random_workspace_bytes.restype = sz
         L.dropit_compress_random_workspace_bytes.argtypes = [i64, i32]
         L.dropit_compress_random.restype = i32
@@ -168,6 +170,25 @@ def compress(x: torch.Tensor, gamma: float, vals: Optional[torch.Tensor] = None,
         _check(lib().dropit_compress(x.data_ptr(), shape, x.dim(), code, float(gamma),
                                      vals.data_ptr() if k else None, idx.data_ptr() if k else None,
                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return vals[:k], idx[:k]
+
+
+def compress_static(x: torch.Tensor, gamma: float, vals: torch.Tensor, idx: torch.Tensor, stream=None
+                    ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """dropit_compress_static: dropit_compress on the library's own static exchange area.  Nothing is
+    allocated, here or in the library: the caller passes the outputs (at least k elements each)."""
+    _require_device(x, vals, idx)
+    code = _dtype_code(x.dtype)
+    k = keep_count(x.numel(), gamma)
+    if k < 0:
+        _check(EINVAL)
+    if vals.numel() < k or idx.numel() < k or vals.dtype != x.dtype or idx.dtype != torch.int32:
+        raise ValueError("vals/idx must hold k=%d elements of %s / int32" % (k, x.dtype))
+    shape = _shape_array(x.shape)
+    with torch.cuda.device(x.device):
+        _check(lib().dropit_compress_static(x.data_ptr(), shape, x.dim(), code, float(gamma),
+                                            vals.data_ptr() if k else None, idx.data_ptr() if k else None,
+                                            _stream_ptr(stream)))
     return vals[:k], idx[:k]
 
 

@@ -1779,6 +1779,54 @@ extern "C" dropit_status dropit_compress(const void *x, const int64_t *shape, in
     return run_compress<uint32_t>(x, numel, k, vals, idx, ws, stream);
 }
 
+// ---- dropit_compress for callers that cannot allocate ----------------------------------------------
+// The select's exchange area (state, histograms, per-chunk table: SelWorkspace::bytes, about 170 KB, the
+// same for every tensor size) as a device array of this library instead of a caller's workspace.  In
+// host code `scratch` is only a handle for the runtime: the array's device address is asked for once
+// per device (each device holds its own copy) and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[SelWorkspace::bytes];
+
+namespace {
+// Device address of `scratch` on the current device, nullptr if the runtime will not tell.
+char *static_scratch()
+{
+    static std::atomic<uint64_t> known{0};
+    static void *address_on[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    void *fresh = nullptr;
+    const bool ok = once_per_device(known, [&] {
+        if (hipGetSymbolAddress(&fresh, HIP_SYMBOL(scratch)) != hipSuccess || fresh == nullptr) {
+            (void)hipGetLastError();
+            return false;
+        }
+        if (dev >= 0 && dev < 64) address_on[dev] = fresh;
+        return true;
+    });
+    if (!ok) return nullptr;
+    return static_cast<char *>((dev >= 0 && dev < 64) ? address_on[dev] : fresh);
+}
+}  // namespace
+
+extern "C" dropit_status dropit_compress_static(const void *x, const int64_t *shape, int ndim, dropit_dtype dt,
+                                                double gamma, void *vals, int32_t *idx, void *hip_stream)
+{
+    if (dt != DROPIT_F32 && dt != DROPIT_BF16) return DROPIT_EINVAL;
+    const int64_t numel = checked_numel(shape, ndim);       // -1 beyond DROPIT_STATIC_MAX_NUMEL
+    if (numel < 1) return DROPIT_EINVAL;
+    const int64_t k = dropit_keep_count(numel, gamma);
+    if (k < 0) return DROPIT_EINVAL;
+    if (x == nullptr || !aligned(x, 16)) return DROPIT_EINVAL;
+    if (k == 0) return DROPIT_OK;
+    if (vals == nullptr || idx == nullptr) return DROPIT_EINVAL;
+    if (!aligned(vals, dt == DROPIT_F32 ? 4 : 2) || !aligned(idx, 4)) return DROPIT_EINVAL;
+    char *ws = static_scratch();
+    if (ws == nullptr) return DROPIT_EHIP;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (dt == DROPIT_BF16) return run_compress<uint16_t>(x, numel, k, vals, idx, ws, stream);
+    return run_compress<uint32_t>(x, numel, k, vals, idx, ws, stream);
+}
+
 extern "C" size_t dropit_compress_random_workspace_bytes(int64_t numel, dropit_dtype dt)
 {
     if (numel < 1 || numel > INT32_MAX) return 0;

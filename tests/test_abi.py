@@ -29,7 +29,8 @@ def test_header_declares_the_expected_entry_points():
         "dropit_compress_rows_workspace_bytes", "dropit_compress_rows",
         "dropit_weight_grad_rows_workspace_bytes", "dropit_weight_grad_rows",
         "dropit_compress_mask_workspace_bytes", "dropit_compress_mask",
-        "dropit_weight_grad_mask_workspace_bytes", "dropit_weight_grad_mask"])
+        "dropit_weight_grad_mask_workspace_bytes", "dropit_weight_grad_mask",
+        "dropit_compress_static"])
 
 
 def test_library_exports_every_declared_symbol():
