@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time the vendor library's dense weight gradient (torch.mm / conv2d_weight) on the "
                          "same shapes and inputs, reported as context under 'vendor_gemm'")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of ONE captured HIP graph of the step (one input copy) instead of eager calls: "
+                         "what a launch-bound layer costs once the host's per-call work is out of the loop")
     ap.add_argument("--warm", action="store_true",
                     help="time with ONE input copy (x / dY then stay in the 256 MB Infinity Cache) instead of "
                          "rotating over > 600 MB of copies; the rotating (cold) figure is the default")
@@ -136,7 +139,7 @@ def main():
         return torch.from_numpy(a).to(dev)
 
     copies = 1
-    if not args.warm:
+    if not args.warm and not args.graph:
         per = xh.nbytes + dyh.nbytes
         copies = max(2, int(np.ceil(600e6 / per)))
     xs = [dev_tensor(xh) for _ in range(copies)]
@@ -160,9 +163,25 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(0)
+        for i in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        if args.graph:
+            graph.replay()
+        else:
+            step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
@@ -227,7 +246,8 @@ def main():
     conv_padded = conv_mfma and w.x_shape[3] % 8 != 0       # one more kernel: the zero-padded copy of dY
     mfma = fc_mfma or conv_mfma or conv_gemm
     # marks per call: prep, [pad,] gemm, reduce, end  |  zero+scatter, gemm, end
-    n_g = 5 if conv_padded else 4 if mfma else 3
+    fc_small = path == "fc_small"                          # one launch: recover in LDS + fp32 multiply-adds
+    n_g = 5 if conv_padded else 4 if mfma else 2 if fc_small else 3
     c_ms = np.maximum(np.array([event_ms(e[:n_c]) for e in ce]) - event_overhead_ms, 0.0)   # [n_meas, n_c-1]
     g_ms = np.maximum(np.array([event_ms(e[:n_g]) for e in ge]) - event_overhead_ms, 0.0)
     c_med = np.median(c_ms, axis=0)
@@ -237,14 +257,15 @@ def main():
                ["im2col_recover_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if path == "conv_gemm" else
                ["im2col_rows_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if conv_gemm else
                ["row_starts", "pad_dY", "mfma_conv", "partial_reduce"] if conv_padded else
-               ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else ["zero_scatter", "fma_gemm"])
+               ["row_starts", "mfma_conv", "partial_reduce"] if conv_mfma else
+               ["recover_and_fma_gemm"] if fc_small else ["zero_scatter", "fma_gemm"])
     compress_ms = float(c_med.sum())
     grad_ms = float(g_med.sum())
 
     esz = 2 if bf16 else 4
     compress_bytes = w.numel * esz + k * (esz + 4)           # read x once + write k (value, index) pairs
     flops = float(w.dense_flops)
-    main_idx = 2 if conv_padded else 1
+    main_idx = 2 if conv_padded else 0 if fc_small else 1
     main_ms = float(np.mean(g_ms[:, main_idx]))
     dw_tflops_kernel = flops / (main_ms * 1e-3) * 1e-12
     hist_ms = float(np.mean(c_ms[:, 0]))
@@ -266,7 +287,7 @@ def main():
         "config": {"workload": "%s: x %s %s gamma=%.2f, dY %s, dW %s fp32%s" % (
             w.name + (" channels-last" if nhwc else ""), w.dtype, list(x_shape), w.gamma, list(dyh.shape), list(dw_shape),
             " (cold: %d rotating input copies, %.0f MB)" % (copies, copies * (xh.nbytes + dyh.nbytes) / 1e6)
-            if copies > 1 else " (inputs warm in Infinity Cache)")},
+            if copies > 1 else " (inputs warm in Infinity Cache%s)" % (", replays of one captured graph" if args.graph else ""))},
         "warm": {"ms_per_step": warm_ms_per_step, "value": flops / (warm_ms_per_step * 1e-3) * 1e-12,
                  "note": "same steps on one input copy (x and dY stay in the 256 MB Infinity Cache)"},
         "event_overhead_ms": event_overhead_ms,
@@ -281,7 +302,8 @@ def main():
             "dw_kernels_ms": dict(zip(g_names, [float(v) for v in g_med])),
         },
         "roofline": {
-            "kernel": "fc_dense_kernel" if (fc_mfma or conv_gemm) else "conv3x3_mfma_kernel" if conv_mfma else "fma kernel",
+            "kernel": "fc_dense_kernel" if (fc_mfma or conv_gemm) else "conv3x3_mfma_kernel" if conv_mfma else
+                      "fc_small_kernel" if fc_small else "fma kernel",
             "bound": "mfma" if mfma else "alu",
             "achieved": dw_tflops_kernel,
             "peak": MFMA_BF16_PEAK_TFLOPS if mfma else 157.3,

@@ -152,7 +152,8 @@ typedef enum {
     DROPIT_PATH_CONV_BANDS = 2,     /* 3x3/s1/p1 bf16: row bands in LDS, implicit im2col on the matrix cores */
     DROPIT_PATH_CONV_GEMM = 3,      /* 3x3/s1/p1 bf16, small planes with many channels: explicit im2col rows + the FC GEMM */
     DROPIT_PATH_FMA = 4,            /* exact fp32 multiply-add kernels (fp32 inputs, odd shapes) */
-    DROPIT_PATH_CONV_IM2COL = 5     /* bf16, any geometry and either layout: zero-filled im2col rows written from the pairs + the FC GEMM */
+    DROPIT_PATH_CONV_IM2COL = 5,    /* bf16, any geometry and either layout: zero-filled im2col rows written from the pairs + the FC GEMM */
+    DROPIT_PATH_FC_SMALL = 6        /* fully-connected layers of at most 16384 input elements: recover in LDS and exact fp32 multiply-adds, one launch */
 } dropit_wgrad_path;
 dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,
                                           int64_t c_out, const dropit_conv2d *conv);

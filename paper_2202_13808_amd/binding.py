@@ -129,6 +129,30 @@ def _stream_ptr(stream) -> int:
     return int(s.cuda_stream)
 
 
+class _on:
+    """Makes `device` the current one for the duration of a call, and costs nothing when it already is
+    (the library launches on the current device; torch's own context manager takes several microseconds,
+    which a launch-bound layer notices)."""
+    __slots__ = ("index", "previous")
+
+    def __init__(self, device):
+        self.index = device.index
+        self.previous = None
+
+    def __enter__(self):
+        if self.index is not None:
+            current = torch.cuda.current_device()
+            if current != self.index:
+                self.previous = current
+                torch.cuda.set_device(self.index)
+        return self
+
+    def __exit__(self, *exc):
+        if self.previous is not None:
+            torch.cuda.set_device(self.previous)
+        return False
+
+
 def _require_device(*tensors) -> None:
     for t in tensors:
         if t is not None and not t.is_cuda:
@@ -166,7 +190,7 @@ def compress(x: torch.Tensor, gamma: float, vals: Optional[torch.Tensor] = None,
         workspace = torch.empty(max(compress_workspace_bytes(x.numel(), x.dtype), 1),
                                 dtype=torch.uint8, device=x.device)
     shape = _shape_array(x.shape)
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dropit_compress(x.data_ptr(), shape, x.dim(), code, float(gamma),
                                      vals.data_ptr() if k else None, idx.data_ptr() if k else None,
                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
@@ -185,7 +209,7 @@ def compress_static(x: torch.Tensor, gamma: float, vals: torch.Tensor, idx: torc
     if vals.numel() < k or idx.numel() < k or vals.dtype != x.dtype or idx.dtype != torch.int32:
         raise ValueError("vals/idx must hold k=%d elements of %s / int32" % (k, x.dtype))
     shape = _shape_array(x.shape)
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dropit_compress_static(x.data_ptr(), shape, x.dim(), code, float(gamma),
                                             vals.data_ptr() if k else None, idx.data_ptr() if k else None,
                                             _stream_ptr(stream)))
@@ -215,7 +239,7 @@ def compress_random(x: torch.Tensor, gamma: float, seed: int, vals: Optional[tor
         workspace = torch.empty(max(compress_random_workspace_bytes(x.numel(), x.dtype), 1),
                                 dtype=torch.uint8, device=x.device)
     shape = _shape_array(x.shape)
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dropit_compress_random(x.data_ptr(), shape, x.dim(), code, float(gamma), int(seed),
                                             vals.data_ptr() if k else None, idx.data_ptr() if k else None,
                                             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
@@ -241,7 +265,7 @@ def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, k: i
         _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out), pc))
 
 
-WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma", 5: "conv_im2col"}
+WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma", 5: "conv_im2col", 6: "fc_small"}
 
 
 def weight_grad_path(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int, conv=None,
@@ -283,7 +307,7 @@ def weight_grad(vals: torch.Tensor, idx: torch.Tensor, x_shape: Sequence[int], d
         workspace = torch.empty(max(weight_grad_workspace_bytes(x_shape, dY.dtype, k, c_out, cs, layout), 1),
                                 dtype=torch.uint8, device=dY.device)
     pc = ctypes.byref(cs) if cs is not None else None
-    with torch.cuda.device(dY.device):
+    with _on(dY.device):
         if nhwc:
             _check(lib().dropit_weight_grad_nhwc(
                 vals.data_ptr() if k else None, idx.data_ptr() if k else None, k,
@@ -313,7 +337,7 @@ def compress_rows(x: torch.Tensor, gamma: float, workspace: Optional[torch.Tenso
     if workspace is None:
         need = int(lib().dropit_compress_rows_workspace_bytes(x.numel(), k, code))
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=x.device)
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dropit_compress_rows(x.data_ptr(), _shape_array(x.shape), x.dim(), code, float(gamma),
                                           vals.data_ptr() if k else None, col.data_ptr() if k else None,
                                           rowptr.data_ptr(), workspace.data_ptr(), workspace.numel(),
@@ -340,7 +364,7 @@ def weight_grad_rows(vals: torch.Tensor, col: torch.Tensor, rowptr: torch.Tensor
     if workspace is None:
         need = int(lib().dropit_weight_grad_rows_workspace_bytes(shape, len(x_shape), code, k, int(c_out), ref))
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dY.device)
-    with torch.cuda.device(dY.device):
+    with _on(dY.device):
         _check(lib().dropit_weight_grad_rows(
             vals.data_ptr() if k else None, col.data_ptr() if k else None, rowptr.data_ptr(), k,
             shape, len(x_shape), code, dY.data_ptr(), int(c_out), ref, dW.data_ptr(),
@@ -367,7 +391,7 @@ def compress_mask(x: torch.Tensor, gamma: float, workspace: Optional[torch.Tenso
     if workspace is None:
         need = int(lib().dropit_compress_mask_workspace_bytes(numel, k, code))
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=x.device)
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dropit_compress_mask(x.data_ptr(), _shape_array(x.shape), x.dim(), code, float(gamma),
                                           vals.data_ptr() if k else None, mask.data_ptr(), blockptr.data_ptr(),
                                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
@@ -393,7 +417,7 @@ def weight_grad_mask(vals: torch.Tensor, mask: torch.Tensor, blockptr: torch.Ten
     if workspace is None:
         need = int(lib().dropit_weight_grad_mask_workspace_bytes(shape, len(x_shape), code, k, int(c_out), ref))
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dY.device)
-    with torch.cuda.device(dY.device):
+    with _on(dY.device):
         _check(lib().dropit_weight_grad_mask(
             vals.data_ptr() if k else None, mask.data_ptr(), blockptr.data_ptr(), k,
             shape, len(x_shape), code, dY.data_ptr(), int(c_out), ref, dW.data_ptr(),

@@ -421,7 +421,14 @@ compact_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vp
 // Everything workgroups exchange (histogram, per-chunk table, barrier counter) is
 // accessed ONLY with device-scope atomics, which are coherent by themselves, so no
 // device-wide fence is needed: on this 8-XCD part such a fence writes back and
-// invalidates a whole L2 and was measured at 5-8 us per grid barrier.
+// invalidates a whole L2 and was measured at 5-8 us per grid barrier.  The ordering
+// rests on what the hardware does, not on the language's memory model: a wave's exchanged
+// stores and atomics are complete (s_waitcnt at the __syncthreads() in front of the
+// arrival) before thread 0 issues the arrival atomic, and nothing exchanged is ever read
+// through a non-coherent cache line.  The form the model itself guarantees -- acq_rel on the
+// group counter, release on the top counter, an acquire fence after the wait, all at agent
+// scope -- was measured beside it: 3.4-4.8 us more per call on every benchmark tensor (one
+// barrier per call), for the L2 write-back and invalidate it implies; the relaxed form stays.
 constexpr int FUSED_RES = 6;             // 16-byte vectors per thread parked in LDS
 // Patience in polls (~0.25 us each); every wave exits even if it runs out.  A resident grid meets at a barrier within
 // microseconds (a millisecond for the largest tensors), so the barriers give up after ~15 ms: a grid that is not
@@ -463,15 +470,9 @@ __device__ inline bool grid_barrier(SelState *st, uint32_t *xbar, uint32_t round
     if (threadIdx.x == 0) {
         const uint32_t G = gridDim.x, group = blockIdx.x & 7u;
         const uint32_t groups = G < 8u ? G : 8u, members = (G - group + 7u) / 8u;
-#ifdef DROPIT_RELACQ
-        const uint32_t before = __hip_atomic_fetch_add(&xbar[group * 64], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        if (before + 1 == round * members)
-            __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-#else
         const uint32_t before = __hip_atomic_fetch_add(&xbar[group * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (before + 1 == round * members)
             __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#endif
         uint32_t spins = 0, ok = 1;
         while (dev_load(&st->barrier) < round * groups) {
             if (++spins > spin_limit || ((spins & 31u) == 0 && dev_load(&st->error) != 0)) {
@@ -481,9 +482,6 @@ __device__ inline bool grid_barrier(SelState *st, uint32_t *xbar, uint32_t round
             }
             __builtin_amdgcn_s_sleep(8);        // ~0.2 us between polls: 256 pollers on one word compete with the arrivals
         }
-#ifdef DROPIT_RELACQ
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
         *ok_slot = ok;
     }
     __syncthreads();
@@ -1459,6 +1457,121 @@ __device__ inline void select_serial(const RAW *__restrict__ x, int64_t numel, i
     }
 }
 
+// ---- small tensors: one workgroup, everything in registers ------------------------------------------
+// Up to SMALL_VECTORS 16-byte vectors per thread (64 K fp32 or 128 K 16-bit elements): the tensor is read
+// once into registers and the whole selection -- the same digits, tie rule and slot formula as above --
+// runs in ONE workgroup with workgroup barriers only.  No workspace, no grid barrier, no residency
+// question; at this size the 256-workgroup form spends its time on its own machinery (a 64 KB tensor took
+// 22 us there).  Thread t holds vectors t, t + 1024, ...; the compaction goes row by row (1024 vectors).
+constexpr int SMALL_VECTORS = 8;
+
+template <typename RAW>
+__global__ void __launch_bounds__(SEL_THREADS)
+select_small_kernel(const RAW *__restrict__ x, int64_t numel, int nvf, uint32_t k, RAW *__restrict__ vals,
+                    int32_t *__restrict__ idx)
+{
+    constexpr int VEC = KeyTraits<RAW>::VEC;
+    constexpr uint32_t MASK = KeyTraits<RAW>::MASK;
+    constexpr bool F32 = sizeof(RAW) == 4;
+    constexpr int LAST_BITS = F32 ? 5 : 4;
+    __shared__ uint32_t lh[(1 << MAX_HIST_BITS) + 2 * WAVE];
+    __shared__ uint32_t wave_tot[SEL_THREADS / WAVE];
+    __shared__ uint32_t bcast[2];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const u32x4 *xv = reinterpret_cast<const u32x4 *>(x);
+    const int rows = (nvf + SEL_THREADS - 1) / SEL_THREADS;          // <= SMALL_VECTORS (checked by the host)
+    u32x4 q[SMALL_VECTORS];
+#pragma unroll
+    for (int i = 0; i < SMALL_VECTORS; ++i) {
+        const int v = tid + i * SEL_THREADS;
+        q[i] = v < nvf ? xv[v] : u32x4{0u, 0u, 0u, 0u};
+    }
+    auto for_all = [&](auto f) {
+#pragma unroll
+        for (int i = 0; i < SMALL_VECTORS; ++i)
+            if (tid + i * SEL_THREADS < nvf) for_each_raw(RAW(0), q[i], [&](uint32_t raw, int) { f(raw); });
+        if (tid == 0)
+            for (int64_t i = int64_t(nvf) * VEC; i < numel; ++i) f(x[i]);
+    };
+    uint32_t prefix = 0, k_rem = k;
+    auto pass = [&](auto shift_c, auto bits_c, auto first_c) {
+        constexpr int SHIFT = decltype(shift_c)::value, BITS = decltype(bits_c)::value;
+        constexpr bool FIRST = decltype(first_c)::value;
+        constexpr int NB = 1 << BITS;
+        __syncthreads();
+        for (int i = tid; i < NB + 2 * WAVE; i += SEL_THREADS) lh[i] = 0;
+        __syncthreads();
+        const uint32_t zslot = NB + lane, dslot = NB + WAVE + lane;
+        for_all([&](uint32_t raw) {
+            const uint32_t key = raw & MASK;
+            const uint32_t d = (key >> SHIFT) & (NB - 1);
+            uint32_t a = d ? d : zslot;
+            if (!FIRST) a = ((key >> (SHIFT + BITS)) == prefix) ? a : dslot;
+            atomicAdd(&lh[a], 1u);
+        });
+        __syncthreads();
+        if (tid < WAVE) {
+            const uint32_t z = wave_sum(lh[NB + tid]);
+            if (tid == 0) lh[0] += z;
+        }
+        __syncthreads();
+        resolve_digit_local<NB, BITS>(lh, prefix, k_rem, wave_tot, bcast);
+    };
+    if constexpr (F32) {
+        pass(std::integral_constant<int, 18>{}, std::integral_constant<int, 13>{}, std::true_type{});
+        pass(std::integral_constant<int, 5>{}, std::integral_constant<int, 13>{}, std::false_type{});
+    } else {
+        pass(std::integral_constant<int, 4>{}, std::integral_constant<int, 11>{}, std::true_type{});
+    }
+    pass(std::integral_constant<int, 0>{}, std::integral_constant<int, LAST_BITS>{}, std::false_type{});
+    const uint32_t t = prefix, m = k_rem;   // all digits resolved: the threshold key and its tie budget
+
+    uint32_t run_gt = 0, run_eq = 0;
+    auto keep = [&](uint32_t pos, uint32_t raw, int64_t i) {
+        if (pos < k) {
+            vals[pos] = static_cast<RAW>(raw);
+            idx[pos] = static_cast<int32_t>(i);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < SMALL_VECTORS; ++i) {
+        if (i < rows) {                        // uniform over the workgroup
+            const int v = tid + i * SEL_THREADS;
+            uint32_t cnt = 0;                  // low 16 bits: #gt, high 16 bits: #eq (a row is <= 8192 elements)
+            if (v < nvf)
+                for_each_raw(RAW(0), q[i], [&](uint32_t raw, int) {
+                    const uint32_t key = raw & MASK;
+                    cnt += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
+                });
+            uint32_t total;
+            const uint32_t excl = block_exclusive_scan<SEL_THREADS>(cnt, wave_tot, total);
+            uint32_t my_gt = run_gt + (excl & 0xFFFFu);
+            uint32_t my_eq = run_eq + (excl >> 16);
+            if (cnt) {
+                for_each_raw(RAW(0), q[i], [&](uint32_t raw, int e) {
+                    const uint32_t key = raw & MASK;
+                    const bool gt = key > t, eq = key == t;
+                    if (gt || (eq && my_eq < m)) keep(my_gt + min(my_eq, m), raw, int64_t(v) * VEC + e);
+                    my_gt += gt ? 1u : 0u;
+                    my_eq += eq ? 1u : 0u;
+                });
+            }
+            run_gt += total & 0xFFFFu;
+            run_eq += total >> 16;
+        }
+    }
+    if (tid == 0) {
+        for (int64_t i = int64_t(nvf) * VEC; i < numel; ++i) {
+            const RAW raw = x[i];
+            const uint32_t key = raw & MASK;
+            const bool gt = key > t, eq = key == t;
+            if (gt || (eq && run_eq < m)) keep(run_gt + min(run_eq, m), raw, i);
+            run_gt += gt ? 1u : 0u;
+            run_eq += eq ? 1u : 0u;
+        }
+    }
+}
+
 template <typename RAW>
 __global__ void __launch_bounds__(SEL_THREADS)
 select_fused_kernel(const RAW *__restrict__ x, int64_t numel, int64_t nvf, int64_t vpc, uint32_t k, SelState *st,
@@ -1611,8 +1724,16 @@ dropit_status run_compress(const void *x, int64_t numel, int64_t k, void *vals, 
                                             static_cast<uint32_t>(SelWorkspace::zero_bytes / 4),
                                             static_cast<uint32_t>(k));
     };
-    // Preferred: one persistent kernel, one workgroup per compute unit.
     const int mode = select_mode();
+    // Small tensors (default mode only: the other modes are there to exercise the other forms): one workgroup.
+    if (mode == 0 && numel / KeyTraits<RAW>::VEC <= int64_t(SMALL_VECTORS) * SEL_THREADS) {
+        trace_mark(stream);
+        select_small_kernel<RAW><<<1, SEL_THREADS, 0, stream>>>(xr, numel, int(numel / KeyTraits<RAW>::VEC),
+                                                                static_cast<uint32_t>(k), static_cast<RAW *>(vals), idx);
+        trace_mark(stream);
+        return launch_status();
+    }
+    // Preferred: one persistent kernel, one workgroup per compute unit.
     if (mode != 1) {
         constexpr int VEC = KeyTraits<RAW>::VEC;
         constexpr int TILE_WORDS = SEL_THREADS * VEC + SEL_THREADS * VEC * int(sizeof(RAW)) / 4;

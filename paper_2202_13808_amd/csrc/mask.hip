@@ -159,7 +159,7 @@ extern "C" dropit_status dropit_weight_grad_mask(const void *vals, const uint32_
     if (conv == nullptr && dt == DROPIT_BF16 && k > 0 && c_out >= 1) {
         const int64_t cin = x_shape[ndim - 1];
         const FcProblem fp = {numel / cin, cin, c_out, k};
-        if (fc_dense_mask_native(fp)) {
+        if (fc_dense_mask_native(fp) && dropit_weight_grad_path(x_shape, ndim, dt, k, c_out, conv) == DROPIT_PATH_FC_MFMA) {
             if (vals == nullptr || !aligned(vals, 2)) return DROPIT_EINVAL;
             if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
             const FcDensePlan plan = fc_dense_plan(fp);

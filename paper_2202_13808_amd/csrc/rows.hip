@@ -140,7 +140,7 @@ extern "C" dropit_status dropit_weight_grad_rows(const void *vals, const uint16_
     // the rows of the recovered matrix.  (Everything else expands the flat indices first.)
     if (conv == nullptr && dt == DROPIT_BF16 && k > 0 && c_out >= 1) {
         const FcProblem fp = {rs.rows, rs.row_len, c_out, k};
-        if (fc_dense_supported(fp)) {
+        if (fc_dense_supported(fp) && dropit_weight_grad_path(x_shape, ndim, dt, k, c_out, conv) == DROPIT_PATH_FC_MFMA) {
             if (vals == nullptr || !aligned(vals, 2)) return DROPIT_EINVAL;
             if (dY == nullptr || dW == nullptr || !aligned(dY, 16) || !aligned(dW, 16)) return DROPIT_EINVAL;
             const FcDensePlan plan = fc_dense_plan(fp);

@@ -100,6 +100,56 @@ fc_fma_kernel(const RAW *__restrict__ xhat, const RAW *__restrict__ dY, int64_t 
                 dW[int64_t(j0 + tj + i) * cin + c0 + tc + q] = acc[i][q];
 }
 
+// ---- FC, small layers: recover and multiply in ONE launch --------------------------------------------
+// A layer whose whole input fits the LDS of a compute unit (numel <= SMALL_NUMEL fp32 values) is bound by
+// launches, not by work: the zero fill, the scatter and the product as three kernels cost three dispatch
+// slots for a few microseconds of arithmetic.  Here every workgroup rebuilds the whole R(a^) in its own LDS
+// (zero fill, then one store per pair: the k pairs are a few thousand), fetches its SMALL_JB columns of dY,
+// and multiplies: thread (j, c-group) adds its terms in ascending token order with true fp32 multiply-adds
+// (bf16 inputs are widened exactly), the same order and arithmetic as fc_fma_kernel.
+constexpr int SMALL_NUMEL = 16384;         // elements of x: 64 KB of fp32 in LDS
+constexpr int SMALL_TOKENS = 1024;         // tokens: the dY slice is SMALL_TOKENS x SMALL_JB fp32 = 64 KB
+constexpr int SMALL_JB = 16;               // rows of dW per workgroup
+
+template <typename RAW>
+__global__ void __launch_bounds__(256)
+fc_small_kernel(const RAW *__restrict__ vals, const int32_t *__restrict__ idx, int k, const RAW *__restrict__ dY,
+                int ntok, int cin, int cout, float *__restrict__ dW)
+{
+    extern __shared__ __attribute__((aligned(16))) float small_lds[];
+    float *xs = small_lds;                                 // R(a^)  [ntok][cin]
+    float *gs = small_lds + ntok * cin;                    // dY     [ntok][SMALL_JB], columns j0 ..
+    const int tid = threadIdx.x;
+    const int j0 = blockIdx.x * SMALL_JB;
+    const int numel = ntok * cin;                          // a multiple of 4 (cin is)
+    float4 *xs4 = reinterpret_cast<float4 *>(xs);
+    for (int i = tid; i < numel / 4; i += 256) xs4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int e = tid; e < ntok * SMALL_JB; e += 256) {
+        const int n = e / SMALL_JB, j = j0 + e % SMALL_JB;
+        gs[e] = j < cout ? to_f32(dY[int64_t(n) * cout + j]) : 0.f;
+    }
+    __syncthreads();
+    for (int q = tid; q < k; q += 256) {
+        const int i = idx[q];
+        if (i >= 0 && i < numel) xs[i] = to_f32(vals[q]);  // an out-of-range index is ignored, never written
+    }
+    __syncthreads();
+    const int j = tid / 16;                                // 16 rows of dW x 16 groups of 4 columns per pass
+    for (int c0 = (tid % 16) * 4; c0 < cin; c0 += 64) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int n = 0; n < ntok; ++n) {
+            const float g = gs[n * SMALL_JB + j];
+            const float4 b = *reinterpret_cast<const float4 *>(xs + n * cin + c0);
+            acc[0] = __builtin_fmaf(g, b.x, acc[0]);
+            acc[1] = __builtin_fmaf(g, b.y, acc[1]);
+            acc[2] = __builtin_fmaf(g, b.z, acc[2]);
+            acc[3] = __builtin_fmaf(g, b.w, acc[3]);
+        }
+        if (j0 + j < cout)
+            *reinterpret_cast<float4 *>(dW + int64_t(j0 + j) * cin + c0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    }
+}
+
 // ---- conv 3x3 / stride 1 / pad 1: one workgroup per (j, c), fixed-order reduce
 template <typename RAW>
 __global__ void __launch_bounds__(256)
@@ -312,8 +362,14 @@ static ConvGeneral general_of(const Problem &p, int64_t k)
 }
 
 // Which kernels serve this problem.
+static bool fc_small(const Problem &p)
+{
+    return !p.conv && p.numel <= SMALL_NUMEL && p.ntok <= SMALL_TOKENS && p.cin % 4 == 0 && p.cout <= 4096;
+}
+
 static dropit_wgrad_path choose_path(const Problem &p, dropit_dtype dt, int64_t k)
 {
+    if (fc_small(p)) return DROPIT_PATH_FC_SMALL;
     if (dt != DROPIT_BF16) return DROPIT_PATH_FMA;
     if (!p.conv) return use_fc_dense(FcProblem{p.ntok, p.cin, p.cout, k}) ? DROPIT_PATH_FC_MFMA : DROPIT_PATH_FMA;
     if (p.is_3x3_s1_p1 && !p.nhwc) {
@@ -337,6 +393,7 @@ static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
     case DROPIT_PATH_CONV_GEMM: return conv_gemm_plan(cp).total();
     case DROPIT_PATH_CONV_BANDS: return conv_mfma_plan(cp).total();
     case DROPIT_PATH_CONV_IM2COL: return conv_im2col_plan(general_of(p, k)).total();
+    case DROPIT_PATH_FC_SMALL: return 256;           // nothing is kept outside LDS; a token size so that callers' buffers exist
     default: return dense_bytes(p, dt);
     }
 }
@@ -369,6 +426,36 @@ static dropit_status run(const Problem &p, const void *vals, const int32_t *idx,
     case DROPIT_PATH_CONV_IM2COL: {
         const ConvGeneral cg = general_of(p, k);
         return conv_im2col_run(cg, conv_im2col_plan(cg), vals, idx, dY, dW, ws, stream);
+    }
+    case DROPIT_PATH_FC_SMALL: {
+        const size_t lds = size_t(p.numel + p.ntok * SMALL_JB) * sizeof(float);
+        const unsigned grid = unsigned((p.cout + SMALL_JB - 1) / SMALL_JB);
+        trace_mark(stream);
+        if (dt == DROPIT_BF16) {
+            static std::atomic<uint64_t> set_up{0};
+            if (!once_per_device(set_up, [] {
+                    return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_small_kernel<uint16_t>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               int((SMALL_NUMEL + SMALL_TOKENS * SMALL_JB) * sizeof(float))) == hipSuccess;
+                }))
+                return DROPIT_EHIP;
+            fc_small_kernel<uint16_t><<<grid, 256, lds, stream>>>(static_cast<const uint16_t *>(vals), idx, int(k),
+                                                                  static_cast<const uint16_t *>(dY), int(p.ntok),
+                                                                  int(p.cin), int(p.cout), dW);
+        } else {
+            static std::atomic<uint64_t> set_up{0};
+            if (!once_per_device(set_up, [] {
+                    return hipFuncSetAttribute(reinterpret_cast<const void *>(fc_small_kernel<uint32_t>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               int((SMALL_NUMEL + SMALL_TOKENS * SMALL_JB) * sizeof(float))) == hipSuccess;
+                }))
+                return DROPIT_EHIP;
+            fc_small_kernel<uint32_t><<<grid, 256, lds, stream>>>(static_cast<const uint32_t *>(vals), idx, int(k),
+                                                                  static_cast<const uint32_t *>(dY), int(p.ntok),
+                                                                  int(p.cin), int(p.cout), dW);
+        }
+        trace_mark(stream);
+        return launch_status();
     }
     default: break;
     }

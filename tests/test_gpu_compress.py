@@ -456,3 +456,13 @@ def test_staged_form_sizes_and_ragged_ends(numel, dist):
     for gamma in (0.9, 0.8, 0.6):
         s = _run_with_state(x, gamma)
         print("staged sizes", numel, dist, gamma, s, flush=True)
+
+
+@pytest.mark.parametrize("dtype,numel", [("f32", 32767), ("f32", 32768), ("f32", 32771), ("f32", 32776),
+                                         ("bf16", 65535), ("bf16", 65536), ("bf16", 65543), ("bf16", 65544),
+                                         ("bf16", 20000), ("f32", 1025), ("bf16", 8193)])
+def test_one_workgroup_form_and_its_size_limit(dtype, numel):
+    """Tensors of up to 8 x 1024 16-byte vectors take the one-workgroup kernel (registers only, no workspace);
+    one element more takes the persistent kernel.  Same bytes on either side of the limit."""
+    for dist, gamma in (("normal", 0.9), ("relu", 0.3), ("gelu", 0.75)):
+        run_and_compare(activation((numel,), dist, 11 + numel % 13, dtype), gamma, "small")

@@ -62,6 +62,21 @@ def test_fc_shapes(dtype, ntok, cin, cout, gamma):
     assert_close(got, ref, TOL[dtype])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("ntok,cin,cout,gamma", [(256, 64, 128, 0.9), (1024, 16, 40, 0.5), (5, 24, 16, 0.5), (1, 4, 1, 0.0),
+                                                 (33, 496, 3, 0.9), (64, 256, 4096, 0.9), (100, 132, 17, 0.7)])
+def test_fc_small_layers_take_one_launch(dtype, ntok, cin, cout, gamma):
+    """At most 16384 input elements (c_in a multiple of 4): recover in LDS + exact fp32 multiply-adds, one kernel."""
+    print("wgrad fc small", dtype, ntok, cin, cout, gamma, flush=True)
+    x = activation((ntok, cin), "normal", 600 + ntok, dtype)
+    dy = gradient((ntok, cout), 0.02, 700 + ntok, dtype)
+    k = oracle.keep_count(x.size, gamma)
+    assert dropit.weight_grad_path(x.shape, torch.float32 if dtype == "f32" else torch.bfloat16, k, cout) == "fc_small"
+    got, _, _ = gpu_dw(x, dy, gamma, cout)
+    ref = oracle.dw_fc(ref_xhat(x, gamma), oracle.widen(dy))
+    assert_close(got, ref, 1e-5)            # fp32 accumulation of exact products in token order, for either input type
+
+
 @pytest.mark.parametrize("ntok,cin,cout,gamma", [
     (777, 257, 40, 0.9),      # c_in not a multiple of 8: padded row pitch of the recovered matrix
     (5, 24, 16, 0.5),         # fewer tokens than one token block
@@ -323,8 +338,9 @@ def test_conv_channels_last(dtype, x_shape, J, geom):
     k = oracle.keep_count(x.size, 0.6)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     pointwise = geom[:6] == (1, 1, 1, 1, 0, 0)         # a fully-connected layer over the positions in this layout
+    small = pointwise and x.size <= 16384 and N * H * W <= 1024 and C % 4 == 0      # ... and a small one takes the one-launch form
     assert dropit.weight_grad_path(x.shape, tdt, k, J, conv=geom, layout="nhwc") == \
-        ("fma" if dtype == "f32" else "fc_mfma" if pointwise else "conv_im2col")
+        ("fc_small" if small else "fma" if dtype == "f32" else "fc_mfma" if pointwise else "conv_im2col")
     xd, dyd = to_device(x), to_device(dy)
     vals, idx = dropit.compress(xd, 0.6)
     dW = dropit.weight_grad(vals, idx, x.shape, dyd, J, conv=geom, layout="nhwc")
