@@ -39,9 +39,17 @@
 extern "C" {
 #endif
 
-typedef enum { DROPIT_F32 = 0, DROPIT_BF16 = 1 } dropit_dtype;
+/* In C an enumeration is an int and any int may arrive in one; C++ callers and this library's own (C++) sources
+ * get the same guarantee from a fixed underlying type, so an unknown code is an error value, never undefined. */
+#ifdef __cplusplus
+#define DROPIT_ENUM(name) enum name : int
+#else
+#define DROPIT_ENUM(name) enum name
+#endif
 
-typedef enum {
+typedef DROPIT_ENUM(dropit_dtype) { DROPIT_F32 = 0, DROPIT_BF16 = 1 } dropit_dtype;
+
+typedef DROPIT_ENUM(dropit_status) {
     DROPIT_OK = 0,
     DROPIT_EINVAL = 1,        /* null / misaligned pointer, bad shape, gamma outside [0,1], numel > 2^31-1 */
     DROPIT_EWORKSPACE = 2,    /* workspace smaller than the matching *_workspace_bytes query */
@@ -146,7 +154,7 @@ size_t dropit_weight_grad_workspace_bytes(const int64_t *x_shape, int ndim, drop
 
 /* Which kernels dropit_weight_grad runs for these arguments (arguments as there; host-only, no GPU work):
  * DROPIT_PATH_NONE for invalid or unsupported arguments. */
-typedef enum {
+typedef DROPIT_ENUM(dropit_wgrad_path) {
     DROPIT_PATH_NONE = 0,
     DROPIT_PATH_FC_MFMA = 1,        /* recover + split-K bf16 MFMA GEMM */
     DROPIT_PATH_CONV_BANDS = 2,     /* 3x3/s1/p1 bf16: row bands in LDS, implicit im2col on the matrix cores */
@@ -216,7 +224,7 @@ dropit_status dropit_weight_grad_nhwc(const void *vals, const int32_t *idx, int6
                                       float *dW, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Row form of the cache: cheaper indices (Sec. 5 counts the indices as the
+ * Row form of the cache: cheaper indices (Sec. 4.3 counts the indices as the
  * method's memory cost; the appendix on choosing gamma prices an int32 index like
  * an fp32 activation).  The tensor is read as rows of its last dimension
  * (row_len = shape[ndim-1] <= 65536, rows = numel / row_len).  A retained element
@@ -250,7 +258,7 @@ dropit_status dropit_weight_grad_rows(const void *vals, const uint16_t *col, con
                                       void *hip_stream);
 
 /*
- * Bit-mask form of the cache (Sec. 5 counts the index bytes as part of the method's memory;
+ * Bit-mask form of the cache (Sec. 4.3 counts the index bytes as part of the method's memory;
  * the appendix on choosing gamma prices an int32 index at one fp32 activation).  Instead of idx:
  *     mask[ceil(numel/32)]  uint32, bit (i mod 32) of word (i div 32) set iff element i is retained
  *                           (bits past numel are 0);

@@ -142,7 +142,7 @@ def compress_random(x: np.ndarray, k: int, seed: int):
 
 def rows_from_pairs(idx: np.ndarray, shape):
     """Row form of a retained index set: (col uint16 [k], rowptr int32 [rows+1]); rows are the last
-    dimension of `shape`  [Sec. 5, index memory]."""
+    dimension of `shape`  [Sec. 4.3, index memory]."""
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     row_len = int(shape[-1])
     rows = int(np.prod(shape[:-1], dtype=np.int64)) if len(shape) > 1 else 1
@@ -168,7 +168,7 @@ MASK_BLOCK = 1024      # elements per entry of the block-offset table of the bit
 
 def mask_from_pairs(idx: np.ndarray, numel: int, block: int = MASK_BLOCK):
     """Bit-mask form of a retained index set: (mask uint32 [ceil(numel/32)], blockptr int32
-    [ceil(numel/block)+1])  [Sec. 5, index memory]."""
+    [ceil(numel/block)+1])  [Sec. 4.3, index memory]."""
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     mask = np.empty((numel + 31) // 32, dtype=np.uint32)
     blockptr = np.empty((numel + block - 1) // block + 1, dtype=np.int32)

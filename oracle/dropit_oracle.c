@@ -15,7 +15,7 @@
  *   - random dropping   D(a) with X_r a uniformly random k-subset            [Sec. 3.3 Random Elements]
  *   - row form of X_r   the retained indices re-encoded as 16-bit positions within
  *                       rows plus row offsets (lossless; the index cost the paper
- *                       discusses)                          [Sec. 5, memory of indices; App. on choosing gamma]
+ *                       discusses)                          [Sec. 4.3, memory of indices; App. on choosing gamma]
  *   - recover           R(a^): dense tensor, dropped positions zero
  *                                                         [Sec. 3.2; Fig. 1 caption]
  *   - FC weight grad    g[j][c] = sum_n dz[n][j] * a^[n][c]
@@ -220,7 +220,7 @@ int oracle_pairs_from_rows(const uint16_t *col, const int32_t *rowptr, int64_t r
  * `block` consecutive elements (a multiple of 32), the number of retained elements
  * before it: blockptr[b], b = 0..ceil(numel/block).  numel/8 bytes of mask against
  * 4 bytes per retained int32 index: smaller whenever more than 1/32 of the tensor
- * is kept (Sec. 5 counts the index bytes as part of the method's memory; the
+ * is kept (Sec. 4.3 counts the index bytes as part of the method's memory; the
  * appendix on choosing gamma prices an int32 index at one fp32 activation).
  * Returns 0, or -1 on bad arguments (an index outside the tensor or out of order). */
 int oracle_mask_from_pairs(const int32_t *idx, int64_t k, int64_t numel, int64_t block,

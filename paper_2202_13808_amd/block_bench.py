@@ -2,7 +2,7 @@
 
     python -m paper_2202_13808_amd.block_bench [--batch 128] [--depth 12] [--steps 20]
 
-Reproduces the *shape* of the paper's memory / speed comparison (Sec. 5, the table that lists maximum
+Reproduces the *shape* of the paper's memory / speed comparison (Sec. 4.3, the table that lists maximum
 memory and ms per iteration at batch size 128, and the cached-tensor table): synthetic tokens, random
 weights, bf16, one GPU.  DropIT is applied to the fully-connected layers of the attention and MLP halves
 of every block (Sec. 3.5); the embedding and the classifier are the first and last layers and stay plain.

@@ -1,6 +1,6 @@
 // Bit-mask form of the retained index set: one bit per element + block offsets.
 //
-// The paper counts the indices as the method's own memory cost (Sec. 5: index memory next to the
+// The paper counts the indices as the method's own memory cost (Sec. 4.3: index memory next to the
 // saved activations; appendix on choosing gamma: an int32 index is as wide as an fp32 activation).
 // A mask of numel/8 bytes locates the retained elements of a tensor whatever their number: smaller
 // than 4-byte indices whenever more than 1/32 of the tensor is kept (gamma < 0.97), and than the

@@ -1,6 +1,6 @@
 // Row form of the retained index set: 16-bit positions within rows + row offsets.
 //
-// The paper counts the indices as the method's own memory cost (Sec. 5: index memory next to the
+// The paper counts the indices as the method's own memory cost (Sec. 4.3: index memory next to the
 // saved activations; appendix on choosing gamma: an int32 index is as wide as an fp32 activation,
 // hence gamma > 50 %).  With bf16 activations an int32 index is twice as wide as the value it
 // locates.  Reading the tensor as rows of its last dimension (<= 65536 long), a retained element

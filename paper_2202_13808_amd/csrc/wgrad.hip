@@ -9,6 +9,7 @@
 // any bf16 shape the MFMA kernels do not cover.
 #include "common.hpp"
 #include "wgrad_internal.hpp"
+#include "dev_hooks.hpp"
 #include <cstdlib>
 
 namespace dropit {
@@ -375,9 +376,7 @@ static dropit_wgrad_path choose_path(const Problem &p, dropit_dtype dt, int64_t 
     if (p.is_3x3_s1_p1 && !p.nhwc) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
         bool gemm = conv_gemm_preferred(cp);
-#ifdef DROPIT_TUNING
-        if (const char *e = getenv("DROPIT_CONV_PATH")) gemm = e[0] == 'g' && conv_gemm_supported(cp);
-#endif
+        if (const long forced = dev_env("DROPIT_CONV_GEMM", -1); forced >= 0) gemm = forced == 1 && conv_gemm_supported(cp);
         if (gemm) return DROPIT_PATH_CONV_GEMM;
         if (conv_mfma_supported(cp)) return DROPIT_PATH_CONV_BANDS;
     }

@@ -17,6 +17,7 @@
 // and written once in full lines, no separate zero fill; other workgroups of the same launch transpose
 // dY from [N][J][H][W] to token-major [N*H*W][J].  The result lands in dW's own layout [J][C][3][3].
 #include "wgrad_internal.hpp"
+#include "dev_hooks.hpp"
 
 namespace dropit {
 namespace {
@@ -145,9 +146,7 @@ ConvGemmPlan conv_gemm_plan(const ConvProblem &p)
     const int64_t HW = p.H * p.W;
     // channel block: a multiple of 8, its tile within the LDS budget where that leaves at least 8 channels
     int64_t budget = 32 * 1024;                // several workgroups per compute unit (measured: 16-24 KB and 64+ KB slower)
-#ifdef DROPIT_TUNING
-    if (const char *e = getenv("DROPIT_IM2COL_LDS")) budget = atol(e);
-#endif
+    budget = dev_env("DROPIT_IM2COL_LDS", budget);
     int64_t cb = budget / (HW * 18) / 8 * 8;
     // ... but token segments of at least 16 channels (288 bytes) while the tile stays within 64 KB:
     // with 8 (144 bytes, 2.25 lines) the writes of B were 3 us slower on 14x14 planes

@@ -19,6 +19,7 @@
 // materialise the nine-fold B; this path serves everything else: 1x1, strided, dilated, large-window
 // (patch embedding) convolutions, and channels-last tensors.
 #include "wgrad_internal.hpp"
+#include "dev_hooks.hpp"
 #include <cstdlib>
 
 namespace dropit {
@@ -340,9 +341,7 @@ ConvIm2colPlan conv_im2col_plan(const ConvGeneral &p)
     const int64_t taps = p.g.kh * p.g.kw;
     int64_t budget = 32 * 1024;                // several workgroups per compute unit hide each other's load rounds (64 KB: 10-15 % slower)
     const int64_t hard = 150 * 1024;
-#ifdef DROPIT_TUNING
-    if (const char *e = getenv("DROPIT_IM2COL_LDS")) budget = atol(e);
-#endif
+    budget = dev_env("DROPIT_IM2COL_LDS", budget);
     const int64_t units_total = p.nhwc ? taps : p.C;          // what a block is a range of
     const int64_t per_unit = p.nhwc ? p.C : taps;             // columns per unit
     plan.tiled = false;
@@ -419,9 +418,7 @@ dropit_status conv_im2col_run(const ConvGeneral &p, const ConvIm2colPlan &plan, 
         // at least 8 threads per channel run: neighbouring lanes then read neighbouring pairs (with one or two
         // threads per run every lane of a load asks for a line of its own: 1x1 over 256 channels 144 -> 126 us)
         int tmin = 8;
-#ifdef DROPIT_TUNING
-        if (const char *e = getenv("DROPIT_IM2COL_TMIN")) tmin = atoi(e);
-#endif
+        tmin = int(dev_env("DROPIT_IM2COL_TMIN", tmin));
         const TileShape ts = {plan.nblocks, plan.blk, plan.bands, plan.rb, plan.rowlen, tmin};
         const int64_t pad_chunks = (plan.gemm.ntok_pad - plan.fp.ntok) * plan.gemm.pitch / 8;
         const int pad_wgs = int(std::min<int64_t>((pad_chunks + 255) / 256, 64));

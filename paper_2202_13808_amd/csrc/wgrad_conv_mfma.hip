@@ -65,10 +65,6 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     const int slots = rows + 2;                        // input rows r0-1 .. r0+rows
     const int slot_bytes = BC * pitch_c;
 
-#ifdef DROPIT_PHASE_CLOCK
-    unsigned long long pc[5];
-    pc[0] = wall_clock64();
-#endif
     // With several images per workgroup (MULTI) the accumulators live across the images; with one they
     // start after the scatter, which leaves the scatter the registers to keep two batches of loads in flight.
     f32x16 acc[9];
@@ -106,9 +102,6 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
         s_last[tid] = max(last, first);
     }
     __syncthreads();
-#ifdef DROPIT_PHASE_CLOCK
-    pc[1] = wall_clock64();
-#endif
     // Each wavefront takes 8 of the 64 channels, SC at a time: the runs of SC channels are walked
     // together so that SC x 2 loads per lane are in flight, and everything per channel (run bounds,
     // plane offset, LDS row base) is wave-uniform scalar work.  Row and column of a pair come from
@@ -167,9 +160,6 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
     }
     __syncthreads();
 
-#ifdef DROPIT_PHASE_CLOCK
-    pc[2] = wall_clock64();
-#endif
     // ---- multiply ---------------------------------------------------------------
     if constexpr (!MULTI) {
 #pragma unroll
@@ -239,9 +229,6 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
 
     }   // images of the group
 
-#ifdef DROPIT_PHASE_CLOCK
-    pc[3] = wall_clock64();
-#endif
     // ---- the two K-groups meet: group 1 parks its sums in LDS (the rows are no longer needed: 4 wavefronts x
     // 9 tiles x 4 KB = exactly the 144 KB the accumulators take), group 0 adds them and writes -----------
     __syncthreads();                                   // every wavefront is done reading the rows
@@ -265,13 +252,6 @@ conv3x3_mfma_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict_
                 if (jj < J && cc < C) dst[(int64_t(s) * J + jj) * C + cc] = acc[s][e] + park[(s * 16 + e) * WAVE + lane];
             }
     }
-#ifdef DROPIT_PHASE_CLOCK
-    pc[4] = wall_clock64();
-    if (blockIdx.x == gridDim.x / 2 && tid == 0) {
-        float *o = partial + int64_t(gridDim.x / (cb_count * jb_count)) * 9 * J * C;   // past the partials (the probe over-allocates)
-        for (int i = 0; i < 4; ++i) o[i] = float(pc[i + 1] - pc[i]);
-    }
-#endif
 }
 
 // Rows of a width that is not a multiple of 8 (28, 14, 7 in the later stages of a ResNet): dY is copied

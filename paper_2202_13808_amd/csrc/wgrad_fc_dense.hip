@@ -20,12 +20,9 @@
 // so dW is bit-reproducible.
 #include "common.hpp"
 #include "wgrad_internal.hpp"
+#include "dev_hooks.hpp"
 #include <cstdlib>
 #include <type_traits>
-
-#ifndef DROPIT_ABLATE
-#define DROPIT_ABLATE 0          // development only: bit mask of pipeline parts to leave out (wrong results)
-#endif
 
 namespace dropit {
 namespace {
@@ -325,7 +322,6 @@ __device__ inline void lgkm_wait()           // until at most N of this wavefron
 
 __device__ inline void workgroup_barrier()
 {
-    if (DROPIT_ABLATE & 16) return;          // development only, and only together with bits 1|4 (no LDS traffic at all)
     asm volatile("s_barrier" ::: "memory");
 }
 
@@ -405,7 +401,6 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         const int m = min(m0 + b / 2, M - 8);
         a_off[i] = uint32_t(r * M + m) * 2u;
         a_off_tail[i] = uint32_t(min(r, rows_tail - 1) * M + m) * 2u;
-        if (DROPIT_ABLATE & 64) a_off[i] = a_off_tail[i] = 0;       // development only: every lane asks for the same 16 bytes
     }
 #pragma unroll
     for (int i = 0; i < C::B_LOADS; ++i) {
@@ -414,12 +409,10 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         const int b = (o % C::ROW_B) ^ ((r & 3) << 6);
         const int n = min(n0 + b / 2, pitch - 8);
         b_off[i] = uint32_t(r * pitch + n) * 2u;
-        if (DROPIT_ABLATE & 64) b_off[i] = 0;
     }
     // load number q (0 .. LOADS-1) of a step: the A loads first, then the B loads
     auto issue_load = [&](auto q_, int stage, int kb) {
         constexpr int q = decltype(q_)::value;
-        if (DROPIT_ABLATE & 1) return;
         if constexpr (q < C::A_LOADS) {
             const char *abase = reinterpret_cast<const char *>(dY) + int64_t(kb) * BK * M * 2;
             char *sa = lds + stage * C::STAGE_BYTES + wave * (C::A_LOADS * 1024);
@@ -467,16 +460,9 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     static_assert(NM >= 2, "the reads of a sub-step go out with the first half of the previous one's MFMAs");
     const uint32_t lds_base = uint32_t(size_t(DROPIT_LPTR(lds)));
     s16x4 fa[2][C::FM][2], fb[2][C::FN][2];            // two fragment sets: one multiplying, one being read
-    if (DROPIT_ABLATE & 4) {
-        for (int q = 0; q < 2; ++q) {
-            for (int i = 0; i < C::FM; ++i) fa[q][i][0] = fa[q][i][1] = s16x4{0, 0, 0, 0};
-            for (int j = 0; j < C::FN; ++j) fb[q][j][0] = fb[q][j][1] = s16x4{0, 0, 0, 0};
-        }
-    }
     // read number r (0 .. SET_READS-1) of sub-step kk of the stage at `stage_base`, into fragment set `set`
     auto issue_read = [&](auto set_, auto kk_, auto r_, uint32_t stage_base) {
         constexpr int set = decltype(set_)::value, kk = decltype(kk_)::value, r = decltype(r_)::value;
-        if (DROPIT_ABLATE & 4) return;
         if constexpr (r < 2 * C::FM) {
             constexpr int i = r / 2, h = r % 2;
             fa[set][i][h] = tr_read<(kk * 16 + h * 4) * C::ROW_A>(stage_base + a_frag[i]);
@@ -509,8 +495,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         }
         static_for<0, NM>([&](auto m_) {
             constexpr int m = decltype(m_)::value, i = m / C::FN, j = m % C::FN;
-            if (!(DROPIT_ABLATE & 8))
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
             static_for<m * READS_PER_MFMA, (m + 1) * READS_PER_MFMA>([&](auto r_) {
                 if constexpr (read_next && decltype(r_)::value < SET_READS)
                     issue_read(std::integral_constant<int, 1 - set>{}, next_kk_, r_, next_base);
@@ -536,18 +521,6 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     // then the sub-steps; the exposed read is for a second resident workgroup to hide.
     // Loads past the last block are clamped to it instead of branched around, so the in-flight
     // count is the same in every iteration; they land in stages that are never multiplied.
-#ifdef DROPIT_PHASE_CLOCK          // development only: where does a wavefront's step go (100 MHz ticks)
-    unsigned long long pc_t[5] = {0, 0, 0, 0, 0}, pc_sum[4] = {0, 0, 0, 0};
-    const unsigned long long pc_begin = wall_clock64();
-    const unsigned long long pc_cyc_begin = __builtin_readcyclecounter();
-#define PHASE_CLOCK(i)                                                        \
-    do {                                                                      \
-        pc_t[i] = wall_clock64();                                             \
-        if ((i) > 0) pc_sum[(i) - 1] += pc_t[i] - pc_t[(i) - 1];              \
-    } while (0)
-#else
-#define PHASE_CLOCK(i) do { } while (0)
-#endif
     if (steps > 0) {
         constexpr int D = C::STAGES - 1;
         constexpr int AHEAD = C::EARLY ? 1 : 0;        // how many steps before its own a stage must be complete
@@ -565,11 +538,8 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         int stage = 0, fill = D;                       // s % STAGES and (s + D) % STAGES
         for (int s = 0; s < steps; ++s) {
             const int next = stage + 1 == C::STAGES ? 0 : stage + 1;
-            PHASE_CLOCK(0);
             wait_loads<(D - 1 - AHEAD) * C::LOADS>();
-            PHASE_CLOCK(1);
             workgroup_barrier();
-            PHASE_CLOCK(2);
             const uint32_t cur_base = lds_base + stage * C::STAGE_BYTES;
             const uint32_t next_base = lds_base + next * C::STAGE_BYTES;
             const int load_kb = min(kb_begin + s + D, kb_last);
@@ -584,9 +554,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
                 else
                     substep(kk_, std::integral_constant<int, 0>{}, std::integral_constant<bool, C::EARLY>{}, next_base,
                             fill, load_kb);
-                if constexpr (kk == 0) PHASE_CLOCK(3);
             });
-            PHASE_CLOCK(4);
             stage = next;
             fill = fill + 1 == C::STAGES ? 0 : fill + 1;
         }
@@ -594,10 +562,6 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         lgkm_wait<0>();                                // or registers when the wavefront goes on
     }
 
-#ifdef DROPIT_PHASE_CLOCK
-    const unsigned long long pc_loop_end = wall_clock64();
-    const unsigned long long pc_cyc_end = __builtin_readcyclecounter();
-#endif
     // epilogue: acc[i][j][e] is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32 of its 32x32 block.
     if (splits == 1) {                                  // straight into dW, row-major
 #pragma unroll
@@ -623,21 +587,10 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             for (int j = 0; j < C::FN; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if ((DROPIT_ABLATE & 2) && acc[i][j][q * 4] != 123.456f) continue;
                     const f32x4 v4 = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
                     dst[((i * C::FN + j) * 4 + q) * C::NTHREADS] = v4;
                 }
     }
-#ifdef DROPIT_PHASE_CLOCK
-    if (v == total / 2 && lane == 0 && (wave == 0 || wave == C::NWAVES - 1)) {
-        float *o = out + int64_t(splits) * nb_count * mb_count * BM * BN + (wave == 0 ? 0 : 8);      // scratch past the partials (the probe over-allocates)
-        for (int i = 0; i < 4; ++i) o[i] = float(pc_sum[i]);
-        o[4] = float(steps);
-        o[5] = float(pc_t[0] ? pc_loop_end - pc_begin : 0);
-        o[6] = float(wall_clock64() - pc_loop_end);
-        o[7] = float(pc_cyc_end - pc_cyc_begin);                             // shader clocks over the same span as o[5]
-    }
-#endif
 }
 
 // Sums the split-K partials in ascending split order, dW = ((p0 + p1) + p2) + ..., and moves
@@ -748,9 +701,7 @@ int tuned_splits(int tiles, int nkb)
     // traffic costs more than the idle compute units (measured on 3136 and 12544 tokens:
     // the best slice count was the one with 19.6 blocks per slice both times)
     int splits = std::min(256 * C::WGS_PER_CU / tiles, std::max(1, (nkb + 10) / 20));
-#ifdef DROPIT_TUNING
-    if (const char *e = getenv("DROPIT_FC_SPLITS")) splits = atoi(e);
-#endif
+    splits = int(dev_env("DROPIT_FC_SPLITS", splits));
     if (splits > nkb) splits = nkb;
     if (splits < 1) splits = 1;
     if (splits > 256) splits = 256;      // one slice per compute unit when the whole result is a single tile
@@ -759,9 +710,7 @@ int tuned_splits(int tiles, int nkb)
 
 bool use_narrow(const FcProblem &p)
 {
-#ifdef DROPIT_TUNING
-    if (const char *e = getenv("DROPIT_GEMM_NARROW")) return e[0] == '1';
-#endif
+    if (const long forced = dev_env("DROPIT_GEMM_NARROW", -1); forced >= 0) return forced == 1;
     return p.cout <= CfgNarrow::BM;
 }
 
@@ -874,9 +823,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     const int64_t margin = 2 * static_cast<int64_t>(__builtin_sqrt(static_cast<double>(p.k))) + 256;
     const double pairs_per_wg = static_cast<double>(p.k) * plan.rows_per_wg / static_cast<double>(std::max<int64_t>(p.ntok, 1));
     bool windowed = pairs_per_wg + 2.0 * margin <= double(RECOVER_WINDOW) * RECOVER_THREADS;
-#ifdef DROPIT_TUNING
-    if (getenv("DROPIT_RECOVER_STREAM")) windowed = false;
-#endif
+    if (dev_env("DROPIT_RECOVER_STREAM", 0)) windowed = false;
     if (windowed) {
         fc_recover_kernel<<<recover_grid, RECOVER_THREADS, recover_lds, stream>>>(
             static_cast<const uint16_t *>(vals), idx, p.k, p.ntok, ntok_pad, int(p.cin), plan.pitch, plan.rows_per_wg,

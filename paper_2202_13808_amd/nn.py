@@ -43,7 +43,7 @@ def _pair(v: _Int2) -> Tuple[int, int]:
 
 
 # ---------------------------------------------------------------------------------------------
-# cache accounting (Sec. 5, table of cached-tensor memory: value bytes fall by exactly gamma;
+# cache accounting (Sec. 4.3, table of cached-tensor memory: value bytes fall by exactly gamma;
 # the indices are the method's own extra cost)
 # ---------------------------------------------------------------------------------------------
 class CacheMeter:
@@ -90,8 +90,8 @@ def _compress_input(x: torch.Tensor, gamma: float, seed: Optional[int], fmt: str
     if not x.is_cuda:
         raise RuntimeError("DropIT layers train on device tensors only: there is no CPU path")
     xc = x.detach()
-    if not xc.is_contiguous():
-        xc = xc.contiguous()
+    if not xc.is_contiguous() or xc.data_ptr() % 16:      # the library reads 16-byte vectors: a contiguous view that
+        xc = xc.clone(memory_format=torch.contiguous_format)   # starts inside a buffer (x[1:]) is copied to an aligned one
     if fmt != "flat":
         if seed is not None:
             raise ValueError("the random strategy keeps flat indices (index_format='flat')")
@@ -115,11 +115,13 @@ def _weight_grad(cache: Sequence[torch.Tensor], fmt: str, x_shape, dy: torch.Ten
 
 def _match_dtype(dy: torch.Tensor, vals: torch.Tensor) -> torch.Tensor:
     dy = dy if dy.dtype == vals.dtype else dy.to(vals.dtype)
-    return dy if dy.is_contiguous() else dy.contiguous()
+    if not dy.is_contiguous() or dy.data_ptr() % 16:       # 16-byte vector loads, as for the input
+        dy = dy.clone(memory_format=torch.contiguous_format)
+    return dy
 
 
 # ---------------------------------------------------------------------------------------------
-# fully-connected layer (Sec. 3.3, weight gradient of a fully-connected layer from the retained elements)
+# fully-connected layer (Sec. 3.2, Eq. fc_backward_elem_save, weight gradient of a fully-connected layer from the retained elements)
 # ---------------------------------------------------------------------------------------------
 class _LinearFn(torch.autograd.Function):
     @staticmethod
@@ -156,7 +158,7 @@ def linear(x: torch.Tensor, weight: torch.Tensor, bias: Optional[torch.Tensor] =
 
 
 # ---------------------------------------------------------------------------------------------
-# convolution (Sec. 3.3, weight gradient of a convolutional layer from the retained elements)
+# convolution (Sec. 3.2, Eq. conv_backward_elem, weight gradient of a convolutional layer from the retained elements)
 # ---------------------------------------------------------------------------------------------
 class _Conv2dFn(torch.autograd.Function):
     @staticmethod

@@ -140,7 +140,7 @@ def _mlp_stack(depth, dim, hidden, dtype):
 
 @pytest.mark.parametrize("gamma", [0.6, 0.7, 0.8, 0.9])
 def test_cached_value_bytes_fall_by_gamma(gamma):
-    """Sec. 5, cached-tensor table: the retained values take (1 - gamma) of the dense cache (its four
+    """Sec. 4.3, cached-tensor table: the retained values take (1 - gamma) of the dense cache (its four
     dropped columns are 0.4, 0.3, 0.2, 0.1 of the baseline to three figures); here exactly k * 2 bytes per
     layer with k = floor((1 - gamma) * numel).  The allocator's own count of live bytes after the forward
     pass must fall by the dense cache minus values and indices."""
@@ -224,3 +224,22 @@ def test_training_steps_reduce_the_loss():
         opt.step()
         losses.append(float(loss.detach()))
     assert losses[-1] < 0.25 * losses[0], (losses[0], losses[-1])
+
+
+def test_linear_takes_a_contiguous_view_that_starts_inside_a_buffer():
+    """x[1:] of a [tokens + 1, c] buffer with an odd row length is contiguous but not 16-byte aligned; the layer
+    copies it to an aligned tensor instead of handing the library a pointer it rejects."""
+    torch.manual_seed(3)
+    buf = torch.randn(65, 100, device="cuda:0", dtype=torch.bfloat16)
+    x = buf[1:]
+    assert x.is_contiguous() and x.data_ptr() % 16 != 0
+    lin = dnn.Linear(100, 24, gamma=0.8).to("cuda:0", torch.bfloat16)
+    y = lin(x)
+    gbuf = torch.randn(65, 24, device="cuda:0", dtype=torch.bfloat16)
+    y.backward(gbuf[1:])                                   # the incoming gradient is an offset view too
+    torch.cuda.synchronize()
+    ref = dnn.Linear(100, 24, gamma=0.8).to("cuda:0", torch.bfloat16)
+    ref.load_state_dict(lin.state_dict())
+    ref(x.clone()).backward(gbuf[1:].clone())
+    torch.cuda.synchronize()
+    assert torch.equal(lin.weight.grad, ref.weight.grad)

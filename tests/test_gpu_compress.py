@@ -466,3 +466,33 @@ def test_one_workgroup_form_and_its_size_limit(dtype, numel):
     one element more takes the persistent kernel.  Same bytes on either side of the limit."""
     for dist, gamma in (("normal", 0.9), ("relu", 0.3), ("gelu", 0.75)):
         run_and_compare(activation((numel,), dist, 11 + numel % 13, dtype), gamma, "small")
+
+
+@pytest.mark.parametrize("dtype,numel,mode", [("bf16", 3000017, 0), ("bf16", 300003, 0), ("f32", 300003, 0), ("bf16", 300003, 1),
+                                              ("f32", 20000, 0)])
+def test_nothing_is_written_outside_the_workspace_and_the_outputs(dtype, numel, mode):
+    """Canaries: the select's workspace and both outputs sit inside poisoned buffers of exactly the advertised size."""
+    x = activation((numel,), "gelu", 23, dtype)
+    xd = to_device(x)
+    k = dropit.keep_count(numel, 0.9)
+    guard, pattern = 4096, 0x3C
+
+    def guarded(nbytes):
+        size = (nbytes + 255) // 256 * 256
+        whole = torch.full((guard + size + guard,), pattern, dtype=torch.uint8, device="cuda:0")
+        lo = (-whole.data_ptr()) % 256 + 2048
+        return whole, lo, whole[lo:lo + nbytes]
+
+    w_ws, lo_ws, ws = guarded(dropit.compress_workspace_bytes(numel, xd.dtype))
+    w_v, lo_v, vb = guarded(k * xd.element_size())
+    w_i, lo_i, ib = guarded(k * 4)
+    dropit.set_select_mode(mode)
+    try:
+        vals, idx = dropit.compress(xd, 0.9, vals=vb.view(xd.dtype), idx=ib.view(torch.int32), workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        dropit.set_select_mode(0)
+    for whole, lo, inner in ((w_ws, lo_ws, ws), (w_v, lo_v, vb), (w_i, lo_i, ib)):
+        assert bool((whole[:lo] == pattern).all()) and bool((whole[lo + inner.numel():] == pattern).all())
+    want_v, want_i = oracle.compress(x, k)
+    assert np.array_equal(to_host(idx), want_i) and to_host(vals).tobytes() == want_v.tobytes()

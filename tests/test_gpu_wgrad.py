@@ -487,3 +487,56 @@ def test_weight_grad_in_a_hip_graph(conv):
         g.replay()
         torch.cuda.synchronize()
         assert to_host(dW).tobytes() == want.tobytes(), replay
+
+
+def _guarded(nbytes, dtype, pattern=0xC3, guard=4096):
+    """A tensor of `nbytes` bytes viewed as `dtype`, carved out of the middle of a larger poisoned buffer
+    (256-byte aligned); returns (tensor, check) where check() asserts the guard zones on both sides are intact."""
+    nbytes = max(int(nbytes), 16)
+    size = (nbytes + 255) // 256 * 256
+    whole = torch.full((guard + size + guard,), pattern, dtype=torch.uint8, device="cuda:0")
+    base = (-whole.data_ptr()) % 256
+    lo = base + (guard // 2) // 256 * 256
+    inner = whole[lo:lo + nbytes]
+
+    def check():
+        assert bool((whole[:lo] == pattern).all()), "bytes before the buffer were written"
+        assert bool((whole[lo + nbytes:] == pattern).all()), "bytes after the buffer were written"
+    return inner.view(dtype), check
+
+
+@pytest.mark.parametrize("case", [
+    dict(x=(3000, 520), gamma=0.85, c_out=264, conv=None, dist="normal"),              # FC on the matrix cores: recover + GEMM + slice sum
+    dict(x=(256, 64), gamma=0.9, c_out=128, conv=None, dist="normal"),                 # small FC: one launch
+    dict(x=(640, 40000), gamma=0.9, c_out=8, conv=None, dist="normal"),                # FC, generic path
+    dict(x=(3, 64, 28, 24), gamma=0.8, c_out=40, conv=CONV3, dist="relu"),             # conv row bands
+    dict(x=(32, 256, 7, 7), gamma=0.8, c_out=256, conv=CONV3, dist="relu"),            # conv as one GEMM over im2col rows
+    dict(x=(3, 8, 15, 14), gamma=0.6, c_out=8, conv=(3, 3, 2, 2, 1, 1, 1, 1), dist="relu"),   # general im2col
+])
+def test_nothing_is_written_outside_dW_and_the_workspace(case):
+    """Canaries: dW and the workspace sit inside poisoned buffers exactly as large as the library asks for."""
+    print("wgrad canary", case, flush=True)
+    x = activation(case["x"], case["dist"], 91, "bf16")
+    conv, c_out = case["conv"], case["c_out"]
+    if conv is None:
+        dy_shape = (x.shape[0], c_out)
+        dw_shape = (c_out, x.shape[1])
+    else:
+        kh, kw, sh, sw, ph, pw, dh, dw_ = conv
+        oh = (x.shape[2] + 2 * ph - dh * (kh - 1) - 1) // sh + 1
+        ow = (x.shape[3] + 2 * pw - dw_ * (kw - 1) - 1) // sw + 1
+        dy_shape = (x.shape[0], c_out, oh, ow)
+        dw_shape = (c_out, x.shape[1], kh, kw)
+    dy = gradient(dy_shape, 0.02, 92, "bf16")
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, case["gamma"])
+    need = dropit.weight_grad_workspace_bytes(x.shape, xd.dtype, vals.numel(), c_out, conv)
+    ws, check_ws = _guarded(need, torch.uint8)
+    dwf, check_dw = _guarded(int(np.prod(dw_shape)) * 4, torch.float32)
+    dW = dwf.view(dw_shape)
+    want = dropit.weight_grad(vals, idx, x.shape, dyd, c_out, conv=conv)
+    got = dropit.weight_grad(vals, idx, x.shape, dyd, c_out, conv=conv, dW=dW, workspace=ws)
+    torch.cuda.synchronize()
+    check_ws()
+    check_dw()
+    assert torch.equal(got, want)
