@@ -26,13 +26,26 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
-# HBM bytes per launch of the dominant kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled
-# by what the same counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0); see
-# profiles/fc_dense_select_fused_vitb_fc1_hbm_traffic.txt.  None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("vitb_fc1", "dw"): int((59045.5 * 2.0 + 64512.0) * 1024),       # fc_dense_kernel: 120.9 MB read + 66.1 MB written
-    ("vitb_fc1", "hist"): int((12767.9 * 2.0 + 5976.5) * 1024),      # select_fused_kernel: 26.1 MB read + 6.1 MB written
-}
+def measured_traffic(workload, kernel_prefix):
+    """HBM bytes per launch of `kernel_prefix` on `workload`, from the table of rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE readings in profiles/hbm_traffic.md (each row names the summary file it was read from and the
+    commit it was taken at; readings are scaled by what the same counter reads for a plain 256 MiB copy in the
+    same run).  None for a kernel/workload pair that is not in the table."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 8 or cells[0] != workload or not cells[1].startswith(kernel_prefix):
+            continue
+        try:
+            fetch_kib, fetch_factor, write_kib, write_factor = (float(cells[i]) for i in (2, 3, 4, 5))
+        except ValueError:
+            continue
+        return {"bytes": int((fetch_kib * fetch_factor + write_kib * write_factor) * 1024),
+                "fetch_bytes": int(fetch_kib * fetch_factor * 1024), "write_bytes": int(write_kib * write_factor * 1024),
+                "source": cells[6], "commit": cells[7]}
+    return None
 
 
 def parse_args():
@@ -50,6 +63,9 @@ def parse_args():
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time the vendor library's dense weight gradient (torch.mm / conv2d_weight) on the "
                          "same shapes and inputs, reported as context under 'vendor_gemm'")
+    ap.add_argument("--fc-recover", choices=["dense", "lds"], default="dense",
+                    help="where the recover step of a bf16 fully-connected layer happens: a dense operand in the "
+                         "workspace (default, the faster form) or inside the product, in LDS (dropit_set_fc_recover)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of ONE captured HIP graph of the step (one input copy) instead of eager calls: "
                          "what a launch-bound layer costs once the host's per-call work is out of the loop")
@@ -118,6 +134,7 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     dropit.lib()  # fail loudly if the extension is not built
+    dropit.set_fc_recover(1 if args.fc_recover == "lds" else 0)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = {**WORKLOADS, **EXTRA_WORKLOADS}[args.workload]
@@ -241,19 +258,21 @@ def main():
     n_c = 2
     path = dropit.weight_grad_path(x_shape, xs[0].dtype, k, w.c_out, conv, layout=args.layout)   # which kernels the library runs
     fc_mfma = path == "fc_mfma"
+    fc_fused = path == "fc_fused"                          # token-block starts, pairs regrouped by tile, product, slice sum
     conv_gemm = path in ("conv_gemm", "conv_im2col")      # operand preparation, then the fully-connected GEMM
     conv_mfma = path == "conv_bands"
     conv_padded = conv_mfma and w.x_shape[3] % 8 != 0       # one more kernel: the zero-padded copy of dY
-    mfma = fc_mfma or conv_mfma or conv_gemm
+    mfma = fc_mfma or fc_fused or conv_mfma or conv_gemm
     # marks per call: prep, [pad,] gemm, reduce, end  |  zero+scatter, gemm, end
     fc_small = path == "fc_small"                          # one launch: recover in LDS + fp32 multiply-adds
-    n_g = 5 if conv_padded else 4 if mfma else 2 if fc_small else 3
+    n_g = 5 if (conv_padded or fc_fused) else 4 if mfma else 2 if fc_small else 3
     c_ms = np.maximum(np.array([event_ms(e[:n_c]) for e in ce]) - event_overhead_ms, 0.0)   # [n_meas, n_c-1]
     g_ms = np.maximum(np.array([event_ms(e[:n_g]) for e in ge]) - event_overhead_ms, 0.0)
     c_med = np.median(c_ms, axis=0)
     g_med = np.median(g_ms, axis=0)
-    c_names = ["select_fused"]
+    c_names = ["select"]
     g_names = (["recover", "mfma_gemm", "splitk_reduce"] if fc_mfma else
+               ["token_block_starts", "pairs_by_tile", "mfma_gemm_with_recover", "splitk_reduce"] if fc_fused else
                ["im2col_recover_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if path == "conv_gemm" else
                ["im2col_rows_and_dY_tokens", "mfma_gemm", "splitk_reduce"] if conv_gemm else
                ["row_starts", "pad_dY", "mfma_conv", "partial_reduce"] if conv_padded else
@@ -265,12 +284,17 @@ def main():
     esz = 2 if bf16 else 4
     compress_bytes = w.numel * esz + k * (esz + 4)           # read x once + write k (value, index) pairs
     flops = float(w.dense_flops)
-    main_idx = 2 if conv_padded else 0 if fc_small else 1
+    main_idx = 2 if (conv_padded or fc_fused) else 0 if fc_small else 1
     main_ms = float(np.mean(g_ms[:, main_idx]))
     dw_tflops_kernel = flops / (main_ms * 1e-3) * 1e-12
     hist_ms = float(np.mean(c_ms[:, 0]))
     hist_gbps = compress_bytes / (hist_ms * 1e-3) * 1e-9
 
+    main_kernel = ("fc_dense_kernel" if (fc_mfma or conv_gemm or fc_fused) else "conv3x3_mfma_kernel" if conv_mfma else
+                   "fc_small_kernel" if fc_small else "fc_fma_kernel")
+    select_kernel = "select_small_kernel" if w.numel // (8 if bf16 else 4) <= 8 * 1024 else "select_fused_kernel"
+    dw_traffic = measured_traffic(w.name + ("+lds" if fc_fused else ""), main_kernel)
+    sel_traffic = measured_traffic(w.name, select_kernel)
     out = {
         "metric": "min-k compress GB/s (% HBM peak) + sparse-input dW TFLOP/s (% MFMA peak)",
         "value": flops / (ms_per_step * 1e-3) * 1e-12,
@@ -285,7 +309,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": "%s: x %s %s gamma=%.2f, dY %s, dW %s fp32%s" % (
-            w.name + (" channels-last" if nhwc else ""), w.dtype, list(x_shape), w.gamma, list(dyh.shape), list(dw_shape),
+            w.name + (" channels-last" if nhwc else "") + (" recover-in-LDS" if fc_fused else ""), w.dtype, list(x_shape), w.gamma, list(dyh.shape), list(dw_shape),
             " (cold: %d rotating input copies, %.0f MB)" % (copies, copies * (xh.nbytes + dyh.nbytes) / 1e6)
             if copies > 1 else " (inputs warm in Infinity Cache%s)" % (", replays of one captured graph" if args.graph else ""))},
         "warm": {"ms_per_step": warm_ms_per_step, "value": flops / (warm_ms_per_step * 1e-3) * 1e-12,
@@ -302,24 +326,25 @@ def main():
             "dw_kernels_ms": dict(zip(g_names, [float(v) for v in g_med])),
         },
         "roofline": {
-            "kernel": "fc_dense_kernel" if (fc_mfma or conv_gemm) else "conv3x3_mfma_kernel" if conv_mfma else
-                      "fc_small_kernel" if fc_small else "fma kernel",
+            "kernel": main_kernel,
             "bound": "mfma" if mfma else "alu",
             "achieved": dw_tflops_kernel,
             "peak": MFMA_BF16_PEAK_TFLOPS if mfma else 157.3,
             "unit": "TFLOP/s",
             "frac": dw_tflops_kernel / (MFMA_BF16_PEAK_TFLOPS if mfma else 157.3),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "dw")),
+            "traffic": (dw_traffic or {}).get("bytes"),
+            "traffic_source": dw_traffic,
             "avg_kernel_ms": main_ms,
         },
         "roofline_compress": {
-            "kernel": "select_fused_kernel (key range from a sample or digit histograms, exact count, ordered compaction)",
+            "kernel": select_kernel,
             "bound": "hbm",
             "achieved": hist_gbps,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": hist_gbps / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "hist")),
+            "traffic": (sel_traffic or {}).get("bytes"),
+            "traffic_source": sel_traffic,
             "avg_kernel_ms": hist_ms,
         },
     }

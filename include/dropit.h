@@ -161,7 +161,8 @@ typedef DROPIT_ENUM(dropit_wgrad_path) {
     DROPIT_PATH_CONV_GEMM = 3,      /* 3x3/s1/p1 bf16, small planes with many channels: explicit im2col rows + the FC GEMM */
     DROPIT_PATH_FMA = 4,            /* exact fp32 multiply-add kernels (fp32 inputs, odd shapes) */
     DROPIT_PATH_CONV_IM2COL = 5,    /* bf16, any geometry and either layout: zero-filled im2col rows written from the pairs + the FC GEMM */
-    DROPIT_PATH_FC_SMALL = 6        /* fully-connected layers of at most 16384 input elements: recover in LDS and exact fp32 multiply-adds, one launch */
+    DROPIT_PATH_FC_SMALL = 6,       /* fully-connected layers of at most 16384 input elements: recover in LDS and exact fp32 multiply-adds, one launch */
+    DROPIT_PATH_FC_FUSED = 7        /* the FC_MFMA product with the recover step inside it (only after dropit_set_fc_recover(1)) */
 } dropit_wgrad_path;
 dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,
                                           int64_t c_out, const dropit_conv2d *conv);
@@ -303,6 +304,21 @@ dropit_status dropit_weight_grad_mask(const void *vals, const uint32_t *mask, co
  * Returns DROPIT_EINVAL for any other mode.
  */
 dropit_status dropit_set_select_mode(int mode);
+
+/*
+ * Where the recover step R(a^) of a bf16 fully-connected layer happens (Sec. 3.2; Fig. 1: the zero-filled
+ * tensor is only ever an operand of the weight gradient).  Per host thread, like the select mode.
+ *   0  (default) R(a^) is written as a dense bf16 operand into the workspace and the product reads it
+ *      (DROPIT_PATH_FC_MFMA).  The faster form on MI355X by 10 - 35 us per layer at the ViT shapes; the
+ *      workspace holds one tensor the size of the layer's input for the duration of the call.
+ *   1  R(a^) is built tile by tile in LDS inside the product and never exists in device memory
+ *      (DROPIT_PATH_FC_FUSED): the workspace holds one 4-byte word per kept pair instead of the dense tensor
+ *      (0.2 of its bytes at gamma = 0.9).  Same dW, bit for bit.  Shapes the form does not cover (c_out <= 128,
+ *      C_in > 32768) keep taking form 0; query with dropit_weight_grad_path.
+ * dropit_weight_grad_workspace_bytes / _path answer for the form set on the calling thread.
+ * Returns DROPIT_EINVAL for any other value.
+ */
+dropit_status dropit_set_fc_recover(int form);
 
 /*
  * Measurement aid (not part of the method): per-kernel timing marks.

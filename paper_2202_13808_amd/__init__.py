@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     keep_count,
     lib,
     lib_path,
+    set_fc_recover,
     set_select_mode,
     trace_events,
     weight_grad,

@@ -91,6 +91,8 @@ def lib() -> ctypes.CDLL:
         L.dropit_weight_grad_nhwc.argtypes = [vp, vp, i64, p64, i32, vp, i64, pconv, vp, vp, sz, vp]
         L.dropit_set_select_mode.restype = i32
         L.dropit_set_select_mode.argtypes = [i32]
+        L.dropit_set_fc_recover.restype = i32
+        L.dropit_set_fc_recover.argtypes = [i32]
         L.dropit_trace_events.restype = None
         L.dropit_trace_events.argtypes = [ctypes.POINTER(vp), i32]
         L.dropit_weight_grad.restype = i32
@@ -265,7 +267,8 @@ def weight_grad_workspace_bytes(x_shape: Sequence[int], dtype: torch.dtype, k: i
         _shape_array(x_shape), len(x_shape), _dtype_code(dtype), int(k), int(c_out), pc))
 
 
-WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma", 5: "conv_im2col", 6: "fc_small"}
+WGRAD_PATHS = {0: "none", 1: "fc_mfma", 2: "conv_bands", 3: "conv_gemm", 4: "fma", 5: "conv_im2col", 6: "fc_small",
+               7: "fc_fused"}
 
 
 def weight_grad_path(x_shape: Sequence[int], dtype: torch.dtype, k: int, c_out: int, conv=None,
@@ -430,6 +433,12 @@ def set_select_mode(mode: int) -> None:
     kernels, 2 = the persistent kernel through a cooperative launch, 3 = test hook that forces
     the persistent kernel's serial redo path."""
     _check(lib().dropit_set_select_mode(int(mode)))
+
+
+def set_fc_recover(form: int) -> None:
+    """dropit_set_fc_recover: 0 = the recover step writes a dense operand into the workspace (default),
+    1 = it happens inside the product, in LDS (smaller workspace, same dW, slower)."""
+    _check(lib().dropit_set_fc_recover(int(form)))
 
 
 def trace_events(events: Optional[Sequence[torch.cuda.Event]]) -> None:

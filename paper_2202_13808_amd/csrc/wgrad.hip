@@ -368,11 +368,23 @@ static bool fc_small(const Problem &p)
     return !p.conv && p.numel <= SMALL_NUMEL && p.ntok <= SMALL_TOKENS && p.cin % 4 == 0 && p.cout <= 4096;
 }
 
+// 0: recover into a dense operand in the workspace, then the product; 1: recover inside the product where that
+// form exists (see dropit_set_fc_recover).  Per host thread.
+static int &fc_recover_form()
+{
+    static thread_local int form = 0;
+    return form;
+}
+
 static dropit_wgrad_path choose_path(const Problem &p, dropit_dtype dt, int64_t k)
 {
     if (fc_small(p)) return DROPIT_PATH_FC_SMALL;
     if (dt != DROPIT_BF16) return DROPIT_PATH_FMA;
-    if (!p.conv) return use_fc_dense(FcProblem{p.ntok, p.cin, p.cout, k}) ? DROPIT_PATH_FC_MFMA : DROPIT_PATH_FMA;
+    if (!p.conv) {
+        const FcProblem fp = {p.ntok, p.cin, p.cout, k};
+        if (!use_fc_dense(fp)) return DROPIT_PATH_FMA;
+        return fc_recover_form() == 1 && k >= 1 && fc_fused_supported(fp) ? DROPIT_PATH_FC_FUSED : DROPIT_PATH_FC_MFMA;
+    }
     if (p.is_3x3_s1_p1 && !p.nhwc) {
         const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
         bool gemm = conv_gemm_preferred(cp);
@@ -389,6 +401,7 @@ static size_t workspace_need(const Problem &p, dropit_dtype dt, int64_t k)
     const ConvProblem cp = {p.N, p.C, p.H, p.W, p.cout, k};
     switch (choose_path(p, dt, k)) {
     case DROPIT_PATH_FC_MFMA: return fc_dense_plan(FcProblem{p.ntok, p.cin, p.cout, k}).total();
+    case DROPIT_PATH_FC_FUSED: return fc_dense_plan(FcProblem{p.ntok, p.cin, p.cout, k}, true).total();
     case DROPIT_PATH_CONV_GEMM: return conv_gemm_plan(cp).total();
     case DROPIT_PATH_CONV_BANDS: return conv_mfma_plan(cp).total();
     case DROPIT_PATH_CONV_IM2COL: return conv_im2col_plan(general_of(p, k)).total();
@@ -419,6 +432,10 @@ static dropit_status run(const Problem &p, const void *vals, const int32_t *idx,
     case DROPIT_PATH_FC_MFMA: {
         const FcProblem fp = {p.ntok, p.cin, p.cout, k};
         return fc_dense_run(fp, fc_dense_plan(fp), vals, idx, dY, dW, ws, stream);
+    }
+    case DROPIT_PATH_FC_FUSED: {
+        const FcProblem fp = {p.ntok, p.cin, p.cout, k};
+        return fc_fused_run(fp, fc_dense_plan(fp, true), vals, idx, dY, dW, ws, stream);
     }
     case DROPIT_PATH_CONV_GEMM: return conv_gemm_run(cp, conv_gemm_plan(cp), vals, idx, dY, dW, ws, stream);
     case DROPIT_PATH_CONV_BANDS: return conv_mfma_run(cp, conv_mfma_plan(cp), vals, idx, dY, dW, ws, stream);
@@ -460,6 +477,13 @@ static dropit_status run(const Problem &p, const void *vals, const int32_t *idx,
     }
     if (dt == DROPIT_BF16) return run_generic<uint16_t>(p, vals, idx, k, dY, dW, ws, need, stream);
     return run_generic<uint32_t>(p, vals, idx, k, dY, dW, ws, need, stream);
+}
+
+extern "C" dropit_status dropit_set_fc_recover(int form)
+{
+    if (form != 0 && form != 1) return DROPIT_EINVAL;
+    fc_recover_form() = form;
+    return DROPIT_OK;
 }
 
 extern "C" dropit_wgrad_path dropit_weight_grad_path(const int64_t *x_shape, int ndim, dropit_dtype dt, int64_t k,

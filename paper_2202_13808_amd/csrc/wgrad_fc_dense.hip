@@ -345,13 +345,31 @@ __device__ inline void static_for(F &&f)
     }
 }
 
-template <typename C>
+// FUSED: the recover step R(a^) happens inside the product.  The B operand is not a dense matrix in memory:
+// a prep kernel (fc_bucket_kernel) has put the pairs of every (token block, column block) tile next to each
+// other as words  value << 16 | place in the tile's LDS rows;  the workgroup fetches a tile's
+// words straight into an LDS staging area four steps ahead (direct loads, like the A tiles), zero-fills the
+// tile's LDS rows three steps ahead, and places the words (one 16-bit LDS store each, at the same swizzled
+// addresses a direct load would have filled) two steps ahead -- each behind a workgroup barrier of its own,
+// and all of it tucked in front of the MFMAs of a sub-step.  The zero-filled tensor exists only as these rows.
+constexpr int FUSE_STAGE_WORDS = 1024;            // words of a tile staged per step (more than that: a slow path)
+constexpr int FUSE_SLOTS = 4;                     // staging slots: tile t uses slot t % 4 (tiles s + 2 .. s + 4 are in flight at step s)
+constexpr int FUSE_LDS_BYTES = FUSE_SLOTS * FUSE_STAGE_WORDS * 4 + 512 * 4;     // + a spare word per thread
+
+template <typename C, bool FUSED>
 __global__ void __launch_bounds__(C::NTHREADS) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
 fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd, int64_t ntok, int M, int N,
                 int pitch, int nb_count, int mb_count, int nkb, int splits,
-                float *__restrict__ out /* dW or partials [splits][M][N] */)
+                float *__restrict__ out /* dW or partials [splits][M][N] */,
+                const uint32_t *__restrict__ packed /* FUSED: the tiles' words */,
+                const uint32_t *__restrict__ tile_ptr /* FUSED: [nkb * nb_count + 1] first word of each tile */,
+                uint32_t kpairs)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK;
+    static_assert(!FUSED || (C::NTHREADS == 512 && BN == 256 && BK == 32 && C::EARLY && C::STAGES == 4),
+                  "the fused form is laid out for 512 threads, 32 x 256 B tiles, four stages, early reads");
+    constexpr int PK_LOADS = FUSED ? FUSE_STAGE_WORDS / C::NTHREADS : 0;      // staging loads (64 words each) per wavefront per step
+    constexpr int STEP_LOADS = FUSED ? C::A_LOADS + PK_LOADS : C::LOADS;      // global loads a wavefront issues per step
     extern __shared__ __attribute__((aligned(1024))) char lds[];     // [STAGES][A tile | B tile]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -408,8 +426,12 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         const int r = o / C::ROW_B;
         const int b = (o % C::ROW_B) ^ ((r & 3) << 6);
         const int n = min(n0 + b / 2, pitch - 8);
-        b_off[i] = uint32_t(r * pitch + n) * 2u;
+        b_off[i] = FUSED ? 0u : uint32_t(r * pitch + n) * 2u;
     }
+    // FUSED: first word of the tile whose words are being staged this step (tile s + 4), and the staging slot
+    char *stg = lds + C::LDS_BYTES;                    // [FUSE_SLOTS][FUSE_STAGE_WORDS] words behind the stages
+    uint32_t dma_start = 0;
+    int dma_slot = 0;
     // load number q (0 .. LOADS-1) of a step: the A loads first, then the B loads
     auto issue_load = [&](auto q_, int stage, int kb) {
         constexpr int q = decltype(q_)::value;
@@ -418,6 +440,14 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             char *sa = lds + stage * C::STAGE_BYTES + wave * (C::A_LOADS * 1024);
             __builtin_amdgcn_global_load_lds(DROPIT_GPTR(abase + (kb == kb_tail ? a_off_tail[q] : a_off[q])),
                                              DROPIT_LPTR(sa + q * 1024), 16, 0, 0);
+        } else if constexpr (FUSED) {
+            // staging load i of the step: words [i * 512 + wave * 64, + 64) of the tile, one per lane (a direct
+            // 4-byte load lands at the wave-uniform LDS base + lane * 4); clamped, unconditional
+            constexpr int i = q - C::A_LOADS;
+            const uint32_t w = uint32_t(i * C::NTHREADS + wave * 64 + lane);
+            __builtin_amdgcn_global_load_lds(DROPIT_GPTR(packed + min(dma_start + w, kpairs - 1)),
+                                             DROPIT_LPTR(stg + dma_slot * (FUSE_STAGE_WORDS * 4) + (i * C::NTHREADS + wave * 64) * 4),
+                                             4, 0, 0);
         } else {
             constexpr int i = q - C::A_LOADS;
             const char *bbase = reinterpret_cast<const char *>(xd) + int64_t(kb) * BK * pitch * 2;
@@ -426,8 +456,56 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         }
     };
     auto issue_loads = [&](int stage, int kb) {
-        static_for<0, C::LOADS>([&](auto q_) { issue_load(q_, stage, kb); });
+        static_for<0, STEP_LOADS>([&](auto q_) { issue_load(q_, stage, kb); });
     };
+    // ---- FUSED: the B tile of a step is zero-filled and the staged words placed, by hand-written LDS accesses
+    // (the compiler would put vmcnt(0) in front of LDS accesses it knows about, see below) ----
+    const uint32_t lds_base0 = uint32_t(size_t(DROPIT_LPTR(lds)));
+    auto zero_b_half = [&](int stage, int half) {      // 16 KB: 2 x 16 bytes per thread
+        const uint32_t a = lds_base0 + stage * C::STAGE_BYTES + C::A_BYTES + half * (C::NTHREADS * 16) + threadIdx.x * 16;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(z) : "memory");
+    };
+    auto zero_b = [&](int stage) {
+        zero_b_half(stage, 0);
+        zero_b_half(stage, 1);
+    };
+    uint32_t staged_w[FUSE_STAGE_WORDS / C::NTHREADS];             // this thread's words of the tile being placed
+    auto read_staged = [&](int slot) {
+        const uint32_t a = lds_base0 + C::LDS_BYTES + slot * (FUSE_STAGE_WORDS * 4) + threadIdx.x * 4;
+#pragma unroll
+        for (int i = 0; i < FUSE_STAGE_WORDS / C::NTHREADS; ++i)
+            asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(staged_w[i]) : "v"(a), "n"(i * C::NTHREADS * 4) : "memory");
+    };
+    // a word is  value << 16 | element offset in the tile's LDS rows  (row * 256 + swizzled column: 13 bits, the rest of the low half is zero)
+    auto place_word = [&](uint32_t w, uint32_t b_base) {
+        const uint32_t a = b_base + ((w & 0x1fffu) << 1);
+        const uint32_t v = w >> 16;
+        asm volatile("ds_write_b16 %0, %1" ::"v"(a), "v"(v) : "memory");
+    };
+    // staged word i of this thread, or -- past the tile's count -- a store to a spare location of the thread's own
+    const uint32_t spare = lds_base0 + C::LDS_BYTES + FUSE_SLOTS * FUSE_STAGE_WORDS * 4 + threadIdx.x * 4;
+    auto place_staged_one = [&](auto i_, int stage, uint32_t count) {
+        constexpr int i = decltype(i_)::value;
+        const uint32_t b_base = lds_base0 + stage * C::STAGE_BYTES + C::A_BYTES;
+        asm volatile("" : "+v"(staged_w[i]));
+        const bool valid = uint32_t(i * C::NTHREADS) + threadIdx.x < count;
+        const uint32_t a = valid ? b_base + ((staged_w[i] & 0x1fffu) << 1) : spare;
+        const uint32_t v = staged_w[i] >> 16;
+        asm volatile("ds_write_b16 %0, %1" ::"v"(a), "v"(v) : "memory");
+    };
+    auto place_staged = [&](int stage, uint32_t count) {          // after the lgkm wait that follows read_staged
+        static_for<0, FUSE_STAGE_WORDS / C::NTHREADS>([&](auto i_) { place_staged_one(i_, stage, count); });
+    };
+    // a tile of more words than the staging slot holds (values that bunch up): the rest straight from memory
+    auto place_overflow = [&](int stage, uint32_t start, uint32_t count) {
+        const uint32_t b_base = lds_base0 + stage * C::STAGE_BYTES + C::A_BYTES;
+        for (uint32_t w = FUSE_STAGE_WORDS + threadIdx.x; w < count; w += C::NTHREADS) {
+            const uint32_t word = packed[min(start + w, kpairs - 1)];
+            place_word(word, b_base);
+        }
+    };
+    (void)zero_b; (void)read_staged; (void)place_staged; (void)place_overflow; (void)stg; (void)place_staged_one;
 
     // ---- LDS -> MFMA fragments -----------------------------------------------------
     // A 32x32x16 operand wants, in lane l, row (l % 32) and k = 8 * (l / 32) + 0..7.  One
@@ -458,7 +536,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     constexpr int READS_PER_MFMA = (SET_READS + NM / 2 - 1) / (NM / 2);   // all reads go out with the first half
     static_assert(KK % 2 == 0, "fragment sets alternate per sub-step and must line up across token blocks");
     static_assert(NM >= 2, "the reads of a sub-step go out with the first half of the previous one's MFMAs");
-    const uint32_t lds_base = uint32_t(size_t(DROPIT_LPTR(lds)));
+    const uint32_t lds_base = lds_base0;
     s16x4 fa[2][C::FM][2], fb[2][C::FN][2];            // two fragment sets: one multiplying, one being read
     // read number r (0 .. SET_READS-1) of sub-step kk of the stage at `stage_base`, into fragment set `set`
     auto issue_read = [&](auto set_, auto kk_, auto r_, uint32_t stage_base) {
@@ -477,11 +555,26 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     // wavefronts of a SIMD run in lockstep between barriers, so anything not tucked between MFMAs
     // would leave the matrix pipe idle in both at once; and a burst of loads would wait for the
     // address unit, which all eight wavefronts feed at the same time.
-    static_assert(C::LOADS <= KK * NM, "at most one global load rides behind each MFMA");
+    static_assert(STEP_LOADS <= KK * NM, "at most one global load rides behind each MFMA");
+    // FUSED, per step s (fz_*: set at the top of the step): sub-step 0 zero-fills the B rows of tile s + 3 and reads
+    // this thread's staged words of tile s + 2; sub-step 1 places them.
+    int fz_zero_stage = 0, fz_place_stage = 0, fz_place_slot = 0, fz_decode_t = 0;
+    uint32_t fz_place_start = 0, fz_place_count = 0, fz_raw_lo = 0, fz_raw_hi = 0, fz_next_start = 0, fz_next_count = 0;
+    const int kb_begin_f = kb_begin, steps_f = steps;
+    auto tile_decode = [&](int t, uint32_t raw_lo, uint32_t raw_hi, uint32_t &start, uint32_t &count) {
+        start = min(raw_lo, kpairs);
+        const uint32_t end = min(raw_hi, kpairs);
+        count = (t < steps_f && end > start) ? end - start : 0u;     // a malformed table places nothing
+    };
+    (void)kb_begin_f; (void)tile_decode;
     auto substep = [&](auto kk_, auto next_kk_, auto read_next_, uint32_t next_base, int load_stage, int load_kb) {
         constexpr int kk = decltype(kk_)::value, set = kk % 2;
         constexpr bool read_next = decltype(read_next_)::value;
         lgkm_wait<0>();                                // the reads of this set were issued one sub-step ago
+        if constexpr (FUSED && kk == 1) {
+            tile_decode(fz_decode_t, fz_raw_lo, fz_raw_hi, fz_next_start, fz_next_count);   // (fetched at the top of the step)
+            if (fz_place_count > uint32_t(FUSE_STAGE_WORDS)) place_overflow(fz_place_stage, fz_place_start, fz_place_count);
+        }
         bf16x8 af[C::FM], bfv[C::FN];
 #pragma unroll
         for (int i = 0; i < C::FM; ++i) {
@@ -500,10 +593,18 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
                 if constexpr (read_next && decltype(r_)::value < SET_READS)
                     issue_read(std::integral_constant<int, 1 - set>{}, next_kk_, r_, next_base);
             });
+            // FUSED: the second half of the MFMAs, which has no reads behind it, carries the zero fill and the staged
+            // reads (sub-step 0) and the placement (sub-step 1)
+            if constexpr (FUSED && kk == 0) {
+                if constexpr (m == NM / 2 || m == NM / 2 + 1) zero_b_half(fz_zero_stage, m - NM / 2);
+                if constexpr (m == NM / 2 + 2) read_staged(fz_place_slot);
+            }
+            if constexpr (FUSED && kk == 1 && m >= NM / 2 && m < NM / 2 + FUSE_STAGE_WORDS / C::NTHREADS)
+                place_staged_one(std::integral_constant<int, m - NM / 2>{}, fz_place_stage, fz_place_count);
             constexpr int g = kk * NM + m;             // MFMA number within the step
-            static_for<0, C::LOADS>([&](auto q_) {     // load q rides behind MFMA (q + 1) * MFMAs / LOADS - 1
+            static_for<0, STEP_LOADS>([&](auto q_) {   // load q rides behind MFMA (q + 1) * MFMAs / LOADS - 1
                 constexpr int q = decltype(q_)::value;
-                if constexpr (g == (q + 1) * KK * NM / C::LOADS - 1) issue_load(q_, load_stage, load_kb);
+                if constexpr (g == (q + 1) * KK * NM / STEP_LOADS - 1) issue_load(q_, load_stage, load_kb);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -526,20 +627,80 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         constexpr int AHEAD = C::EARLY ? 1 : 0;        // how many steps before its own a stage must be complete
         static_assert(D >= 1 + AHEAD, "stages: one being multiplied, one per step of load latency, one more if read early");
         const int kb_last = kb_end - 1;
+        // FUSED: where tile t of the slice starts among the words, and how many it has (t past the slice: none)
+        // (the table entries are wavefront-uniform: scalar loads, fetched a step before they are decoded)
+        auto tile_fetch = [&](int t, uint32_t &raw_lo, uint32_t &raw_hi) {
+            const int64_t b = int64_t(kb_begin + min(t, steps - 1)) * nb_count + nb;
+            raw_lo = tile_ptr[b];
+            raw_hi = tile_ptr[b + 1];
+        };
+        uint32_t r2_start = 0, r2_count = 0, r3_start = 0, r3_count = 0, r4_start = 0, r4_count = 0, r5_start = 0, r5_count = 0;
+        if constexpr (FUSED) {
+            // before the first step: tiles 0 .. 3 staged, stages 0 .. 2 zero-filled, tiles 0 and 1 placed -- the table
+            // entries, the A tiles of the first three steps and the staged words are all requested before the first wait
+            uint32_t lo[6], hi[6], st[6], ct[6];
 #pragma unroll
-        for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
+            for (int t = 0; t < 6; ++t) tile_fetch(t, lo[t], hi[t]);
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                static_for<0, C::A_LOADS>([&](auto q_) { issue_load(q_, d, min(kb_begin + d, kb_last)); });
+#pragma unroll
+            for (int t = 0; t < 6; ++t) tile_decode(t, lo[t], hi[t], st[t], ct[t]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                dma_start = st[t];
+                dma_slot = t;
+                static_for<C::A_LOADS, STEP_LOADS>([&](auto q_) { issue_load(q_, 0, 0); });
+            }
+            zero_b(0);
+            zero_b(1);
+            zero_b(2);
+            wait_loads<0>();
+            lgkm_wait<0>();
+            workgroup_barrier();
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                read_staged(t);
+                lgkm_wait<0>();
+                place_staged(t, ct[t]);
+                if (ct[t] > uint32_t(FUSE_STAGE_WORDS)) place_overflow(t, st[t], ct[t]);
+            }
+            lgkm_wait<0>();
+            r2_start = st[2]; r2_count = ct[2];
+            r3_start = st[3]; r3_count = ct[3];
+            r4_start = st[4]; r4_count = ct[4];
+            r5_start = st[5]; r5_count = ct[5];
+        } else {
+#pragma unroll
+            for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
+        }
         if constexpr (C::EARLY) {
-            wait_loads<(D - 1) * C::LOADS>();
+            if constexpr (FUSED) wait_loads<0>();
+            else wait_loads<(D - 1) * C::LOADS>();
             workgroup_barrier();
             static_for<0, SET_READS>([&](auto r_) {
                 issue_read(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, r_, lds_base);
             });
         }
         int stage = 0, fill = D;                       // s % STAGES and (s + D) % STAGES
+        int slot2 = 2 % FUSE_SLOTS, slot4 = 4 % FUSE_SLOTS;        // staging slots of tiles s + 2 and s + 4
+        static_assert(FUSE_SLOTS == 4, "the prologue stages tiles 0 .. 3 at once");
         for (int s = 0; s < steps; ++s) {
             const int next = stage + 1 == C::STAGES ? 0 : stage + 1;
-            wait_loads<(D - 1 - AHEAD) * C::LOADS>();
+            wait_loads<(D - 1 - AHEAD) * STEP_LOADS>();
+            if constexpr (FUSED) lgkm_wait<0>();           // this wavefront's zero fill and placed words are in LDS
             workgroup_barrier();
+            if constexpr (FUSED) {
+                tile_fetch(s + 6, fz_raw_lo, fz_raw_hi);
+                fz_decode_t = s + 6;
+                fz_zero_stage = (stage + 3) % C::STAGES;
+                fz_place_stage = (stage + 2) % C::STAGES;
+                fz_place_slot = slot2;
+                fz_place_start = r2_start;
+                fz_place_count = r2_count;
+                dma_start = r4_start;
+                dma_slot = slot4;
+            }
             const uint32_t cur_base = lds_base + stage * C::STAGE_BYTES;
             const uint32_t next_base = lds_base + next * C::STAGE_BYTES;
             const int load_kb = min(kb_begin + s + D, kb_last);
@@ -557,6 +718,14 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             });
             stage = next;
             fill = fill + 1 == C::STAGES ? 0 : fill + 1;
+            if constexpr (FUSED) {
+                slot2 = slot2 + 1 == FUSE_SLOTS ? 0 : slot2 + 1;
+                slot4 = slot4 + 1 == FUSE_SLOTS ? 0 : slot4 + 1;
+                r2_start = r3_start; r2_count = r3_count;
+                r3_start = r4_start; r3_count = r4_count;
+                r4_start = r5_start; r4_count = r5_count;
+                r5_start = fz_next_start; r5_count = fz_next_count;
+            }
         }
         wait_loads<0>();                               // nothing may still be writing LDS
         lgkm_wait<0>();                                // or registers when the wavefront goes on
@@ -679,6 +848,104 @@ splitk_sum_wide_kernel(const f32x4 *__restrict__ partial, int splits, int M, int
     }
 }
 
+// Prep of the in-LDS form: the pairs of token block kb (pairs [kb_ptr[kb], kb_ptr[kb + 1]), in index order, that
+// is by row and then by column) are regrouped by column block of 256 as the words the product consumes, and the
+// table of where each (token block, column block) tile starts is written.  In index order the pairs of one
+// (row, column block) are a run; the regrouping moves whole runs: run (r, b) goes behind the runs (r' < r, b) of
+// its column block, which go behind all of the column blocks before b.  Run starts are found like row starts
+// (every pair is compared with its predecessor), so no counter is contended and the order of the words is fixed.
+// One workgroup per token block.
+constexpr int BUCKET_THREADS = 512;
+constexpr int BUCKET_MAX_NB = RECOVER_ELEMS_MAX / 256;
+__global__ void __launch_bounds__(BUCKET_THREADS)
+fc_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ idx, int64_t k, uint32_t cin,
+                 int nb_count, int nkb, const uint32_t *__restrict__ kb_ptr, uint32_t *__restrict__ packed,
+                 uint32_t *__restrict__ tile_ptr)
+{
+    extern __shared__ uint32_t bucket_lds[];
+    const int runs = 32 * nb_count;
+    uint32_t *run_in = bucket_lds;                     // [runs + 1] first pair of run (r, b), key r * nb_count + b
+    uint32_t *run_out = bucket_lds + runs + 1;         // [runs]     where its first word goes
+    uint32_t *total = run_out + runs;                  // [nb_count] pairs of the column block, then its first word
+    const int kb = blockIdx.x;
+    const uint32_t lo = kb_ptr[kb], hi = kb_ptr[kb + 1];
+    const uint32_t first = uint32_t(kb) * 32u * cin;      // flat index of the block's first element (below 2^31)
+    const float inv = 1.0f / float(cin);
+    // row and column of an element of the block: rel < 32 * cin, so the quotient estimate is off by one at most
+    auto split = [&](uint32_t rel, uint32_t &r, uint32_t &col) {
+        r = min(uint32_t(float(rel) * inv), 31u);
+        int32_t c = int32_t(rel - r * cin);
+        if (c < 0) { r -= 1; c += int32_t(cin); }
+        if (c >= int32_t(cin)) { r += 1; c -= int32_t(cin); }
+        r &= 31u;
+        col = uint32_t(c);
+    };
+    auto key_of = [&](uint32_t flat) {
+        uint32_t r, col;
+        split(flat - first, r, col);
+        return int(r) * nb_count + int(min(col >> 8, uint32_t(nb_count - 1)));
+    };
+    constexpr int U = 4;                               // pairs per thread in flight: all their loads go out first
+    for (uint32_t j0 = lo + threadIdx.x; j0 <= hi; j0 += U * BUCKET_THREADS) {
+        uint32_t cur[U], prev[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t j = j0 + u * BUCKET_THREADS;
+            cur[u] = j < hi ? uint32_t(idx[j]) : first;
+            prev[u] = j > lo && j <= hi ? uint32_t(idx[j - 1]) : first;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t j = j0 + u * BUCKET_THREADS;
+            if (j > hi) break;
+            const int before = j == lo ? -1 : key_of(prev[u]);
+            const int here = j == hi ? runs : key_of(cur[u]);
+            for (int q = before + 1; q <= here; ++q) run_in[q] = j;
+        }
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < nb_count; b += BUCKET_THREADS) {
+        uint32_t acc = 0;
+        for (int r = 0; r < 32; ++r) {
+            run_out[r * nb_count + b] = acc;
+            acc += run_in[r * nb_count + b + 1] - run_in[r * nb_count + b];
+        }
+        total[b] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = lo;
+        for (int b = 0; b < nb_count; ++b) {
+            const uint32_t n = total[b];
+            total[b] = run;
+            tile_ptr[int64_t(kb) * nb_count + b] = run;
+            run += n;
+        }
+        if (kb == nkb - 1) tile_ptr[int64_t(nkb) * nb_count] = uint32_t(k);
+    }
+    __syncthreads();
+    for (uint32_t j0 = lo + threadIdx.x; j0 < hi; j0 += U * BUCKET_THREADS) {
+        uint32_t cur[U], val[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t j = j0 + u * BUCKET_THREADS;
+            cur[u] = j < hi ? uint32_t(idx[j]) : first;
+            val[u] = j < hi ? uint32_t(vals[j]) : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t j = j0 + u * BUCKET_THREADS;
+            if (j >= hi) break;
+            uint32_t r, col;
+            split(cur[u] - first, r, col);
+            const int b = int(min(col >> 8, uint32_t(nb_count - 1)));
+            const int key = int(r) * nb_count + b;
+            const uint32_t at = min(max(total[b] + run_out[key] + (j - run_in[key]), lo), hi - 1);   // (inside the block whatever idx holds)
+            packed[at] = val[u] << 16 | r << 8 | ((col & 255u) ^ ((r & 3u) << 5));
+        }
+    }
+}
+
 #ifndef DROPIT_GEMM_CFG
 #define DROPIT_GEMM_CFG 256, 256, 32, 4, 2, 4, 2, 1
 #endif
@@ -691,6 +958,7 @@ splitk_sum_wide_kernel(const f32x4 *__restrict__ partial, int splits, int M, int
 using Cfg = GemmCfg<DROPIT_GEMM_CFG>;
 using CfgNarrow = GemmCfg<DROPIT_GEMM_CFG_NARROW>;
 static_assert(Cfg::BK == CfgNarrow::BK && Cfg::BN == CfgNarrow::BN, "the recovered operand is laid out once for both");
+static_assert(Cfg::BK == 32 && Cfg::BN == 256, "the words of the in-LDS form address a 32 x 256 tile");
 
 template <typename C>
 int tuned_splits(int tiles, int nkb)
@@ -735,7 +1003,14 @@ bool fc_dense_supported(const FcProblem &p)
            p.cout * Cfg::BK * 2 < (int64_t(1) << 31);
 }
 
-FcDensePlan fc_dense_plan(const FcProblem &p)
+bool fc_fused_supported(const FcProblem &p)
+{
+    // the wide tile only; the column blocks of a token block are counted in LDS; pair positions are 32-bit
+    return fc_dense_supported(p) && !use_narrow(p) && (p.cin + Cfg::BN - 1) / Cfg::BN <= BUCKET_MAX_NB &&
+           p.k < (int64_t(1) << 31);
+}
+
+FcDensePlan fc_dense_plan(const FcProblem &p, bool fused)
 {
     FcDensePlan plan;
     plan.nkb = int((p.ntok + Cfg::BK - 1) / Cfg::BK);
@@ -748,6 +1023,10 @@ FcDensePlan fc_dense_plan(const FcProblem &p)
     plan.rows_per_wg = std::max(1, (plan.pitch <= RECOVER_ELEMS ? RECOVER_ELEMS : RECOVER_ELEMS_MAX) / plan.pitch);
     plan.ntok_pad = int64_t(plan.nkb) * Cfg::BK;
     plan.dense_bytes = round_up(size_t(plan.ntok_pad) * plan.pitch * 2, 256);
+    plan.fused = fused;
+    plan.packed_bytes = round_up(size_t(std::max<int64_t>(p.k, 1)) * 4, 256);
+    plan.table_bytes = round_up((size_t(plan.nkb) * plan.nb_count + 1) * 4, 256);
+    plan.kbptr_bytes = round_up((size_t(plan.nkb) + 1) * 4, 256);
     return plan;
 }
 
@@ -764,23 +1043,26 @@ static bool fc_dense_attributes()
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_recover_rows_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                    RECOVER_ELEMS_MAX * 2 + (RECOVER_ELEMS_MAX / 8 + 1) * 4) == hipSuccess &&
-               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg>),
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess &&
-               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<CfgNarrow>),
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES + FUSE_LDS_BYTES) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<CfgNarrow, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, CfgNarrow::LDS_BYTES) == hipSuccess;
     });
 }
 
-template <typename C>
+template <typename C, bool FUSED = false>
 static dropit_status launch_gemm(const FcProblem &p, const FcDensePlan &plan, const void *dY, const uint16_t *dense,
-                                 float *partial, float *dW, hipStream_t stream)
+                                 float *partial, float *dW, hipStream_t stream, const uint32_t *packed = nullptr,
+                                 const uint32_t *tile_ptr = nullptr)
 {
     const int total = plan.nb_count * plan.mb_count * plan.splits;
     const int grid = (total + 7) / 8 * 8;
     float *out = plan.splits > 1 ? partial : dW;
-    fc_dense_kernel<C><<<grid, C::NTHREADS, C::LDS_BYTES, stream>>>(
+    fc_dense_kernel<C, FUSED><<<grid, C::NTHREADS, C::LDS_BYTES + (FUSED ? FUSE_LDS_BYTES : 0), stream>>>(
         static_cast<const uint16_t *>(dY), dense, p.ntok, int(p.cout), int(p.cin), plan.pitch, plan.nb_count,
-        plan.mb_count, plan.nkb, plan.splits, out);
+        plan.mb_count, plan.nkb, plan.splits, out, packed, tile_ptr, uint32_t(std::max<int64_t>(p.k, 1)));
 
     trace_mark(stream);
     if (plan.splits > 1) {
@@ -813,7 +1095,7 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
     uint16_t *dense = reinterpret_cast<uint16_t *>(ws);
     float *partial = reinterpret_cast<float *>(ws + plan.dense_bytes);
     const int64_t ntok_pad = plan.ntok_pad;
-    if (!fc_dense_attributes()) return DROPIT_EHIP;
+    if (!fc_dense_attributes() || plan.fused) return DROPIT_EHIP;
 
     trace_mark(stream);
     const int recover_grid = int((ntok_pad + plan.rows_per_wg - 1) / plan.rows_per_wg);
@@ -839,6 +1121,25 @@ dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const vo
 
     trace_mark(stream);
     return fc_dense_gemm(p, plan, dY, dense, partial, dW, stream);
+}
+
+dropit_status fc_fused_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
+                           const void *dY, float *dW, char *ws, hipStream_t stream)
+{
+    if (!fc_dense_attributes() || !plan.fused || plan.narrow || p.k < 1) return DROPIT_EHIP;
+    uint32_t *packed = reinterpret_cast<uint32_t *>(ws);
+    uint32_t *tile_ptr = reinterpret_cast<uint32_t *>(ws + plan.packed_bytes);
+    uint32_t *kb_ptr = reinterpret_cast<uint32_t *>(ws + plan.packed_bytes + plan.table_bytes);
+    float *partial = reinterpret_cast<float *>(ws + plan.operand_bytes());
+    trace_mark(stream);
+    launch_row_starts(idx, p.k, uint32_t(Cfg::BK * p.cin), plan.nkb, kb_ptr, stream);
+    trace_mark(stream);
+    const size_t lds = (size_t(2) * Cfg::BK * plan.nb_count + 1 + plan.nb_count) * 4;
+    fc_bucket_kernel<<<plan.nkb, BUCKET_THREADS, lds, stream>>>(static_cast<const uint16_t *>(vals), idx, p.k,
+                                                                uint32_t(p.cin), plan.nb_count, plan.nkb, kb_ptr, packed,
+                                                                tile_ptr);
+    trace_mark(stream);
+    return launch_gemm<Cfg, true>(p, plan, dY, nullptr, partial, dW, stream, packed, tile_ptr);
 }
 
 bool fc_dense_mask_native(const FcProblem &p) { return fc_dense_supported(p) && p.cin % 8 == 0; }

@@ -16,13 +16,23 @@ struct FcDensePlan {
     bool narrow;                               // the 128-row tile configuration (layers with few output channels)
     int64_t ntok_pad;                          // rows of the dense operand: the tokens rounded up to whole token blocks
     size_t dense_bytes, partial_bytes;
-    size_t total() const { return dense_bytes + partial_bytes; }
+    // the in-LDS form keeps no dense operand: the pairs regrouped by tile (a word each), the table of tile starts
+    // and the table of token-block starts take its place at the front of the workspace
+    bool fused;
+    size_t packed_bytes, table_bytes, kbptr_bytes;
+    size_t operand_bytes() const { return fused ? packed_bytes + table_bytes + kbptr_bytes : dense_bytes; }
+    size_t total() const { return operand_bytes() + partial_bytes; }
 };
 
 // bf16 fully-connected weight gradient: recover R(a^) densely, then a direct-to-LDS GEMM (wgrad_fc_dense.hip)
 bool fc_dense_supported(const FcProblem &p);
-FcDensePlan fc_dense_plan(const FcProblem &p);
+FcDensePlan fc_dense_plan(const FcProblem &p, bool fused = false);
 dropit_status fc_dense_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
+                           const void *dY, float *dW, char *ws, hipStream_t stream);
+
+// the same product with the recover step inside it: the zero-filled tensor exists only as LDS tiles (plan.fused)
+bool fc_fused_supported(const FcProblem &p);
+dropit_status fc_fused_run(const FcProblem &p, const FcDensePlan &plan, const void *vals, const int32_t *idx,
                            const void *dY, float *dW, char *ws, hipStream_t stream);
 
 // the same from the row form of the cache (col = position in the row, rowptr = pairs before each row)

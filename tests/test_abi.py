@@ -22,7 +22,7 @@ def declared_symbols():
 def test_header_declares_the_expected_entry_points():
     assert declared_symbols() == sorted([
         "dropit_status_string", "dropit_keep_count", "dropit_compress_workspace_bytes", "dropit_compress",
-        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode",
+        "dropit_weight_grad_workspace_bytes", "dropit_weight_grad", "dropit_trace_events", "dropit_set_select_mode", "dropit_set_fc_recover",
         "dropit_weight_grad_path",
         "dropit_weight_grad_nhwc_path", "dropit_weight_grad_nhwc_workspace_bytes", "dropit_weight_grad_nhwc",
         "dropit_compress_random_workspace_bytes", "dropit_compress_random",
@@ -216,6 +216,26 @@ def test_select_mode_switch_validates():
     assert L.dropit_set_select_mode(3) == binding.OK
     assert L.dropit_set_select_mode(4) == binding.EINVAL
     assert L.dropit_set_select_mode(-1) == binding.EINVAL
+    assert L.dropit_set_select_mode(0) == binding.OK                  # leave the default for whatever runs next
+
+
+def test_fc_recover_switch_validates_and_changes_the_answers():
+    L = dropit.lib()
+    shape, k, c_out = (12608, 768), 968294, 3072
+    dense_form = dropit.weight_grad_workspace_bytes(shape, torch.bfloat16, k, c_out)
+    assert dropit.weight_grad_path(shape, torch.bfloat16, k, c_out) == "fc_mfma"
+    assert L.dropit_set_fc_recover(2) == binding.EINVAL and L.dropit_set_fc_recover(-1) == binding.EINVAL
+    assert L.dropit_set_fc_recover(1) == binding.OK
+    try:
+        assert dropit.weight_grad_path(shape, torch.bfloat16, k, c_out) == "fc_fused"
+        in_lds = dropit.weight_grad_workspace_bytes(shape, torch.bfloat16, k, c_out)
+        # the dense operand (2 bytes per element of x) gives way to a word per pair and two small tables
+        assert dense_form - in_lds > 12608 * 768 * 2 - 4 * k - (1 << 16)
+        assert dropit.weight_grad_path(shape, torch.bfloat16, k, 128) == "fc_mfma"      # not covered: unchanged
+        assert dropit.weight_grad_path(shape, torch.float32, k, c_out) == "fma"
+    finally:
+        assert L.dropit_set_fc_recover(0) == binding.OK
+    assert dropit.weight_grad_path(shape, torch.bfloat16, k, c_out) == "fc_mfma"
 
 
 def test_workspace_queries():

@@ -377,6 +377,138 @@ def test_conv_window_larger_than_input_is_rejected():
     assert e.value.status == 1
 
 
+@pytest.fixture
+def recover_in_lds():
+    """The FC recover step inside the product (dropit_set_fc_recover(1)) for the test, the default form after it."""
+    dropit.set_fc_recover(1)
+    try:
+        yield
+    finally:
+        dropit.set_fc_recover(0)
+
+
+def _dw_both_forms(x, dy, gamma, cout):
+    """dW of one layer by the dense-operand form and by the in-LDS form, each in a workspace of exactly its size
+    filled with NaN bits; also the two workspace sizes."""
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, gamma)
+    out, need = {}, {}
+    for form in (0, 1):
+        dropit.set_fc_recover(form)
+        try:
+            assert dropit.weight_grad_path(x.shape, xd.dtype, vals.numel(), cout) == ("fc_fused" if form else "fc_mfma")
+            need[form] = dropit.weight_grad_workspace_bytes(x.shape, xd.dtype, vals.numel(), cout)
+            ws, check_ws = _guarded(need[form], torch.uint8, pattern=0xFF)
+            dwf, check_dw = _guarded(cout * x.shape[-1] * 4, torch.float32, pattern=0xFF)
+            out[form] = dropit.weight_grad(vals, idx, x.shape, dyd, cout, dW=dwf.view(cout, x.shape[-1]), workspace=ws)
+            torch.cuda.synchronize()
+            check_ws()
+            check_dw()
+        finally:
+            dropit.set_fc_recover(0)
+    return out, need
+
+
+@pytest.mark.parametrize("ntok,cin,cout,gamma", [
+    (200, 264, 512, 0.9),      # ragged token block, ragged column tile, two row tiles, a single K-slice
+    (33, 520, 264, 0.9),       # two token blocks only: fewer tiles than the pipeline is deep
+    (1000, 520, 264, 0.9),
+    (4100, 768, 768, 0.8),     # ~1640 pairs per tile: every tile takes the path for more words than the staging slot holds
+    (2500, 768, 1536, 0.0),    # nothing dropped: 8192 words per tile
+    (3000, 1000, 520, 0.5),
+    (700, 2048, 256, 0.97),    # eight column blocks per token block
+    (9000, 512, 512, 0.9),     # several K-slices per tile
+    (6000, 300, 136, 0.9),     # just over 128 output channels: the smallest layer the form covers
+    (3000, 777, 200, 0.9),     # c_in not a multiple of 8
+    (5000, 768, 768, 0.999),   # 24 pairs per token block: most tiles hold a handful of pairs, some none
+])
+def test_fc_recover_inside_the_product_is_bit_identical(ntok, cin, cout, gamma):
+    """Sec. 3.2: R(a^) built tile by tile in LDS gives the dW of the dense-operand form bit for bit, in a smaller
+    workspace; and the dense-operand form is the one compared with the oracle element by element above."""
+    print("wgrad fc in-LDS recover", ntok, cin, cout, gamma, flush=True)
+    x = activation((ntok, cin), "normal", 700 + ntok, "bf16")
+    dy = gradient((ntok, cout), 0.02, 800 + ntok, "bf16")
+    out, need = _dw_both_forms(x, dy, gamma, cout)
+    assert torch.equal(out[0], out[1])
+    if gamma >= 0.5:
+        assert need[1] < need[0]
+    ref = oracle.dw_fc(ref_xhat(x, gamma), oracle.widen(dy))
+    assert_close(to_host(out[1]).astype(np.float64), ref, TOL["bf16"])
+
+
+@pytest.mark.parametrize("layout", ["one_column_block", "tail_rows", "stripes", "single_row"])
+def test_fc_recover_inside_the_product_uneven_density(layout):
+    """Kept elements that bunch up: tiles of thousands of words beside empty ones, empty token blocks."""
+    print("wgrad fc in-LDS recover density", layout, flush=True)
+    ntok, cin, cout, gamma = 3000, 768, 264, 0.9
+    rng = np.random.default_rng(17)
+    xf = rng.standard_normal((ntok, cin), dtype=np.float32)
+    rows = np.arange(ntok)
+    if layout == "one_column_block":
+        xf[:, :256] *= 1e-3
+        xf[:, 512:] *= 1e-3
+    elif layout == "tail_rows":
+        xf[rows < int(0.8 * ntok)] *= 1e-3
+    elif layout == "stripes":
+        xf[(rows // 100) % 2 == 0] *= 1e-3
+    else:
+        xf *= 1e-3
+        xf[1234] = rng.standard_normal(cin, dtype=np.float32) + 3.0
+    x = f32_to_bf16_bits(xf)
+    dy = gradient((ntok, cout), 0.02, 501, "bf16")
+    out, _ = _dw_both_forms(x, dy, gamma, cout)
+    assert torch.equal(out[0], out[1])
+    ref = oracle.dw_fc(ref_xhat(x, gamma), oracle.widen(dy))
+    assert_close(to_host(out[1]).astype(np.float64), ref, TOL["bf16"])
+
+
+def test_fc_recover_form_falls_back_where_it_does_not_exist(recover_in_lds):
+    """Layers the in-LDS form does not cover keep their path; the setting is per call, not sticky state in the result."""
+    bf16 = torch.bfloat16
+    assert dropit.weight_grad_path((4000, 768), bf16, 1000, 128) == "fc_mfma"          # the 128-row tile
+    assert dropit.weight_grad_path((256, 64), bf16, 100, 128) == "fc_small"
+    assert dropit.weight_grad_path((4000, 768), torch.float32, 1000, 256) == "fma"
+    assert dropit.weight_grad_path((4000, 768), bf16, 0, 256) == "fc_mfma"             # k == 0: dW = 0 either way
+    assert dropit.weight_grad_path((4, 64, 28, 28), bf16, 1000, 64, conv=CONV3) == "conv_bands"
+    assert dropit.weight_grad_path((4000, 768), bf16, 1000, 256) == "fc_fused"
+    with pytest.raises(dropit.DropitError):
+        dropit.set_fc_recover(2)
+    # a narrow layer still computes, through the dense operand
+    x = activation((700, 520), "normal", 5, "bf16")
+    dy = gradient((700, 64), 0.02, 6, "bf16")
+    got, _, _ = gpu_dw(x, dy, 0.9, 64)
+    assert_close(got, oracle.dw_fc(ref_xhat(x, 0.9), oracle.widen(dy)), TOL["bf16"])
+
+
+def test_fc_recover_inside_the_product_in_a_hip_graph(recover_in_lds):
+    print("wgrad fc in-LDS recover graph", flush=True)
+    x = activation((3000, 520), "normal", 31, "bf16")
+    dy = gradient((3000, 264), 0.02, 32, "bf16")
+    xd, dyd = to_device(x), to_device(dy)
+    vals, idx = dropit.compress(xd, 0.9)
+    assert dropit.weight_grad_path(x.shape, xd.dtype, vals.numel(), 264) == "fc_fused"
+    ws = torch.empty(dropit.weight_grad_workspace_bytes(x.shape, xd.dtype, vals.numel(), 264), dtype=torch.uint8, device="cuda:0")
+    dW = dropit.weight_grad(vals, idx, x.shape, dyd, 264, workspace=ws)        # warm-up outside capture
+    torch.cuda.synchronize()
+    want = to_host(dW).copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dropit.weight_grad(vals, idx, x.shape, dyd, 264, dW=dW, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        dropit.weight_grad(vals, idx, x.shape, dyd, 264, dW=dW, workspace=ws)
+    for replay in range(3):
+        dW.zero_()
+        ws.fill_(replay * 41 + 1)                                         # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert to_host(dW).tobytes() == want.tobytes(), replay
+
+
 def report_elementwise(name, got, ref, cond):
     """Printed, not gated (the gate is the max-normalised error): the worst element-wise error relative to
     the sum of the magnitudes of the element's terms, sum_n |dY[n][j] * R(a^)[n][c]|, which is what bounds
