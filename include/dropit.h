@@ -294,7 +294,11 @@ dropit_status dropit_weight_grad_mask(const void *vals, const uint32_t *mask, co
  *                with other persistent kernels) the kernel redoes the selection serially in its
  *                last workgroup, so the result is complete either way, only late.
  *   1            the same select as separate ordinary kernels (no grid barriers, no memset
- *                nodes): for callers that must not depend on co-residency at all.
+ *                nodes): for callers that must not depend on co-residency at all.  Use it when
+ *                other kernels that hold compute units or LDS for long (another select on a
+ *                second stream, a persistent kernel) run on the device at the same time: mode 0
+ *                then waits out its patience (milliseconds) and redoes the selection serially,
+ *                correct but orders of magnitude later than its usual 25 - 50 us.
  *   2            mode 0's kernel through a cooperative launch: the runtime then guarantees
  *                co-residency, at the price of tens of microseconds of queue switching per
  *                call; cannot be recorded into a HIP graph (falls back to mode 0's launch).

@@ -432,6 +432,9 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     char *stg = lds + C::LDS_BYTES;                    // [FUSE_SLOTS][FUSE_STAGE_WORDS] words behind the stages
     uint32_t dma_start = 0;
     int dma_slot = 0;
+    uint32_t pk_off[FUSE_STAGE_WORDS / C::NTHREADS];   // byte offset of this lane's word in staging load i
+#pragma unroll
+    for (int i = 0; i < FUSE_STAGE_WORDS / C::NTHREADS; ++i) pk_off[i] = uint32_t(i * C::NTHREADS + wave * 64 + lane) * 4u;
     // load number q (0 .. LOADS-1) of a step: the A loads first, then the B loads
     auto issue_load = [&](auto q_, int stage, int kb) {
         constexpr int q = decltype(q_)::value;
@@ -442,10 +445,11 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
                                              DROPIT_LPTR(sa + q * 1024), 16, 0, 0);
         } else if constexpr (FUSED) {
             // staging load i of the step: words [i * 512 + wave * 64, + 64) of the tile, one per lane (a direct
-            // 4-byte load lands at the wave-uniform LDS base + lane * 4); clamped, unconditional
+            // 4-byte load lands at the wave-uniform LDS base + lane * 4); unconditional: past the tile's words it
+            // brings the next tiles', which are not placed
             constexpr int i = q - C::A_LOADS;
-            const uint32_t w = uint32_t(i * C::NTHREADS + wave * 64 + lane);
-            __builtin_amdgcn_global_load_lds(DROPIT_GPTR(packed + min(dma_start + w, kpairs - 1)),
+            const char *src = reinterpret_cast<const char *>(packed + dma_start);     // wavefront-uniform; the words are
+            __builtin_amdgcn_global_load_lds(DROPIT_GPTR(src + pk_off[i]),            // followed by a slot's worth of slack
                                              DROPIT_LPTR(stg + dma_slot * (FUSE_STAGE_WORDS * 4) + (i * C::NTHREADS + wave * 64) * 4),
                                              4, 0, 0);
         } else {
@@ -461,10 +465,11 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     // ---- FUSED: the B tile of a step is zero-filled and the staged words placed, by hand-written LDS accesses
     // (the compiler would put vmcnt(0) in front of LDS accesses it knows about, see below) ----
     const uint32_t lds_base0 = uint32_t(size_t(DROPIT_LPTR(lds)));
+    u32x4 zero4 = {0u, 0u, 0u, 0u};                    // kept in registers for the whole loop
+    if constexpr (FUSED) asm volatile("" : "+v"(zero4));
     auto zero_b_half = [&](int stage, int half) {      // 16 KB: 2 x 16 bytes per thread
         const uint32_t a = lds_base0 + stage * C::STAGE_BYTES + C::A_BYTES + half * (C::NTHREADS * 16) + threadIdx.x * 16;
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(z) : "memory");
+        asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(zero4) : "memory");
     };
     auto zero_b = [&](int stage) {
         zero_b_half(stage, 0);
@@ -477,11 +482,11 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         for (int i = 0; i < FUSE_STAGE_WORDS / C::NTHREADS; ++i)
             asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(staged_w[i]) : "v"(a), "n"(i * C::NTHREADS * 4) : "memory");
     };
-    // a word is  value << 16 | element offset in the tile's LDS rows  (row * 256 + swizzled column: 13 bits, the rest of the low half is zero)
+    // a word is  value << 16 | byte offset in the tile's LDS rows  (row * 512 + 2 * swizzled column: 14 bits); the
+    // store takes the value from the upper half of the register
     auto place_word = [&](uint32_t w, uint32_t b_base) {
-        const uint32_t a = b_base + ((w & 0x1fffu) << 1);
-        const uint32_t v = w >> 16;
-        asm volatile("ds_write_b16 %0, %1" ::"v"(a), "v"(v) : "memory");
+        const uint32_t a = b_base + (w & 0x3fffu);
+        asm volatile("ds_write_b16_d16_hi %0, %1" ::"v"(a), "v"(w) : "memory");
     };
     // staged word i of this thread, or -- past the tile's count -- a store to a spare location of the thread's own
     const uint32_t spare = lds_base0 + C::LDS_BYTES + FUSE_SLOTS * FUSE_STAGE_WORDS * 4 + threadIdx.x * 4;
@@ -490,9 +495,8 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         const uint32_t b_base = lds_base0 + stage * C::STAGE_BYTES + C::A_BYTES;
         asm volatile("" : "+v"(staged_w[i]));
         const bool valid = uint32_t(i * C::NTHREADS) + threadIdx.x < count;
-        const uint32_t a = valid ? b_base + ((staged_w[i] & 0x1fffu) << 1) : spare;
-        const uint32_t v = staged_w[i] >> 16;
-        asm volatile("ds_write_b16 %0, %1" ::"v"(a), "v"(v) : "memory");
+        const uint32_t a = valid ? b_base + (staged_w[i] & 0x3fffu) : spare;
+        asm volatile("ds_write_b16_d16_hi %0, %1" ::"v"(a), "v"(staged_w[i]) : "memory");
     };
     auto place_staged = [&](int stage, uint32_t count) {          // after the lgkm wait that follows read_staged
         static_for<0, FUSE_STAGE_WORDS / C::NTHREADS>([&](auto i_) { place_staged_one(i_, stage, count); });
@@ -558,13 +562,16 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     static_assert(STEP_LOADS <= KK * NM, "at most one global load rides behind each MFMA");
     // FUSED, per step s (fz_*: set at the top of the step): sub-step 0 zero-fills the B rows of tile s + 3 and reads
     // this thread's staged words of tile s + 2; sub-step 1 places them.
-    int fz_zero_stage = 0, fz_place_stage = 0, fz_place_slot = 0, fz_decode_t = 0;
-    uint32_t fz_place_start = 0, fz_place_count = 0, fz_raw_lo = 0, fz_raw_hi = 0, fz_next_start = 0, fz_next_count = 0;
+    int fz_zero_stage = 0, fz_place_stage = 0, fz_place_t = 0, fz_decode_t = 0;
+    uint32_t fz_place_count = 0, fz_raw_lo = 0, fz_raw_hi = 0, fz_next_start = 0, fz_next_count = 0;
     const int kb_begin_f = kb_begin, steps_f = steps;
+    // table entry of the slice's tile t: fz_table[t * nb_count] (first word) and the entry after it (end); the table
+    // is followed by six token blocks' worth of slack, so entries of tiles past the slice can be fetched (and ignored)
+    const uint32_t *fz_table = FUSED ? tile_ptr + (int64_t(kb_begin) * nb_count + nb) : nullptr;
     auto tile_decode = [&](int t, uint32_t raw_lo, uint32_t raw_hi, uint32_t &start, uint32_t &count) {
         start = min(raw_lo, kpairs);
         const uint32_t end = min(raw_hi, kpairs);
-        count = (t < steps_f && end > start) ? end - start : 0u;     // a malformed table places nothing
+        count = t < steps_f ? min(end - start, uint32_t(BK * BN)) : 0u;   // (a tile has at most BK * BN words whatever the table says)
     };
     (void)kb_begin_f; (void)tile_decode;
     auto substep = [&](auto kk_, auto next_kk_, auto read_next_, uint32_t next_base, int load_stage, int load_kb) {
@@ -573,7 +580,8 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         lgkm_wait<0>();                                // the reads of this set were issued one sub-step ago
         if constexpr (FUSED && kk == 1) {
             tile_decode(fz_decode_t, fz_raw_lo, fz_raw_hi, fz_next_start, fz_next_count);   // (fetched at the top of the step)
-            if (fz_place_count > uint32_t(FUSE_STAGE_WORDS)) place_overflow(fz_place_stage, fz_place_start, fz_place_count);
+            if (fz_place_count > uint32_t(FUSE_STAGE_WORDS))
+                place_overflow(fz_place_stage, min(fz_table[int64_t(fz_place_t) * nb_count], kpairs), fz_place_count);
         }
         bf16x8 af[C::FM], bfv[C::FN];
 #pragma unroll
@@ -597,7 +605,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             // reads (sub-step 0) and the placement (sub-step 1)
             if constexpr (FUSED && kk == 0) {
                 if constexpr (m == NM / 2 || m == NM / 2 + 1) zero_b_half(fz_zero_stage, m - NM / 2);
-                if constexpr (m == NM / 2 + 2) read_staged(fz_place_slot);
+                if constexpr (m == NM / 2 + 2) read_staged(fz_place_stage);      // (tile t is staged in slot t % 4 = its stage)
             }
             if constexpr (FUSED && kk == 1 && m >= NM / 2 && m < NM / 2 + FUSE_STAGE_WORDS / C::NTHREADS)
                 place_staged_one(std::integral_constant<int, m - NM / 2>{}, fz_place_stage, fz_place_count);
@@ -627,25 +635,23 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         constexpr int AHEAD = C::EARLY ? 1 : 0;        // how many steps before its own a stage must be complete
         static_assert(D >= 1 + AHEAD, "stages: one being multiplied, one per step of load latency, one more if read early");
         const int kb_last = kb_end - 1;
-        // FUSED: where tile t of the slice starts among the words, and how many it has (t past the slice: none)
-        // (the table entries are wavefront-uniform: scalar loads, fetched a step before they are decoded)
-        auto tile_fetch = [&](int t, uint32_t &raw_lo, uint32_t &raw_hi) {
-            const int64_t b = int64_t(kb_begin + min(t, steps - 1)) * nb_count + nb;
-            raw_lo = tile_ptr[b];
-            raw_hi = tile_ptr[b + 1];
-        };
-        uint32_t r2_start = 0, r2_count = 0, r3_start = 0, r3_count = 0, r4_start = 0, r4_count = 0, r5_start = 0, r5_count = 0;
+        // FUSED: counts of the tiles s + 2 .. s + 4 (placed two steps after they are staged) and where tile s + 4 starts
+        uint32_t c2 = 0, c3 = 0, c4 = 0, st4 = 0;
+        const uint32_t *fz_tp = fz_table;
         if constexpr (FUSED) {
             // before the first step: tiles 0 .. 3 staged, stages 0 .. 2 zero-filled, tiles 0 and 1 placed -- the table
             // entries, the A tiles of the first three steps and the staged words are all requested before the first wait
-            uint32_t lo[6], hi[6], st[6], ct[6];
+            uint32_t lo[5], hi[5], st[5], ct[5];
 #pragma unroll
-            for (int t = 0; t < 6; ++t) tile_fetch(t, lo[t], hi[t]);
+            for (int t = 0; t < 5; ++t) {
+                lo[t] = fz_table[int64_t(t) * nb_count];
+                hi[t] = fz_table[int64_t(t) * nb_count + 1];
+            }
 #pragma unroll
             for (int d = 0; d < D; ++d)
                 static_for<0, C::A_LOADS>([&](auto q_) { issue_load(q_, d, min(kb_begin + d, kb_last)); });
 #pragma unroll
-            for (int t = 0; t < 6; ++t) tile_decode(t, lo[t], hi[t], st[t], ct[t]);
+            for (int t = 0; t < 5; ++t) tile_decode(t, lo[t], hi[t], st[t], ct[t]);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 dma_start = st[t];
@@ -666,10 +672,11 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
                 if (ct[t] > uint32_t(FUSE_STAGE_WORDS)) place_overflow(t, st[t], ct[t]);
             }
             lgkm_wait<0>();
-            r2_start = st[2]; r2_count = ct[2];
-            r3_start = st[3]; r3_count = ct[3];
-            r4_start = st[4]; r4_count = ct[4];
-            r5_start = st[5]; r5_count = ct[5];
+            c2 = ct[2];
+            c3 = ct[3];
+            c4 = ct[4];
+            st4 = st[4];
+            fz_tp = fz_table + int64_t(4) * nb_count;
         } else {
 #pragma unroll
             for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
@@ -683,23 +690,23 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             });
         }
         int stage = 0, fill = D;                       // s % STAGES and (s + D) % STAGES
-        int slot2 = 2 % FUSE_SLOTS, slot4 = 4 % FUSE_SLOTS;        // staging slots of tiles s + 2 and s + 4
-        static_assert(FUSE_SLOTS == 4, "the prologue stages tiles 0 .. 3 at once");
+        static_assert(FUSE_SLOTS == 4 && C::STAGES == 4, "tile t is staged in slot t % 4, which is also its stage");
         for (int s = 0; s < steps; ++s) {
             const int next = stage + 1 == C::STAGES ? 0 : stage + 1;
             wait_loads<(D - 1 - AHEAD) * STEP_LOADS>();
             if constexpr (FUSED) lgkm_wait<0>();           // this wavefront's zero fill and placed words are in LDS
             workgroup_barrier();
             if constexpr (FUSED) {
-                tile_fetch(s + 6, fz_raw_lo, fz_raw_hi);
-                fz_decode_t = s + 6;
+                fz_tp += nb_count;                         // tile s + 5: decoded during the step, staged in the next one
+                fz_raw_lo = fz_tp[0];
+                fz_raw_hi = fz_tp[1];
+                fz_decode_t = s + 5;
                 fz_zero_stage = (stage + 3) % C::STAGES;
                 fz_place_stage = (stage + 2) % C::STAGES;
-                fz_place_slot = slot2;
-                fz_place_start = r2_start;
-                fz_place_count = r2_count;
-                dma_start = r4_start;
-                dma_slot = slot4;
+                fz_place_t = s + 2;
+                fz_place_count = c2;
+                dma_start = st4;
+                dma_slot = stage;
             }
             const uint32_t cur_base = lds_base + stage * C::STAGE_BYTES;
             const uint32_t next_base = lds_base + next * C::STAGE_BYTES;
@@ -719,12 +726,10 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             stage = next;
             fill = fill + 1 == C::STAGES ? 0 : fill + 1;
             if constexpr (FUSED) {
-                slot2 = slot2 + 1 == FUSE_SLOTS ? 0 : slot2 + 1;
-                slot4 = slot4 + 1 == FUSE_SLOTS ? 0 : slot4 + 1;
-                r2_start = r3_start; r2_count = r3_count;
-                r3_start = r4_start; r3_count = r4_count;
-                r4_start = r5_start; r4_count = r5_count;
-                r5_start = fz_next_start; r5_count = fz_next_count;
+                c2 = c3;
+                c3 = c4;
+                c4 = fz_next_count;
+                st4 = fz_next_start;
             }
         }
         wait_loads<0>();                               // nothing may still be writing LDS
@@ -941,7 +946,7 @@ fc_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ 
             const int b = int(min(col >> 8, uint32_t(nb_count - 1)));
             const int key = int(r) * nb_count + b;
             const uint32_t at = min(max(total[b] + run_out[key] + (j - run_in[key]), lo), hi - 1);   // (inside the block whatever idx holds)
-            packed[at] = val[u] << 16 | r << 8 | ((col & 255u) ^ ((r & 3u) << 5));
+            packed[at] = val[u] << 16 | (r << 8 | ((col & 255u) ^ ((r & 3u) << 5))) << 1;
         }
     }
 }
@@ -1024,8 +1029,10 @@ FcDensePlan fc_dense_plan(const FcProblem &p, bool fused)
     plan.ntok_pad = int64_t(plan.nkb) * Cfg::BK;
     plan.dense_bytes = round_up(size_t(plan.ntok_pad) * plan.pitch * 2, 256);
     plan.fused = fused;
-    plan.packed_bytes = round_up(size_t(std::max<int64_t>(p.k, 1)) * 4, 256);
-    plan.table_bytes = round_up((size_t(plan.nkb) * plan.nb_count + 1) * 4, 256);
+    // (the product fetches a staging slot's worth of words from any tile start, and table entries up to six token
+    // blocks past its slice: both arrays carry that much slack)
+    plan.packed_bytes = round_up((size_t(std::max<int64_t>(p.k, 1)) + FUSE_STAGE_WORDS) * 4, 256);
+    plan.table_bytes = round_up(((size_t(plan.nkb) + 6) * plan.nb_count + 1) * 4, 256);
     plan.kbptr_bytes = round_up((size_t(plan.nkb) + 1) * 4, 256);
     return plan;
 }
