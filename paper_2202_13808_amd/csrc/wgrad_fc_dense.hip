@@ -347,11 +347,13 @@ __device__ inline void static_for(F &&f)
 
 // FUSED: the recover step R(a^) happens inside the product.  The B operand is not a dense matrix in memory:
 // a prep kernel (fc_bucket_kernel) has put the pairs of every (token block, column block) tile next to each
-// other as words  value << 16 | place in the tile's LDS rows;  the workgroup fetches a tile's
-// words straight into an LDS staging area four steps ahead (direct loads, like the A tiles), zero-fills the
-// tile's LDS rows three steps ahead, and places the words (one 16-bit LDS store each, at the same swizzled
-// addresses a direct load would have filled) two steps ahead -- each behind a workgroup barrier of its own,
-// and all of it tucked in front of the MFMAs of a sub-step.  The zero-filled tensor exists only as these rows.
+// other as words  value << 16 | byte offset in the tile's LDS rows.  At step s the workgroup
+//   - fetches the words of tile s + 4 straight into an LDS staging slot (direct loads, counted with the A loads),
+//   - zero-fills the LDS rows of tile s + 3,
+//   - places the words of tile s + 2 (one 16-bit LDS store each, at the swizzled address a direct load of the
+//     dense operand would have filled),
+// each a workgroup barrier of the main loop behind the one before it, and all of it issued behind the second
+// half of a sub-step's MFMAs.  The zero-filled tensor exists only as these rows.
 constexpr int FUSE_STAGE_WORDS = 1024;            // words of a tile staged per step (more than that: a slow path)
 constexpr int FUSE_SLOTS = 4;                     // staging slots: tile t uses slot t % 4 (tiles s + 2 .. s + 4 are in flight at step s)
 constexpr int FUSE_LDS_BYTES = FUSE_SLOTS * FUSE_STAGE_WORDS * 4 + 512 * 4;     // + a spare word per thread
@@ -362,7 +364,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
                 int pitch, int nb_count, int mb_count, int nkb, int splits,
                 float *__restrict__ out /* dW or partials [splits][M][N] */,
                 const uint32_t *__restrict__ packed /* FUSED: the tiles' words */,
-                const uint32_t *__restrict__ tile_ptr /* FUSED: [nkb * nb_count + 1] first word of each tile */,
+                const uint32_t *__restrict__ tile_ptr /* FUSED: [(nkb + 6) * nb_count + 1] first word of each tile, then slack */,
                 uint32_t kpairs)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK;
