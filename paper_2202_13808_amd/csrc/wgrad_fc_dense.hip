@@ -511,6 +511,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             place_word(word, b_base);
         }
     };
+    // (the FUSED instantiation alone uses these)
     (void)zero_b; (void)read_staged; (void)place_staged; (void)place_overflow; (void)stg; (void)place_staged_one;
 
     // ---- LDS -> MFMA fragments -----------------------------------------------------
@@ -566,7 +567,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
     // this thread's staged words of tile s + 2; sub-step 1 places them.
     int fz_zero_stage = 0, fz_place_stage = 0, fz_place_t = 0, fz_decode_t = 0;
     uint32_t fz_place_count = 0, fz_raw_lo = 0, fz_raw_hi = 0, fz_next_start = 0, fz_next_count = 0;
-    const int kb_begin_f = kb_begin, steps_f = steps;
+    const int steps_f = steps;
     // table entry of the slice's tile t: fz_table[t * nb_count] (first word) and the entry after it (end); the table
     // is followed by six token blocks' worth of slack, so entries of tiles past the slice can be fetched (and ignored)
     const uint32_t *fz_table = FUSED ? tile_ptr + (int64_t(kb_begin) * nb_count + nb) : nullptr;
@@ -575,7 +576,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         const uint32_t end = min(raw_hi, kpairs);
         count = t < steps_f ? min(end - start, uint32_t(BK * BN)) : 0u;   // (a tile has at most BK * BN words whatever the table says)
     };
-    (void)kb_begin_f; (void)tile_decode;
+    (void)tile_decode;                                 // (used by the FUSED instantiation only)
     auto substep = [&](auto kk_, auto next_kk_, auto read_next_, uint32_t next_base, int load_stage, int load_kb) {
         constexpr int kk = decltype(kk_)::value, set = kk % 2;
         constexpr bool read_next = decltype(read_next_)::value;
