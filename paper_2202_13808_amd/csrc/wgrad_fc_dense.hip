@@ -653,19 +653,20 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
         // 16-token sub-step (twice the barriers); the second sub-step's reads, or the loads, inside or at either
         // end of the multiplying phase (anything a multiplying wavefront issues besides MFMAs delays them); no wait
         // for the reads before the barrier; one barrier per block with the groups half a block apart.
-        static_assert(!FUSED && C::STAGES == 4 && BK == 32 && C::NWAVES == 8 && C::LOADS == 4, "laid out for the wide tile");
+        static_assert(!FUSED && C::STAGES >= 4 && BK == 32 && C::NWAVES == 8 && C::LOADS == 4, "laid out for the wide tile");
+        constexpr int D = C::STAGES - 1;               // blocks a load runs ahead of the block being read
         if (steps > 0) {
             const int kb_last = kb_end - 1;
             const bool late = wave >= C::NWAVES / 2;
 #pragma unroll
-            for (int d = 0; d < 3; ++d) issue_loads(d, min(kb_begin + d, kb_last));
+            for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
             wait_loads<0>();
             workgroup_barrier();
             if (late) workgroup_barrier();
-            int stage = 0, fill = 3;
+            int stage = 0, fill = D;
             for (int s = 0; s < steps; ++s) {
                 const uint32_t cur_base = lds_base + stage * C::STAGE_BYTES;
-                const int load_kb = min(kb_begin + s + 3, kb_last);
+                const int load_kb = min(kb_begin + s + D, kb_last);
                 // M: the fragments of both sub-steps of the block, this wavefront's four loads between them (a load
                 // takes tens of cycles to issue: behind the reads that time is covered by their latency, in front
                 // of them or next to the MFMAs it is not)
@@ -676,7 +677,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
                     issue_load(std::integral_constant<int, 2 * kk + 1>{}, fill, load_kb);
                 });
                 lgkm_wait<0>();
-                wait_loads<2 * C::LOADS>();
+                wait_loads<(D - 1) * C::LOADS>();
                 __builtin_amdgcn_sched_barrier(0);
                 workgroup_barrier();
                 __builtin_amdgcn_sched_barrier(0);
@@ -769,7 +770,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             });
         }
         int stage = 0, fill = D;                       // s % STAGES and (s + D) % STAGES
-        static_assert(FUSE_SLOTS == 4 && C::STAGES == 4, "tile t is staged in slot t % 4, which is also its stage");
+        static_assert(!FUSED || (FUSE_SLOTS == 4 && C::STAGES == 4), "tile t is staged in slot t % 4, which is also its stage");
         for (int s = 0; s < steps; ++s) {
             const int next = stage + 1 == C::STAGES ? 0 : stage + 1;
             wait_loads<(D - 1 - AHEAD) * STEP_LOADS>();
@@ -1040,9 +1041,10 @@ fc_bucket_kernel(const uint16_t *__restrict__ vals, const int32_t *__restrict__ 
 #define DROPIT_GEMM_CFG_NARROW 128, 256, 32, 2, 4, 4, 2, 1
 #endif
 using Cfg = GemmCfg<DROPIT_GEMM_CFG>;
+using CfgFused = GemmCfg<256, 256, 32, 4, 2, 4, 2, 1>;          // the in-LDS recover form is laid out for four stages
 using CfgNarrow = GemmCfg<DROPIT_GEMM_CFG_NARROW>;
 static_assert(Cfg::BK == CfgNarrow::BK && Cfg::BN == CfgNarrow::BN, "the recovered operand is laid out once for both");
-static_assert(Cfg::BK == 32 && Cfg::BN == 256, "the words of the in-LDS form address a 32 x 256 tile");
+static_assert(Cfg::BM == CfgFused::BM && Cfg::BN == CfgFused::BN && Cfg::BK == CfgFused::BK, "one plan serves both forms");
 
 template <typename C>
 int tuned_splits(int tiles, int nkb)
@@ -1133,8 +1135,8 @@ static bool fc_dense_attributes()
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess &&
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg, false, true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES) == hipSuccess &&
-               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<Cfg, true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES + FUSE_LDS_BYTES) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<CfgFused, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, CfgFused::LDS_BYTES + FUSE_LDS_BYTES) == hipSuccess &&
                hipFuncSetAttribute(reinterpret_cast<const void *>(fc_dense_kernel<CfgNarrow, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, CfgNarrow::LDS_BYTES) == hipSuccess;
     });
@@ -1228,7 +1230,7 @@ dropit_status fc_fused_run(const FcProblem &p, const FcDensePlan &plan, const vo
                                                                 uint32_t(p.cin), plan.nb_count, plan.nkb, kb_ptr, packed,
                                                                 tile_ptr);
     trace_mark(stream);
-    return launch_gemm<Cfg, true>(p, plan, dY, nullptr, partial, dW, stream, packed, tile_ptr);
+    return launch_gemm<CfgFused, true>(p, plan, dY, nullptr, partial, dW, stream, packed, tile_ptr);
 }
 
 bool fc_dense_mask_native(const FcProblem &p) { return fc_dense_supported(p) && p.cin % 8 == 0; }
