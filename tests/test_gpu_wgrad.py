@@ -88,6 +88,8 @@ def test_fc_small_layers_take_one_launch(dtype, ntok, cin, cout, gamma):
     (20000, 200, 64, 0.9),    # the whole result is one 128-row tile: 31 K-slices, added by the many-slice kernel
     (70000, 64, 8, 0.8),      # ... 109 slices of a nearly empty tile
     (6000, 300, 136, 0.9),    # just over 128 output channels: the wide tile, two column tiles
+    (20, 1024, 264, 0.9),     # the wide tile with a single (partial) token block: the pipeline's prologue is the whole loop
+    (70, 520, 392, 0.5),      # ... three token blocks, as many as are loaded ahead
 ])
 def test_fc_bf16_tile_edges(ntok, cin, cout, gamma):
     print("wgrad fc edges", ntok, cin, cout, gamma, flush=True)
@@ -412,6 +414,7 @@ def _dw_both_forms(x, dy, gamma, cout):
 @pytest.mark.parametrize("ntok,cin,cout,gamma", [
     (200, 264, 512, 0.9),      # ragged token block, ragged column tile, two row tiles, a single K-slice
     (33, 520, 264, 0.9),       # two token blocks only: fewer tiles than the pipeline is deep
+    (20, 1024, 264, 0.9),      # a single token block
     (1000, 520, 264, 0.9),
     (4100, 768, 768, 0.8),     # ~1640 pairs per tile: every tile takes the path for more words than the staging slot holds
     (2500, 768, 1536, 0.0),    # nothing dropped: 8192 words per tile
