@@ -313,7 +313,7 @@ dropit_status dropit_set_select_mode(int mode);
  * Where the recover step R(a^) of a bf16 fully-connected layer happens (Sec. 3.2; Fig. 1: the zero-filled
  * tensor is only ever an operand of the weight gradient).  Per host thread, like the select mode.
  *   0  (default) R(a^) is written as a dense bf16 operand into the workspace and the product reads it
- *      (DROPIT_PATH_FC_MFMA).  The faster form on MI355X by 10 - 35 us per layer at the ViT shapes; the
+ *      (DROPIT_PATH_FC_MFMA).  The faster form on MI355X by 10 - 15 us per layer at the ViT shapes; the
  *      workspace holds one tensor the size of the layer's input for the duration of the call.
  *   1  R(a^) is built tile by tile in LDS inside the product and never exists in device memory
  *      (DROPIT_PATH_FC_FUSED): the workspace holds one 4-byte word per kept pair instead of the dense tensor
