@@ -660,7 +660,7 @@ fc_dense_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ xd
             const bool late = wave >= C::NWAVES / 2;
 #pragma unroll
             for (int d = 0; d < D; ++d) issue_loads(d, min(kb_begin + d, kb_last));
-            wait_loads<0>();
+            wait_loads<(D - 1) * C::LOADS>();          // block 0 is there; the loop's own waits cover the others
             workgroup_barrier();
             if (late) workgroup_barrier();
             int stage = 0, fill = D;
